@@ -1,0 +1,95 @@
+// Shared host-side declarations of the rSVD library (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "../../include/rsvd.h"
+
+struct rsvd_ctx {
+  int device;
+  int cu_count;
+  size_t lds_per_block;     // bytes of LDS one workgroup may use
+  char hip_error[256];
+};
+
+namespace rsvd {
+
+constexpr int kWave = 64;
+
+inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+inline size_t dtype_size(rsvd_dtype d) { return d == RSVD_F32 ? 4 : 8; }
+
+// Device-side diagnostics block (4 x int32), same field order as rsvd_info.
+struct DevInfo {
+  int status;
+  int jacobi_sweeps;
+  int refilled;
+  int reserved;
+};
+
+// ---------------------------------------------------------------- GEMM
+// C (M x N) = alpha * op(A) (M x K) * B (K x N) + beta * C, row-major.
+//   trans_a == 0: A is M x K (lda >= K).   trans_a != 0: A is K x M (lda >= M).
+//   trans_c != 0: the result is stored transposed (C is N x M, ldc >= M); beta must be 0.
+//   dead != NULL: for every column j with dead[j] != 0 the stored value is replaced by
+//     refill_scale * N(0,1) drawn from Philox stream `refill_stream`, element
+//     index row * refill_ld + j (used by the orthonormalisation to replace
+//     linearly dependent columns).
+struct GemmDesc {
+  int trans_a = 0;
+  int trans_c = 0;
+  int64_t M = 0, N = 0, K = 0;
+  const void *A = nullptr; int64_t lda = 0;
+  const void *B = nullptr; int64_t ldb = 0;
+  void *C = nullptr;       int64_t ldc = 0;
+  double alpha = 1.0, beta = 0.0;
+  const int *dead = nullptr;
+  uint64_t seed = 0; uint32_t refill_stream = 0; double refill_scale = 1.0; int64_t refill_ld = 0;
+  void *partial = nullptr; size_t partial_bytes = 0;   // split-K scratch
+  int force_splits = 0;                                 // 0 = heuristic
+};
+
+enum GemmKind { GEMM_F32 = 0, GEMM_F64 = 1, GEMM_F32_ACC64 = 2 };  // last: fp32 inputs, fp64 MFMA and output
+
+// Bytes of split-K scratch the heuristic would use for this shape.
+size_t gemm_partial_bytes(const rsvd_ctx *ctx, GemmKind kind, int trans_a, int64_t M, int64_t N, int64_t K);
+hipError_t gemm_launch(const rsvd_ctx *ctx, hipStream_t s, GemmKind kind, const GemmDesc &d);
+
+// ---------------------------------------------------------------- sketch
+hipError_t sketch_launch(hipStream_t s, rsvd_dtype dtype, uint64_t seed, uint32_t stream_id,
+                         int64_t rows, int64_t cols, void *out, int64_t ld);
+hipError_t philox_raw_launch(hipStream_t s, uint64_t seed, uint32_t stream_id, uint64_t first_group,
+                             int64_t n_groups, uint32_t *out);
+
+// ---------------------------------------------------------------- small dense kernels
+// Largest block order the single-workgroup Cholesky kernel can hold in LDS.
+int chol_max_block(const rsvd_ctx *ctx);
+// Upper Cholesky factor G = R^T R of the symmetric positive semi-definite fp64
+// matrix G (l x l, ld ldg; overwritten), R^-1 written in `out_dtype`, and one
+// flag per column that was found dependent (pivot <= tau * original diagonal).
+//   Rinv (l x l, ld l, out_dtype, upper triangular, zero below)
+//   R    (l x l, ld l, fp64, upper triangular, zero below) or NULL
+//   dead (l ints), info->refilled += number of flagged columns
+//   scratch: fp64 scratch of at least chol_scratch_elems(l) elements (blocked path)
+size_t chol_scratch_elems(const rsvd_ctx *ctx, int64_t l);
+hipError_t chol_inverse_launch(const rsvd_ctx *ctx, hipStream_t s, rsvd_dtype out_dtype, int64_t l,
+                               double *G, int64_t ldg, double tau, void *Rinv, double *R, int *dead,
+                               DevInfo *info, double *scratch, void *partial, size_t partial_bytes);
+// Rb = R2 * R1 for upper triangular fp64 l x l matrices (ld l).
+hipError_t triu_product_launch(hipStream_t s, int64_t l, const double *R2, const double *R1, double *Rb);
+hipError_t zero_ints_launch(hipStream_t s, int *p, int n);
+
+// ---------------------------------------------------------------- Jacobi
+// Largest order the single-workgroup LDS-resident Jacobi kernel handles.
+int jacobi_max_lds_order(const rsvd_ctx *ctx, rsvd_dtype dtype);
+size_t jacobi_scratch_bytes(const rsvd_ctx *ctx, rsvd_dtype dtype, int64_t l);
+// One-sided Jacobi SVD  M = X diag(sigma) W^T  of the l x l row-major matrix M
+// (ld l; fp64 when m_is_f64 else `dtype`).  Outputs in `dtype`, sigma descending.
+hipError_t jacobi_launch(const rsvd_ctx *ctx, hipStream_t s, rsvd_dtype dtype, int64_t l,
+                         const void *M, int m_is_f64, void *sigma, void *X, void *W,
+                         DevInfo *info, void *scratch, size_t scratch_bytes);
+
+}  // namespace rsvd

@@ -1,0 +1,343 @@
+// MFMA GEMM for the tall-skinny / short-wide products of Algorithm 1
+// (steps 2, 4 and 6: products of A, A^T and Q with n x l, m x l and l x k
+// blocks; also the Gram matrices and triangular applies of step 3).
+//
+// One template covers every product:  C = alpha * op(A) * B + beta * C  with
+//   op(A) = A   (row-major M x K)  : tiles of A are staged in LDS as [row][k]
+//   op(A) = A^T (A stored K x M)   : tiles are staged as [k][row]
+// B is always K x N row-major (the skinny operand), staged as [k][col].
+// A 256-thread workgroup (4 wavefronts arranged WGM x WGN) owns a BM x BN tile of
+// C; each wavefront owns TM x TN blocks of 16 x 16 and issues
+// v_mfma_{f32,f64}_16x16x4 on fragments read from LDS.  The K range can be split
+// over gridDim.z; partial tiles then go to a scratch buffer and a second kernel
+// adds them in a fixed order, so results do not depend on scheduling.
+//
+// Included by gemm_f32.hip, gemm_f64.hip and gemm_f32acc64.hip, one per
+// (input type, accumulator type) pair.
+#pragma once
+
+#include "common.hpp"
+#include "philox_dev.hpp"
+
+namespace rsvd {
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef double f64x4 __attribute__((ext_vector_type(4)));
+
+// 16x16x4 MFMA: lane L supplies A[L % 16][L / 16] and B[L / 16][L % 16];
+// the 4 accumulator registers of lane L hold column L % 16 and the rows given by row().
+template <typename TAcc> struct Mfma;
+template <> struct Mfma<float> {
+  typedef f32x4 vec;
+  static __device__ __forceinline__ vec run(float a, float b, vec c) {
+    return __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, c, 0, 0, 0);
+  }
+  static __device__ __forceinline__ int row(int lane, int v) { return 4 * (lane >> 4) + v; }
+};
+template <> struct Mfma<double> {
+  typedef f64x4 vec;
+  static __device__ __forceinline__ vec run(double a, double b, vec c) {
+    return __builtin_amdgcn_mfma_f64_16x16x4f64(a, b, c, 0, 0, 0);
+  }
+  static __device__ __forceinline__ int row(int lane, int v) { return 4 * v + (lane >> 4); }
+};
+
+struct GemmParams {
+  int64_t M, N, K;
+  const void *A; int64_t lda;
+  const void *B; int64_t ldb;
+  void *C; int64_t ldc;
+  void *partial;            // [splits][M][N] accumulator-typed, used when splits > 1
+  int64_t k_per_split;
+  int splits;
+  int trans_c;
+  double alpha, beta;
+  const int *dead;
+  uint64_t seed; uint32_t refill_stream; double refill_scale; int64_t refill_ld;
+};
+
+// Final store of one element of C, shared by the GEMM and the split-K reduction.
+template <typename TOut, typename TAcc, bool F32STREAM>
+__device__ __forceinline__ void store_result(const GemmParams &P, int64_t row, int64_t col, TAcc acc) {
+  TOut *C = (TOut *)P.C;
+  double v = P.alpha * (double)acc;
+  if (P.dead != nullptr && P.dead[col] != 0) {
+    v = P.refill_scale *
+        philox_normal_at<F32STREAM>((uint64_t)(row * P.refill_ld + col), P.refill_stream, P.seed);
+  }
+  if (P.trans_c) {
+    C[col * P.ldc + row] = (TOut)v;
+  } else {
+    TOut *p = C + row * P.ldc + col;
+    if (P.beta != 0.0) v += P.beta * (double)(*p);
+    *p = (TOut)v;
+  }
+}
+
+// LDS padding: k-major tiles ([k][x], lanes read 16 consecutive x for 4 consecutive k)
+// want a row stride that is not a multiple of 32 words.
+__host__ __device__ constexpr int pad_kmajor(int x) { return (x % 32 == 0) ? 16 : 0; }
+
+template <typename TIn, int ROWS, int COLS, int VEC>
+struct TileStage {
+  static constexpr int SLOTS_PER_ROW = COLS / VEC;
+  static constexpr int SLOTS = ROWS * SLOTS_PER_ROW;
+  static constexpr int ITERS = (SLOTS + 255) / 256;
+  TIn regs[ITERS][VEC];
+
+  // rows_left / cols_left: extent of valid data from the tile origin (may exceed the tile).
+  __device__ __forceinline__ void load(const TIn *__restrict__ origin, int64_t ld, int64_t rows_left,
+                                       int64_t cols_left, int tid) {
+#pragma unroll
+    for (int it = 0; it < ITERS; ++it) {
+      const int idx = tid + it * 256;
+      const int r = idx / SLOTS_PER_ROW;
+      const int c = (idx - r * SLOTS_PER_ROW) * VEC;
+      const bool ok = (ITERS * 256 == SLOTS || idx < SLOTS) && r < rows_left && c < cols_left;
+      if (VEC == 1) {
+        regs[it][0] = ok ? origin[(int64_t)r * ld + c] : (TIn)0;
+      } else {
+        typedef TIn vec_t __attribute__((ext_vector_type(VEC)));
+        vec_t v = (vec_t)(TIn)0;
+        if (ok) v = *reinterpret_cast<const vec_t *>(origin + (int64_t)r * ld + c);
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) regs[it][e] = v[e];
+      }
+    }
+  }
+  __device__ __forceinline__ void store(TIn *lds, int stride, int tid) const {
+#pragma unroll
+    for (int it = 0; it < ITERS; ++it) {
+      const int idx = tid + it * 256;
+      if (ITERS * 256 == SLOTS || idx < SLOTS) {
+        const int r = idx / SLOTS_PER_ROW;
+        const int c = (idx - r * SLOTS_PER_ROW) * VEC;
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) lds[r * stride + c + e] = regs[it][e];
+      }
+    }
+  }
+};
+
+template <typename TIn, typename TAcc, typename TOut, bool TA, int BM, int BN, int WGM, int WGN, int VEC>
+__global__ __launch_bounds__(256) void gemm_kernel(const GemmParams P) {
+  constexpr int BK = 32;
+  static_assert(WGM * WGN == 4, "four wavefronts per workgroup");
+  constexpr int WM = BM / WGM, WN = BN / WGN;
+  static_assert(WM % 16 == 0 && WN % 16 == 0, "wave tile must be made of 16x16 blocks");
+  constexpr int TM = WM / 16, TN = WN / 16;
+  // LDS strides (elements)
+  constexpr int SA = TA ? (BM + pad_kmajor(BM)) : (BK + (sizeof(TIn) == 4 ? 4 : 1));
+  constexpr int SB = BN + pad_kmajor(BN);
+  constexpr int A_ROWS = TA ? BK : BM, A_COLS = TA ? BM : BK;
+  __shared__ TIn As[A_ROWS * SA];
+  __shared__ TIn Bs[BK * SB];
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63, wave = tid >> 6;
+  const int wm0 = (wave / WGN) * WM, wn0 = (wave % WGN) * WN;
+  const int r16 = lane & 15, kq = lane >> 4;
+
+  const int64_t m0 = (int64_t)blockIdx.y * BM;
+  const int64_t n0 = (int64_t)blockIdx.x * BN;
+  const int64_t k_begin = (int64_t)blockIdx.z * P.k_per_split;
+  const int64_t k_end = (k_begin + P.k_per_split < P.K) ? (k_begin + P.k_per_split) : P.K;
+
+  const TIn *A = (const TIn *)P.A;
+  const TIn *B = (const TIn *)P.B;
+
+  typedef typename Mfma<TAcc>::vec acc_t;
+  acc_t acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j) acc[i][j] = (acc_t)(TAcc)0;
+
+  TileStage<TIn, A_ROWS, A_COLS, VEC> sa;
+  TileStage<TIn, BK, BN, VEC> sb;
+
+  auto load_tiles = [&](int64_t k0) {
+    if (TA) sa.load(A + k0 * P.lda + m0, P.lda, k_end - k0, P.M - m0, tid);
+    else    sa.load(A + m0 * P.lda + k0, P.lda, P.M - m0, k_end - k0, tid);
+    sb.load(B + k0 * P.ldb + n0, P.ldb, k_end - k0, P.N - n0, tid);
+  };
+
+  if (k_begin < k_end) load_tiles(k_begin);
+  for (int64_t k0 = k_begin; k0 < k_end; k0 += BK) {
+    sa.store(As, SA, tid);
+    sb.store(Bs, SB, tid);
+    __syncthreads();
+    if (k0 + BK < k_end) load_tiles(k0 + BK);
+#pragma unroll
+    for (int kk = 0; kk < BK; kk += 4) {
+      TAcc af[TM], bf[TN];
+#pragma unroll
+      for (int i = 0; i < TM; ++i) {
+        const int row = wm0 + i * 16 + r16;
+        af[i] = (TAcc)(TA ? As[(kk + kq) * SA + row] : As[row * SA + kk + kq]);
+      }
+#pragma unroll
+      for (int j = 0; j < TN; ++j) bf[j] = (TAcc)Bs[(kk + kq) * SB + wn0 + j * 16 + r16];
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) acc[i][j] = Mfma<TAcc>::run(af[i], bf[j], acc[i][j]);
+    }
+    __syncthreads();
+  }
+
+  // epilogue
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int v = 0; v < 4; ++v) {
+        const int64_t row = m0 + wm0 + i * 16 + Mfma<TAcc>::row(lane, v);
+        const int64_t col = n0 + wn0 + j * 16 + r16;
+        if (row < P.M && col < P.N) {
+          if (P.splits > 1) {
+            ((TAcc *)P.partial)[((int64_t)blockIdx.z * P.M + row) * P.N + col] = acc[i][j][v];
+          } else {
+            store_result<TOut, TAcc, sizeof(TIn) == 4>(P, row, col, acc[i][j][v]);
+          }
+        }
+      }
+}
+
+template <typename TIn, typename TAcc, typename TOut>
+__global__ __launch_bounds__(256) void splitk_reduce_kernel(const GemmParams P) {
+  const int64_t total = P.M * P.N;
+  for (int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; e < total;
+       e += (int64_t)gridDim.x * blockDim.x) {
+    const TAcc *p = (const TAcc *)P.partial + e;
+    TAcc sum = (TAcc)0;
+    for (int s = 0; s < P.splits; ++s) sum += p[(int64_t)s * total];
+    const int64_t row = e / P.N;
+    store_result<TOut, TAcc, sizeof(TIn) == 4>(P, row, e - row * P.N, sum);
+  }
+}
+
+// ---------------------------------------------------------------- host side
+
+struct TileChoice {
+  int bm, bn;   // workgroup tile
+};
+
+// Tile shapes instantiated below (see the dispatch switch).
+inline TileChoice choose_tile(int64_t M, int64_t N) {
+  TileChoice t;
+  if (N <= 128) {
+    t.bm = 64;
+    t.bn = (int)(ceil_div(N, 16) * 16);
+  } else {
+    // wide outputs: 128-row tiles, column tile with the least padding
+    t.bm = 128;
+    const int64_t pad96 = ceil_div(N, 96) * 96 - N, pad128 = ceil_div(N, 128) * 128 - N;
+    t.bn = (pad96 < pad128) ? 96 : 128;
+  }
+  (void)M;
+  return t;
+}
+
+struct SplitChoice {
+  int splits;
+  int64_t k_per_split;
+};
+
+inline SplitChoice choose_split(const rsvd_ctx *ctx, const TileChoice &t, int64_t M, int64_t N, int64_t K,
+                                int force) {
+  const int64_t tiles = ceil_div(M, t.bm) * ceil_div(N, t.bn);
+  const int64_t ktiles = ceil_div(K, 32);
+  int64_t s = 1;
+  if (force > 0) {
+    s = force;
+  } else {
+    const int64_t want = 2 * (int64_t)ctx->cu_count;
+    if (tiles < want) s = ceil_div(want, tiles);
+    const int64_t max_by_k = ktiles / 4 > 0 ? ktiles / 4 : 1;   // at least 4 k-tiles per split
+    if (s > max_by_k) s = max_by_k;
+    if (s > 256) s = 256;
+  }
+  if (s > ktiles) s = ktiles > 0 ? ktiles : 1;
+  SplitChoice c;
+  c.k_per_split = ceil_div(ktiles, s) * 32;
+  c.splits = (int)ceil_div(K, c.k_per_split);
+  if (c.splits < 1) c.splits = 1;
+  return c;
+}
+
+template <typename TIn, typename TAcc, typename TOut>
+struct GemmDispatch {
+  template <bool TA, int BM, int BN, int WGM, int WGN>
+  static hipError_t run(hipStream_t s, const GemmParams &P, bool vec) {
+    dim3 grid((unsigned)ceil_div(P.N, BN), (unsigned)ceil_div(P.M, BM), (unsigned)P.splits);
+    constexpr int V = 16 / sizeof(TIn);
+    if (vec) {
+      hipLaunchKernelGGL((gemm_kernel<TIn, TAcc, TOut, TA, BM, BN, WGM, WGN, V>), grid, dim3(256), 0, s, P);
+    } else {
+      hipLaunchKernelGGL((gemm_kernel<TIn, TAcc, TOut, TA, BM, BN, WGM, WGN, 1>), grid, dim3(256), 0, s, P);
+    }
+    return hipGetLastError();
+  }
+
+  template <bool TA>
+  static hipError_t by_tile(hipStream_t s, const GemmParams &P, const TileChoice &t, bool vec) {
+    if (t.bm == 64) {
+      switch (t.bn) {
+        case 16:  return run<TA, 64, 16, 4, 1>(s, P, vec);
+        case 32:  return run<TA, 64, 32, 4, 1>(s, P, vec);
+        case 48:  return run<TA, 64, 48, 4, 1>(s, P, vec);
+        case 64:  return run<TA, 64, 64, 4, 1>(s, P, vec);
+        case 80:  return run<TA, 64, 80, 4, 1>(s, P, vec);
+        case 96:  return run<TA, 64, 96, 4, 1>(s, P, vec);
+        case 112: return run<TA, 64, 112, 4, 1>(s, P, vec);
+        case 128: return run<TA, 64, 128, 4, 1>(s, P, vec);
+      }
+    } else {
+      if (t.bn == 96)  return run<TA, 128, 96, 2, 2>(s, P, vec);
+      if (t.bn == 128) return run<TA, 128, 128, 2, 2>(s, P, vec);
+    }
+    return hipErrorInvalidValue;
+  }
+
+  static size_t partial_bytes(const rsvd_ctx *ctx, int64_t M, int64_t N, int64_t K) {
+    const TileChoice t = choose_tile(M, N);
+    const SplitChoice c = choose_split(ctx, t, M, N, K, 0);
+    return c.splits > 1 ? (size_t)c.splits * (size_t)M * (size_t)N * sizeof(TAcc) : 0;
+  }
+
+  static hipError_t launch(const rsvd_ctx *ctx, hipStream_t s, const GemmDesc &d) {
+    if (d.M <= 0 || d.N <= 0) return hipSuccess;
+    const TileChoice t = choose_tile(d.M, d.N);
+    SplitChoice c = choose_split(ctx, t, d.M, d.N, d.K, d.force_splits);
+    if (c.splits > 1) {
+      const size_t need = (size_t)c.splits * (size_t)d.M * (size_t)d.N * sizeof(TAcc);
+      if (d.partial == nullptr || d.partial_bytes < need) return hipErrorInvalidValue;
+    }
+    if (d.trans_c && d.beta != 0.0) return hipErrorInvalidValue;
+    GemmParams P;
+    P.M = d.M; P.N = d.N; P.K = d.K;
+    P.A = d.A; P.lda = d.lda; P.B = d.B; P.ldb = d.ldb; P.C = d.C; P.ldc = d.ldc;
+    P.partial = d.partial; P.k_per_split = c.k_per_split; P.splits = c.splits;
+    P.trans_c = d.trans_c; P.alpha = d.alpha; P.beta = d.beta;
+    P.dead = d.dead; P.seed = d.seed; P.refill_stream = d.refill_stream;
+    P.refill_scale = d.refill_scale; P.refill_ld = d.refill_ld;
+    // 16-byte vector loads need aligned bases, leading dimensions and extents.
+    constexpr int V = 16 / sizeof(TIn);
+    const int64_t a_contig = d.trans_a ? d.M : d.K;
+    const bool vec = ((uintptr_t)d.A % 16 == 0) && ((uintptr_t)d.B % 16 == 0) && d.lda % V == 0 &&
+                     d.ldb % V == 0 && a_contig % V == 0 && d.N % V == 0;
+    hipError_t e = d.trans_a ? by_tile<true>(s, P, t, vec) : by_tile<false>(s, P, t, vec);
+    if (e != hipSuccess) return e;
+    if (c.splits > 1) {
+      int64_t blocks = ceil_div(d.M * d.N, 256);
+      if (blocks > 8192) blocks = 8192;
+      hipLaunchKernelGGL((splitk_reduce_kernel<TIn, TAcc, TOut>), dim3((unsigned)blocks), dim3(256), 0, s, P);
+      e = hipGetLastError();
+    }
+    return e;
+  }
+};
+
+}  // namespace rsvd

@@ -1,0 +1,478 @@
+// C ABI of the library: argument checks, workspace layout and the sequence of
+// kernel launches for Algorithm 1 (sketch, range product, power scheme with
+// re-orthonormalisation, projection, small SVD, lift).  Host code only.
+#include <math.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <new>
+
+#include "common.hpp"
+
+namespace rsvd {
+
+size_t gemm_partial_bytes_f32(const rsvd_ctx *, int64_t, int64_t, int64_t);
+size_t gemm_partial_bytes_f64(const rsvd_ctx *, int64_t, int64_t, int64_t);
+size_t gemm_partial_bytes_f32acc64(const rsvd_ctx *, int64_t, int64_t, int64_t);
+hipError_t gemm_launch_f32(const rsvd_ctx *, hipStream_t, const GemmDesc &);
+hipError_t gemm_launch_f64(const rsvd_ctx *, hipStream_t, const GemmDesc &);
+hipError_t gemm_launch_f32acc64(const rsvd_ctx *, hipStream_t, const GemmDesc &);
+
+size_t gemm_partial_bytes(const rsvd_ctx *ctx, GemmKind kind, int trans_a, int64_t M, int64_t N, int64_t K) {
+  (void)trans_a;
+  switch (kind) {
+    case GEMM_F32: return gemm_partial_bytes_f32(ctx, M, N, K);
+    case GEMM_F64: return gemm_partial_bytes_f64(ctx, M, N, K);
+    default:       return gemm_partial_bytes_f32acc64(ctx, M, N, K);
+  }
+}
+
+hipError_t gemm_launch(const rsvd_ctx *ctx, hipStream_t s, GemmKind kind, const GemmDesc &d) {
+  switch (kind) {
+    case GEMM_F32: return gemm_launch_f32(ctx, s, d);
+    case GEMM_F64: return gemm_launch_f64(ctx, s, d);
+    default:       return gemm_launch_f32acc64(ctx, s, d);
+  }
+}
+
+template <typename T>
+__global__ void copy_kernel(const T *__restrict__ src, T *__restrict__ dst, int64_t n) {
+  for (int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; e < n; e += (int64_t)gridDim.x * blockDim.x)
+    dst[e] = src[e];
+}
+
+static hipError_t copy_launch(hipStream_t s, rsvd_dtype dtype, const void *src, void *dst, int64_t n) {
+  if (n <= 0) return hipSuccess;
+  int64_t blocks = ceil_div(n, 256);
+  if (blocks > 4096) blocks = 4096;
+  if (dtype == RSVD_F32)
+    hipLaunchKernelGGL(copy_kernel<float>, dim3((unsigned)blocks), dim3(256), 0, s, (const float *)src, (float *)dst, n);
+  else
+    hipLaunchKernelGGL(copy_kernel<double>, dim3((unsigned)blocks), dim3(256), 0, s, (const double *)src, (double *)dst, n);
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------- workspace
+
+// Offsets (bytes) into the caller's workspace.  Depends on (dtype, m, n, l) only.
+struct Layout {
+  size_t bufM[2], bufN[2];          // m x l and n x l panels (ld l), ping-pong for CholeskyQR
+  size_t partial, partial_bytes;    // split-K scratch
+  size_t G, chol_scratch;           // fp64 Gram matrix, blocked-Cholesky scratch
+  size_t Rinv, R1, R2, Rb;          // R^-1 (dtype), R factors of both rounds and their product (fp64)
+  size_t dead, info;                // flags per column, DevInfo
+  size_t sigma, Wj, Xj;             // all l triplets of step 5: sigma, Ub (= W), X
+  size_t jac_scratch, jac_scratch_bytes;
+  size_t total;
+};
+
+static Layout make_layout(const rsvd_ctx *ctx, rsvd_dtype dtype, int64_t m, int64_t n, int64_t l) {
+  Layout L;
+  const size_t es = dtype_size(dtype);
+  size_t off = 0;
+  auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
+  for (int i = 0; i < 2; ++i) L.bufM[i] = take((size_t)m * l * es);
+  for (int i = 0; i < 2; ++i) L.bufN[i] = take((size_t)n * l * es);
+  const GemmKind kind = dtype == RSVD_F32 ? GEMM_F32 : GEMM_F64;
+  const GemmKind gram = dtype == RSVD_F32 ? GEMM_F32_ACC64 : GEMM_F64;
+  size_t pb = gemm_partial_bytes(ctx, kind, 0, m, l, n);
+  size_t t;
+  if ((t = gemm_partial_bytes(ctx, kind, 1, n, l, m)) > pb) pb = t;
+  if ((t = gemm_partial_bytes(ctx, gram, 1, l, l, m)) > pb) pb = t;
+  if ((t = gemm_partial_bytes(ctx, gram, 1, l, l, n)) > pb) pb = t;
+  L.partial_bytes = pb;
+  L.partial = take(pb);
+  L.G = take((size_t)l * l * 8);
+  L.chol_scratch = take(chol_scratch_elems(ctx, l) * 8);
+  L.Rinv = take((size_t)l * l * es);
+  L.R1 = take((size_t)l * l * 8);
+  L.R2 = take((size_t)l * l * 8);
+  L.Rb = take((size_t)l * l * 8);
+  L.dead = take((size_t)l * sizeof(int));
+  L.info = take(sizeof(DevInfo));
+  L.sigma = take((size_t)l * es);
+  L.Wj = take((size_t)l * l * es);
+  L.Xj = take((size_t)l * l * es);
+  L.jac_scratch_bytes = jacobi_scratch_bytes(ctx, dtype, l);
+  L.jac_scratch = take(L.jac_scratch_bytes);
+  L.total = off;
+  return L;
+}
+
+struct Ws {
+  char *base;
+  Layout L;
+  template <typename P> P *at(size_t off) const { return reinterpret_cast<P *>(base + off); }
+};
+
+static int fail_hip(rsvd_ctx *ctx, hipError_t e, const char *where) {
+  snprintf(ctx->hip_error, sizeof(ctx->hip_error), "%s: %s", where, hipGetErrorString(e));
+  return RSVD_ERR_HIP;
+}
+
+#define RSVD_TRY(expr, where)                                   \
+  do {                                                          \
+    hipError_t e_ = (expr);                                     \
+    if (e_ != hipSuccess) return fail_hip(ctx, e_, where);      \
+  } while (0)
+
+// ---------------------------------------------------------------- building blocks
+
+// Y (rows x l, ld ldy) -> Q in place by two rounds of CholeskyQR; `tmp` is a
+// rows x l panel (ld l).  Rout (fp64, l x l) receives R with Y = Q R, or NULL.
+static int orthonormalize(rsvd_ctx *ctx, hipStream_t s, rsvd_dtype dtype, const Ws &w, int64_t rows, int64_t l,
+                          void *Y, int64_t ldy, void *tmp, double *Rout, uint64_t seed, uint32_t refill_stream) {
+  const GemmKind kind = dtype == RSVD_F32 ? GEMM_F32 : GEMM_F64;
+  const GemmKind gram = dtype == RSVD_F32 ? GEMM_F32_ACC64 : GEMM_F64;
+  const Layout &L = w.L;
+  // pivot threshold: rounding level of the fp64 Gram matrix and its elimination
+  const double tau = 32.0 * 2.220446049250313e-16 * ((double)l + sqrt((double)rows));
+  void *src = Y; int64_t lds_ = ldy;
+  void *dst = tmp; int64_t ldd = l;
+  for (int round = 0; round < 2; ++round) {
+    GemmDesc g;
+    g.trans_a = 1; g.M = l; g.N = l; g.K = rows;
+    g.A = src; g.lda = lds_; g.B = src; g.ldb = lds_;
+    g.C = w.at<double>(L.G); g.ldc = l;
+    g.partial = w.at<void>(L.partial); g.partial_bytes = L.partial_bytes;
+    RSVD_TRY(gemm_launch(ctx, s, gram, g), "gram");
+    double *R = Rout ? w.at<double>(round == 0 ? L.R1 : L.R2) : nullptr;
+    RSVD_TRY(chol_inverse_launch(ctx, s, dtype, l, w.at<double>(L.G), l, tau, w.at<void>(L.Rinv), R,
+                                 w.at<int>(L.dead), w.at<DevInfo>(L.info), w.at<double>(L.chol_scratch),
+                                 w.at<void>(L.partial), L.partial_bytes),
+             "cholesky");
+    GemmDesc a;
+    a.M = rows; a.N = l; a.K = l;
+    a.A = src; a.lda = lds_; a.B = w.at<void>(L.Rinv); a.ldb = l;
+    a.C = dst; a.ldc = ldd;
+    a.dead = w.at<int>(L.dead); a.seed = seed; a.refill_stream = refill_stream + (uint32_t)round;
+    a.refill_scale = 1.0 / sqrt((double)rows); a.refill_ld = l;
+    a.force_splits = 1;
+    RSVD_TRY(gemm_launch(ctx, s, kind, a), "apply R^-1");
+    void *tp = src; src = dst; dst = tp;
+    int64_t tl = lds_; lds_ = ldd; ldd = tl;
+  }
+  if (Rout) RSVD_TRY(triu_product_launch(s, l, w.at<double>(L.R2), w.at<double>(L.R1), Rout), "R product");
+  return 0;
+}
+
+static int product(rsvd_ctx *ctx, hipStream_t s, rsvd_dtype dtype, const Ws &w, int trans_a, int64_t M, int64_t N,
+                   int64_t K, const void *A, int64_t lda, const void *B, int64_t ldb, void *C, int64_t ldc,
+                   int trans_c, bool allow_split) {
+  GemmDesc d;
+  d.trans_a = trans_a; d.trans_c = trans_c; d.M = M; d.N = N; d.K = K;
+  d.A = A; d.lda = lda; d.B = B; d.ldb = ldb; d.C = C; d.ldc = ldc;
+  if (allow_split) { d.partial = w.at<void>(w.L.partial); d.partial_bytes = w.L.partial_bytes; }
+  else d.force_splits = 1;
+  RSVD_TRY(gemm_launch(ctx, s, dtype == RSVD_F32 ? GEMM_F32 : GEMM_F64, d), "gemm");
+  return 0;
+}
+
+// Step 5 on Bt (n x l, ld ldbt): Bt = Qb Rb, Rb = X Sigma W^T.  On exit Bt holds Qb,
+// and sigma / W / X sit in the workspace.
+static int small_svd(rsvd_ctx *ctx, hipStream_t s, rsvd_dtype dtype, const Ws &w, int64_t n, int64_t l, void *Bt,
+                     int64_t ldbt, void *tmp, uint64_t seed, uint32_t refill_stream) {
+  const Layout &L = w.L;
+  int rc = orthonormalize(ctx, s, dtype, w, n, l, Bt, ldbt, tmp, w.at<double>(L.Rb), seed, refill_stream);
+  if (rc) return rc;
+  hipError_t e = jacobi_launch(ctx, s, dtype, l, w.at<void>(L.Rb), 1, w.at<void>(L.sigma), w.at<void>(L.Xj),
+                               w.at<void>(L.Wj), w.at<DevInfo>(L.info), w.at<void>(L.jac_scratch),
+                               L.jac_scratch_bytes);
+  if (e == hipErrorNotSupported) return RSVD_ERR_UNSUPPORTED;
+  RSVD_TRY(e, "jacobi");
+  return 0;
+}
+
+static int finish_info(rsvd_ctx *ctx, hipStream_t s, const Ws &w, rsvd_info *info) {
+  if (info == nullptr) return 0;
+  DevInfo h;
+  RSVD_TRY(hipMemcpyAsync(&h, w.at<DevInfo>(w.L.info), sizeof(h), hipMemcpyDeviceToHost, s), "info copy");
+  RSVD_TRY(hipStreamSynchronize(s), "synchronize");
+  info->status = h.status;
+  info->jacobi_sweeps = h.jacobi_sweeps;
+  info->refilled_columns = h.refilled;
+  info->reserved = 0;
+  return h.status;
+}
+
+static bool valid_dtype(rsvd_dtype d) { return d == RSVD_F32 || d == RSVD_F64; }
+
+}  // namespace rsvd
+
+using namespace rsvd;
+
+extern "C" {
+
+int rsvd_create(rsvd_ctx **out, int device) {
+  if (out == nullptr) return -1;
+  *out = nullptr;
+  hipDeviceProp_t prop;
+  if (hipGetDeviceProperties(&prop, device) != hipSuccess) return -2;
+  rsvd_ctx *c = new (std::nothrow) rsvd_ctx;
+  if (c == nullptr) return RSVD_ERR_HIP;
+  c->device = device;
+  c->cu_count = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
+  size_t lds = prop.sharedMemPerBlock;
+#if HIP_VERSION_MAJOR >= 6
+  if (prop.sharedMemPerBlockOptin > lds) lds = prop.sharedMemPerBlockOptin;
+#endif
+  if (lds > 160 * 1024) lds = 160 * 1024;
+  if (lds < 32 * 1024) lds = 32 * 1024;
+  c->lds_per_block = lds;
+  c->hip_error[0] = 0;
+  *out = c;
+  return 0;
+}
+
+int rsvd_destroy(rsvd_ctx *ctx) {
+  delete ctx;
+  return 0;
+}
+
+const char *rsvd_status_string(int code) {
+  switch (code) {
+    case RSVD_OK: return "success";
+    case RSVD_ERR_NONFINITE: return "non-finite values met during orthonormalisation";
+    case RSVD_ERR_NO_CONVERGENCE: return "Jacobi SVD did not converge within the sweep cap";
+    case RSVD_ERR_HIP: return "HIP runtime error";
+    case RSVD_ERR_UNSUPPORTED: return "problem shape not supported";
+    default: return code < 0 ? "invalid argument" : "unknown status";
+  }
+}
+
+const char *rsvd_last_hip_error(const rsvd_ctx *ctx) { return ctx ? ctx->hip_error : ""; }
+
+int rsvd_workspace_bytes(rsvd_ctx *ctx, rsvd_dtype dtype, int64_t m, int64_t n, int k, int p, int q, rsvd_job job,
+                         size_t *bytes) {
+  if (ctx == nullptr) return -1;
+  if (!valid_dtype(dtype)) return -2;
+  if (m < 1) return -3;
+  if (n < 1) return -4;
+  if (k < 1) return -5;
+  if (p < 0 || (int64_t)k + p > (m < n ? m : n)) return -6;
+  if (q < 0) return -7;
+  if (job < RSVD_JOB_S || job > RSVD_JOB_SUV) return -8;
+  if (bytes == nullptr) return -9;
+  *bytes = make_layout(ctx, dtype, m, n, (int64_t)k + p).total;
+  return 0;
+}
+
+int rsvd_run(rsvd_ctx *ctx, void *stream, rsvd_dtype dtype, rsvd_job job, int64_t m, int64_t n, const void *A,
+             int64_t lda, int k, int p, int q, uint64_t seed, void *S, void *U, int64_t ldu, void *Vt, int64_t ldvt,
+             void *workspace, size_t workspace_bytes, rsvd_info *info) {
+  if (ctx == nullptr) return -1;
+  if (!valid_dtype(dtype)) return -3;
+  if (job < RSVD_JOB_S || job > RSVD_JOB_SUV) return -4;
+  if (m < 1) return -5;
+  if (n < 1) return -6;
+  if (A == nullptr) return -7;
+  if (lda < n) return -8;
+  if (k < 1) return -9;
+  if (p < 0 || (int64_t)k + p > (m < n ? m : n)) return -10;
+  if (q < 0) return -11;
+  if (S == nullptr) return -13;
+  if (job == RSVD_JOB_SUV && U == nullptr) return -14;
+  if (job == RSVD_JOB_SUV && ldu < k) return -15;
+  if (job >= RSVD_JOB_SV && Vt == nullptr) return -16;
+  if (job >= RSVD_JOB_SV && ldvt < n) return -17;
+  const int64_t l = (int64_t)k + p;
+  Ws w;
+  w.L = make_layout(ctx, dtype, m, n, l);
+  w.base = (char *)workspace;
+  if (workspace == nullptr || ((uintptr_t)workspace & 255) != 0) return -18;
+  if (workspace_bytes < w.L.total) return -19;
+  if (l > jacobi_max_lds_order(ctx, dtype) && jacobi_scratch_bytes(ctx, dtype, l) == 0) return RSVD_ERR_UNSUPPORTED;
+  hipStream_t s = (hipStream_t)stream;
+  const Layout &L = w.L;
+  void *bM0 = w.at<void>(L.bufM[0]), *bM1 = w.at<void>(L.bufM[1]);
+  void *bN0 = w.at<void>(L.bufN[0]), *bN1 = w.at<void>(L.bufN[1]);
+  int rc;
+
+  RSVD_TRY(zero_ints_launch(s, w.at<int>(L.info), 4), "zero info");
+  // step 1
+  RSVD_TRY(sketch_launch(s, dtype, seed, 0u, n, l, bN0, l), "sketch");
+  // step 2: Y = A Omega, then q rounds of Z = A^T Q, Y = A Z, each re-orthonormalised
+  if ((rc = product(ctx, s, dtype, w, 0, m, l, n, A, lda, bN0, l, bM0, l, 0, true))) return rc;
+  uint32_t refill = 16;
+  if ((rc = orthonormalize(ctx, s, dtype, w, m, l, bM0, l, bM1, nullptr, seed, refill))) return rc;
+  refill += 2;
+  for (int it = 0; it < q; ++it) {
+    if ((rc = product(ctx, s, dtype, w, 1, n, l, m, A, lda, bM0, l, bN0, l, 0, true))) return rc;
+    if ((rc = orthonormalize(ctx, s, dtype, w, n, l, bN0, l, bN1, nullptr, seed, refill))) return rc;
+    refill += 2;
+    if ((rc = product(ctx, s, dtype, w, 0, m, l, n, A, lda, bN0, l, bM0, l, 0, true))) return rc;
+    // step 3 on the last pass
+    if ((rc = orthonormalize(ctx, s, dtype, w, m, l, bM0, l, bM1, nullptr, seed, refill))) return rc;
+    refill += 2;
+  }
+  // step 4: B^T = A^T Q
+  if ((rc = product(ctx, s, dtype, w, 1, n, l, m, A, lda, bM0, l, bN0, l, 0, true))) return rc;
+  // step 5
+  if ((rc = small_svd(ctx, s, dtype, w, n, l, bN0, l, bN1, seed, refill))) return rc;
+  RSVD_TRY(copy_launch(s, dtype, w.at<void>(L.sigma), S, k), "copy S");
+  if (job >= RSVD_JOB_SV) {
+    // V^T = (Qb X[:, :k])^T
+    if ((rc = product(ctx, s, dtype, w, 0, n, k, l, bN0, l, w.at<void>(L.Xj), l, Vt, ldvt, 1, false))) return rc;
+  }
+  if (job == RSVD_JOB_SUV) {
+    // step 6: U = Q Ub[:, :k]
+    if ((rc = product(ctx, s, dtype, w, 0, m, k, l, bM0, l, w.at<void>(L.Wj), l, U, ldu, 0, false))) return rc;
+  }
+  return finish_info(ctx, s, w, info);
+}
+
+int rsvd_stage_sketch(rsvd_ctx *ctx, void *stream, rsvd_dtype dtype, uint64_t seed, uint32_t stream_id, int64_t rows,
+                      int64_t cols, void *Omega, int64_t ldo) {
+  if (ctx == nullptr) return -1;
+  if (!valid_dtype(dtype)) return -3;
+  if (rows < 0) return -6;
+  if (cols < 0) return -7;
+  if (rows * cols == 0) return 0;
+  if (Omega == nullptr) return -8;
+  if (ldo < cols) return -9;
+  RSVD_TRY(sketch_launch((hipStream_t)stream, dtype, seed, stream_id, rows, cols, Omega, ldo), "sketch");
+  return 0;
+}
+
+int rsvd_stage_philox_raw(rsvd_ctx *ctx, void *stream, uint64_t seed, uint32_t stream_id, uint64_t first_group,
+                          int64_t n_groups, uint32_t *out) {
+  if (ctx == nullptr) return -1;
+  if (n_groups < 0) return -6;
+  if (n_groups == 0) return 0;
+  if (out == nullptr) return -7;
+  RSVD_TRY(philox_raw_launch((hipStream_t)stream, seed, stream_id, first_group, n_groups, out), "philox");
+  return 0;
+}
+
+static int stage_gemm(rsvd_ctx *ctx, void *stream, rsvd_dtype dtype, int trans_a, int64_t m, int64_t n, int64_t l,
+                      const void *A, int64_t lda, const void *X, int64_t ldx, void *Y, int64_t ldy, void *workspace,
+                      size_t workspace_bytes) {
+  if (ctx == nullptr) return -1;
+  if (!valid_dtype(dtype)) return -3;
+  if (m < 1) return -4;
+  if (n < 1) return -5;
+  if (l < 1 || l > (m < n ? m : n)) return -6;
+  if (A == nullptr) return -7;
+  if (lda < n) return -8;
+  if (X == nullptr) return -9;
+  if (ldx < l) return -10;
+  if (Y == nullptr) return -11;
+  if (ldy < l) return -12;
+  Ws w;
+  w.L = make_layout(ctx, dtype, m, n, l);
+  w.base = (char *)workspace;
+  if (workspace == nullptr || ((uintptr_t)workspace & 255) != 0) return -13;
+  if (workspace_bytes < w.L.total) return -14;
+  if (trans_a) return product(ctx, (hipStream_t)stream, dtype, w, 1, n, l, m, A, lda, X, ldx, Y, ldy, 0, true);
+  return product(ctx, (hipStream_t)stream, dtype, w, 0, m, l, n, A, lda, X, ldx, Y, ldy, 0, true);
+}
+
+int rsvd_stage_gemm_an(rsvd_ctx *ctx, void *stream, rsvd_dtype dtype, int64_t m, int64_t n, int64_t l, const void *A,
+                       int64_t lda, const void *X, int64_t ldx, void *Y, int64_t ldy, void *workspace,
+                       size_t workspace_bytes) {
+  return stage_gemm(ctx, stream, dtype, 0, m, n, l, A, lda, X, ldx, Y, ldy, workspace, workspace_bytes);
+}
+
+int rsvd_stage_gemm_atn(rsvd_ctx *ctx, void *stream, rsvd_dtype dtype, int64_t m, int64_t n, int64_t l, const void *A,
+                        int64_t lda, const void *X, int64_t ldx, void *Z, int64_t ldz, void *workspace,
+                        size_t workspace_bytes) {
+  return stage_gemm(ctx, stream, dtype, 1, m, n, l, A, lda, X, ldx, Z, ldz, workspace, workspace_bytes);
+}
+
+int rsvd_stage_orth(rsvd_ctx *ctx, void *stream, rsvd_dtype dtype, int64_t rows, int64_t l, void *Y, int64_t ldy,
+                    double *R, uint64_t seed, uint32_t refill_stream, void *workspace, size_t workspace_bytes,
+                    rsvd_info *info) {
+  if (ctx == nullptr) return -1;
+  if (!valid_dtype(dtype)) return -3;
+  if (rows < 1) return -4;
+  if (l < 1 || l > rows) return -5;
+  if (Y == nullptr) return -6;
+  if (ldy < l) return -7;
+  Ws w;
+  w.L = make_layout(ctx, dtype, rows, rows, l);
+  w.base = (char *)workspace;
+  if (workspace == nullptr || ((uintptr_t)workspace & 255) != 0) return -11;
+  if (workspace_bytes < w.L.total) return -12;
+  hipStream_t s = (hipStream_t)stream;
+  RSVD_TRY(zero_ints_launch(s, w.at<int>(w.L.info), 4), "zero info");
+  int rc = orthonormalize(ctx, s, dtype, w, rows, l, Y, ldy, w.at<void>(w.L.bufM[1]),
+                          R ? w.at<double>(w.L.Rb) : nullptr, seed, refill_stream);
+  if (rc) return rc;
+  if (R) RSVD_TRY(copy_launch(s, RSVD_F64, w.at<void>(w.L.Rb), R, l * l), "copy R");
+  return finish_info(ctx, s, w, info);
+}
+
+int rsvd_stage_small_svd(rsvd_ctx *ctx, void *stream, rsvd_dtype dtype, int64_t n, int64_t l, void *Bt, int64_t ldbt,
+                         void *sigma, void *Ub, void *V, int64_t ldv, uint64_t seed, void *workspace,
+                         size_t workspace_bytes, rsvd_info *info) {
+  if (ctx == nullptr) return -1;
+  if (!valid_dtype(dtype)) return -3;
+  if (n < 1) return -4;
+  if (l < 1 || l > n) return -5;
+  if (Bt == nullptr) return -6;
+  if (ldbt < l) return -7;
+  if (sigma == nullptr) return -8;
+  if (Ub == nullptr) return -9;
+  if (V == nullptr) return -10;
+  if (ldv < l) return -11;
+  Ws w;
+  w.L = make_layout(ctx, dtype, n, n, l);
+  w.base = (char *)workspace;
+  if (workspace == nullptr || ((uintptr_t)workspace & 255) != 0) return -13;
+  if (workspace_bytes < w.L.total) return -14;
+  if (l > jacobi_max_lds_order(ctx, dtype) && jacobi_scratch_bytes(ctx, dtype, l) == 0) return RSVD_ERR_UNSUPPORTED;
+  hipStream_t s = (hipStream_t)stream;
+  RSVD_TRY(zero_ints_launch(s, w.at<int>(w.L.info), 4), "zero info");
+  int rc = small_svd(ctx, s, dtype, w, n, l, Bt, ldbt, w.at<void>(w.L.bufN[1]), seed, 16u);
+  if (rc) return rc;
+  RSVD_TRY(copy_launch(s, dtype, w.at<void>(w.L.sigma), sigma, l), "copy sigma");
+  RSVD_TRY(copy_launch(s, dtype, w.at<void>(w.L.Wj), Ub, l * l), "copy Ub");
+  if ((rc = product(ctx, s, dtype, w, 0, n, l, l, Bt, ldbt, w.at<void>(w.L.Xj), l, V, ldv, 0, false))) return rc;
+  return finish_info(ctx, s, w, info);
+}
+
+int rsvd_stage_jacobi(rsvd_ctx *ctx, void *stream, rsvd_dtype dtype, int64_t l, void *M, void *sigma, void *X, void *W,
+                      void *workspace, size_t workspace_bytes, rsvd_info *info) {
+  if (ctx == nullptr) return -1;
+  if (!valid_dtype(dtype)) return -3;
+  if (l < 1) return -4;
+  if (M == nullptr) return -5;
+  if (sigma == nullptr) return -6;
+  if (X == nullptr) return -7;
+  if (W == nullptr) return -8;
+  Ws w;
+  w.L = make_layout(ctx, dtype, l, l, l);
+  w.base = (char *)workspace;
+  if (workspace == nullptr || ((uintptr_t)workspace & 255) != 0) return -9;
+  if (workspace_bytes < w.L.total) return -10;
+  hipStream_t s = (hipStream_t)stream;
+  RSVD_TRY(zero_ints_launch(s, w.at<int>(w.L.info), 4), "zero info");
+  hipError_t e = jacobi_launch(ctx, s, dtype, l, M, dtype == RSVD_F64, sigma, X, W, w.at<DevInfo>(w.L.info),
+                               w.at<void>(w.L.jac_scratch), w.L.jac_scratch_bytes);
+  if (e == hipErrorNotSupported) return RSVD_ERR_UNSUPPORTED;
+  RSVD_TRY(e, "jacobi");
+  return finish_info(ctx, s, w, info);
+}
+
+int rsvd_stage_lift(rsvd_ctx *ctx, void *stream, rsvd_dtype dtype, int64_t m, int64_t l, int64_t k, const void *Q,
+                    int64_t ldq, const void *W, int64_t ldw, void *U, int64_t ldu, int transpose_out, void *workspace,
+                    size_t workspace_bytes) {
+  (void)workspace; (void)workspace_bytes;
+  if (ctx == nullptr) return -1;
+  if (!valid_dtype(dtype)) return -3;
+  if (m < 1) return -4;
+  if (l < 1) return -5;
+  if (k < 1 || k > l) return -6;
+  if (Q == nullptr) return -7;
+  if (ldq < l) return -8;
+  if (W == nullptr) return -9;
+  if (ldw < k) return -10;
+  if (U == nullptr) return -11;
+  if (ldu < (transpose_out ? m : k)) return -12;
+  Ws w;
+  w.base = nullptr;
+  memset(&w.L, 0, sizeof(w.L));
+  return product(ctx, (hipStream_t)stream, dtype, w, 0, m, k, l, Q, ldq, W, ldw, U, ldu, transpose_out ? 1 : 0, false);
+}
+
+}  // extern "C"

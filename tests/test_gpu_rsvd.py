@@ -1,0 +1,118 @@
+"""GPU parity of the whole randomized k-SVD (Algorithm 1) through rsvd_run
+against the CPU oracle, at reduced and at full benchmark sizes."""
+import numpy as np
+import pytest
+
+import workloads
+from workloads import CONFIGS, scaled
+from oracle import rsvd as orc
+import parity
+from gpu_util import ctx, to_dev, to_np, say
+
+pytestmark = pytest.mark.gpu
+
+
+def run_and_compare(cfg, A_dev, A_host, q=None, note=""):
+    """Run the HIP path and the oracle on the same A; assert the benchmark spec's tolerances."""
+    import torch
+    q = cfg.q if q is None else q
+    k, p, l, dt = cfg.k, cfg.p, cfg.l, cfg.dtype
+    m, n = cfg.m, cfg.n
+    c = ctx()
+    say(f"rsvd {cfg.name} {dt} k={k} p={p} q={q} {note}")
+    S, U, Vt, info = c.rsvd_run(A_dev, k, p, q, seed=cfg.seed)
+    Sa, Ua, Vta, _ = c.rsvd_run(A_dev, l, 0, q, seed=cfg.seed)          # same sketch, no truncation
+    torch.cuda.synchronize()
+    S, U, Vt, Sa, Ua, Vta = (to_np(t).astype(np.float64) for t in (S, U, Vt, Sa, Ua, Vta))
+    say(f"  info: status={info.status} sweeps={info.jacobi_sweeps} refilled={info.refilled_columns}")
+    assert info.status == 0
+    assert (S == Sa[:k]).all() and (U == Ua[:, :k]).all()               # deterministic
+
+    o = orc.rsvd(A_host, k, p, q, cfg.seed, cfg.np_dtype)
+    res = parity.check_triplets(S, U, Vt, o.S, o.U, o.Vt, dt, m, n,
+                                S_all_o=o.S_all, U_all_o=o.Q @ o.Ub, Vt_all_o=o.Vt_all,
+                                S_all_g=Sa, U_all_g=Ua, Vt_all_g=Vta)
+    eps = parity.EPS[dt]
+    sig = parity.significant(o.S, dt, m, n)
+    ns = int(sig.sum())
+    assert parity.orthonormality(U[:, :ns]) <= 50 * l * eps
+    assert parity.orthonormality(Vt[:ns].T) <= 50 * l * eps
+    err_g = orc.reconstruction_error(A_host, U, S, Vt)
+    err_o = orc.reconstruction_error(A_host, o.U, o.S, o.Vt)
+    normA = float(np.sqrt(np.sum(A_host.astype(np.float64) ** 2)))
+    say(f"  sv_rel={res['sv_rel_max']:.2e} sinU={res['sin_u']:.2e} sinV={res['sin_v']:.2e} "
+        f"clusters={res['clusters']} skipped={res['skipped']} err_g/err_o={err_g / max(err_o, 1e-300):.6f}")
+    assert err_g <= 1.01 * err_o + 50 * eps * normA
+    # whole-basis angle: the l-dimensional ranges agree
+    assert parity.sin_theta(Ua[:, :ns], (o.Q @ o.Ub)[:, :ns]) <= parity.ANGLE_TOL[dt] or ns < l
+    return res
+
+
+SMALL = [
+    scaled(CONFIGS[1], 96, 160, rank=7, k=7, p=3),            # wide, exact recovery
+    scaled(CONFIGS[1], 200, 200, rank=12, k=10, p=6),
+    scaled(CONFIGS[2], 1250, 250, k=16, p=24),
+    scaled(CONFIGS[2], 777, 333, k=20, p=13),                  # odd l: scalar load paths
+    scaled(CONFIGS[3], 6250, 250, rank=25, k=25, p=5),
+    scaled(CONFIGS[4], 1250, 1250, rank=128, k=16, p=4),
+    scaled(CONFIGS[5], 2048, 512, rank=16, k=16, p=16),
+]
+
+
+@pytest.mark.parametrize("cfg", SMALL, ids=lambda c: c.name)
+def test_reduced_configs(cfg):
+    A = workloads.build(cfg)
+    run_and_compare(cfg, to_dev(A), A)
+
+
+@pytest.mark.parametrize("q", [0, 1, 3])
+def test_power_iteration_counts(q):
+    cfg = scaled(CONFIGS[2], 900, 300, k=12, p=12)
+    A = workloads.build(cfg)
+    run_and_compare(cfg, to_dev(A), A, q=q)
+
+
+def test_jobs_and_leading_dimensions():
+    import torch
+    from paper_2110_03423_amd import JOB_S, JOB_SV
+    cfg = scaled(CONFIGS[4], 400, 300, rank=64, k=8, p=8)
+    A = workloads.build(cfg)
+    c = ctx()
+    Abig = torch.zeros((400, 308), dtype=torch.float64, device="cuda:0")
+    Abig[:, :300] = to_dev(A)
+    S0, U0, Vt0, _ = c.rsvd_run(to_dev(A), cfg.k, cfg.p, cfg.q)
+    S1, U1, Vt1, _ = c.rsvd_run(Abig[:, :300], cfg.k, cfg.p, cfg.q)
+    assert torch.equal(S0, S1) and torch.equal(U0, U1) and torch.equal(Vt0, Vt1)
+    S2, U2, Vt2, _ = c.rsvd_run(to_dev(A), cfg.k, cfg.p, cfg.q, job=JOB_S)
+    assert U2 is None and Vt2 is None and torch.equal(S0, S2)
+    S3, U3, Vt3, _ = c.rsvd_run(to_dev(A), cfg.k, cfg.p, cfg.q, job=JOB_SV)
+    assert U3 is None and torch.equal(Vt0, Vt3)
+    # outputs with their own leading dimensions
+    Ub = torch.full((400, 12), 9.0, dtype=torch.float64, device="cuda:0")
+    Vb = torch.full((cfg.k, 310), 9.0, dtype=torch.float64, device="cuda:0")
+    Sb = torch.empty(cfg.k, dtype=torch.float64, device="cuda:0")
+    c.rsvd_run(to_dev(A), cfg.k, cfg.p, cfg.q, out=(Sb, Ub[:, :cfg.k], Vb[:, :300]))
+    assert torch.equal(Ub[:, :cfg.k], U0) and torch.equal(Vb[:, :300], Vt0)
+    assert (Ub[:, cfg.k:] == 9.0).all() and (Vb[:, 300:] == 9.0).all()
+
+
+def test_seed_changes_the_sketch_not_the_answer():
+    cfg = scaled(CONFIGS[1], 300, 200, rank=9, k=9, p=5)
+    A = workloads.build(cfg)
+    c = ctx()
+    S0, _, _, _ = c.rsvd_run(to_dev(A), cfg.k, cfg.p, cfg.q, seed=0)
+    S1, _, _, _ = c.rsvd_run(to_dev(A), cfg.k, cfg.p, cfg.q, seed=12345)
+    np.testing.assert_allclose(to_np(S0), to_np(S1), rtol=1e-11)
+    np.testing.assert_allclose(to_np(S0), 10.0 ** (-np.arange(9) / 5.0), rtol=1e-11)
+
+
+@pytest.mark.parametrize("cid", [1, 2, 3])
+def test_full_size_configs(cid):
+    """The benchmark's configurations at full size, oracle run in full beside the HIP path."""
+    cfg = CONFIGS[cid]
+    A_dev = workloads.build(cfg, device="cuda:0")
+    A = to_np(A_dev)
+    res = run_and_compare(cfg, A_dev, A, note="(full size)")
+    if cid == 1:      # planted spectrum, exact recovery expected
+        S, _, _, _ = ctx().rsvd_run(A_dev, cfg.k, cfg.p, cfg.q, seed=cfg.seed)
+        np.testing.assert_allclose(to_np(S), 10.0 ** (-np.arange(10) / 5.0), rtol=1e-11)
