@@ -1,0 +1,200 @@
+#!/usr/bin/env python3
+"""Benchmark of the randomized SVD hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config C]
+
+A step is one full rsvd_run (sketch, range product, power iterations with
+re-orthonormalisation, projection, small SVD, lift) on a synthetic matrix that
+is already resident in HBM.  Prints one JSON line: wall time per call, the
+roofline position of the kernel class that takes the most time (measured with
+HIP events around every kernel launch in a second pass over the same steps),
+and the CPU oracle timed on the host cores for the same workload.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+# MI355X published peaks
+PEAK_HBM = 8.0e12                                # B/s
+PEAK_MFMA = {"f32": 157.3e12, "f64": 78.6e12}    # dense matrix FLOP/s
+PEAK_VALU = {"f32": 157.3e12, "f64": 78.6e12}    # vector FLOP/s (256 CUs, 2.4 GHz)
+
+
+def kernel_models(cfg):
+    """Algorithmic flops and HBM bytes of ONE launch of each kernel class (unit: one launch)."""
+    m, n, l, k = cfg.m, cfg.n, cfg.l, cfg.k
+    sz = 4 if cfg.dtype == "f32" else 8
+    rows_avg = None
+    models = {
+        # products with A: read A once, read the skinny operand, write the result
+        "gemm_ax": dict(flops=2.0 * m * n * l, bytes=(m * n + n * l + m * l) * sz, mfma=cfg.dtype),
+        "gemm_atx": dict(flops=2.0 * m * n * l, bytes=(m * n + m * l + n * l) * sz, mfma=cfg.dtype),
+        # small dense stages (latency / ALU bound): flops of the textbook algorithm
+        "cholesky": dict(flops=(2.0 / 3.0) * l ** 3, bytes=2 * l * l * 8, alu="f64"),
+        "jacobi": dict(flops=None, bytes=3 * l * l * sz, alu=cfg.dtype),
+        "sketch": dict(flops=None, bytes=n * l * sz),
+    }
+    return models, rows_avg
+
+
+def per_launch_model(name, cfg, launches_per_call):
+    """Flops / bytes of one launch for classes whose size alternates between m and n rows."""
+    m, n, l, k = cfg.m, cfg.n, cfg.l, cfg.k
+    sz = 4 if cfg.dtype == "f32" else 8
+    q = cfg.q
+    n_m, n_n = 2 * (q + 1), 2 * (q + 1)            # CholeskyQR rounds on m x l and on n x l panels
+    if name == "gram":
+        rows = (n_m * m + n_n * n) / (n_m + n_n)
+        return dict(flops=2.0 * rows * l * l, bytes=rows * l * sz + l * l * 8, mfma="f64")
+    if name == "apply_rinv":
+        rows = (n_m * m + n_n * n) / (n_m + n_n)
+        return dict(flops=2.0 * rows * l * l, bytes=2 * rows * l * sz + l * l * sz, mfma=cfg.dtype)
+    if name == "lift":
+        rows = (m + n) / 2.0
+        return dict(flops=2.0 * rows * l * k, bytes=rows * (l + k) * sz, mfma=cfg.dtype)
+    models, _ = kernel_models(cfg)
+    return models.get(name)
+
+
+def roofline_for(name, avg_ms, cfg):
+    mod = per_launch_model(name, cfg, None)
+    if mod is None or avg_ms <= 0:
+        return None
+    t = avg_ms * 1e-3
+    t_mem = mod["bytes"] / PEAK_HBM
+    flops = mod.get("flops")
+    if "mfma" in mod and flops and flops / PEAK_MFMA[mod["mfma"]] > t_mem:
+        peak = PEAK_MFMA[mod["mfma"]]
+        return dict(bound="mfma", achieved=flops / t / 1e12, peak=peak / 1e12, unit="TFLOP/s",
+                    frac=flops / t / peak, traffic=None, kernel=name, avg_us=avg_ms * 1e3)
+    if "alu" in mod and flops and flops / PEAK_VALU[mod["alu"]] > t_mem:
+        peak = PEAK_VALU[mod["alu"]]
+        return dict(bound="alu", achieved=flops / t / 1e12, peak=peak / 1e12, unit="TFLOP/s",
+                    frac=flops / t / peak, traffic=None, kernel=name, avg_us=avg_ms * 1e3)
+    return dict(bound="hbm", achieved=mod["bytes"] / t / 1e9, peak=PEAK_HBM / 1e9, unit="GB/s",
+                frac=mod["bytes"] / t / PEAK_HBM, traffic=None, kernel=name, avg_us=avg_ms * 1e3)
+
+
+def cpu_baseline(cfg, A_host, budget_s=20.0):
+    """The oracle as it stands, on the host cores, on the same workload."""
+    import numpy as np
+    from oracle import rsvd as orc
+    cores = len(os.sched_getaffinity(0))
+    try:
+        from threadpoolctl import threadpool_info
+        nt = [d.get("num_threads") for d in threadpool_info() if d.get("user_api") == "blas"]
+        if nt:
+            cores = min(cores, max(nt))
+    except Exception:
+        pass
+    runs, t_total = 0, 0.0
+    while runs < 3 and t_total < budget_s:
+        t0 = time.perf_counter()
+        orc.rsvd(A_host, cfg.k, cfg.p, cfg.q, cfg.seed, cfg.np_dtype)
+        t_total += time.perf_counter() - t0
+        runs += 1
+    return dict(value=t_total / runs * 1e3, unit="ms", cores=cores, kind="oracle",
+                sample=f"{runs} full call(s) of the numpy fp64 oracle on the whole {cfg.m}x{cfg.n} workload")
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", type=int, default=2, help="benchmark configuration 1..5 (default 2)")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import workloads
+    from paper_2110_03423_amd import Rsvd, F32, F64
+
+    cfg = workloads.CONFIGS[args.config]
+    dev = "cuda:0"
+    A = workloads.build(cfg, device=dev)
+    ctx = Rsvd(0)
+    dt = F32 if cfg.dtype == "f32" else F64
+    ws = ctx.workspace(dt, cfg.m, cfg.n, cfg.k, cfg.p)
+    out = (torch.empty(cfg.k, dtype=A.dtype, device=dev), torch.empty((cfg.m, cfg.k), dtype=A.dtype, device=dev),
+           torch.empty((cfg.k, cfg.n), dtype=A.dtype, device=dev))
+
+    def step():
+        ctx.rsvd_run(A, cfg.k, cfg.p, cfg.q, seed=cfg.seed, workspace=ws, want_info=False, out=out)
+
+    for _ in range(args.warmup):
+        step()
+    _, _, _, info = ctx.rsvd_run(A, cfg.k, cfg.p, cfg.q, seed=cfg.seed, workspace=ws, out=out)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+
+    # per-call spread (paper's protocol: mean and standard deviation over repeated runs)
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(10)]
+    for a, b in evs:
+        a.record(); step(); b.record()
+    torch.cuda.synchronize()
+    per_call = np.array([a.elapsed_time(b) for a, b in evs])
+
+    # second pass over the same steps with HIP events around every kernel launch
+    ctx.rsvd_profile_enable(True)
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    prof = ctx.rsvd_profile_read()
+    ctx.rsvd_profile_enable(False)
+    kernels = {name: dict(ms_per_call=tot / args.steps, launches_per_call=cnt / args.steps,
+                          avg_us=tot / cnt * 1e3) for name, (tot, cnt) in prof.items()}
+    dominant = max(kernels, key=lambda kname: kernels[kname]["ms_per_call"])
+    roof = roofline_for(dominant, kernels[dominant]["avg_us"] * 1e-3, cfg)
+    stage_roof = {}
+    for name in kernels:
+        r = roofline_for(name, kernels[name]["avg_us"] * 1e-3, cfg)
+        if r is not None:
+            stage_roof[name] = dict(bound=r["bound"], achieved=round(r["achieved"], 3), unit=r["unit"],
+                                    frac=round(r["frac"], 4))
+
+    cpu = None
+    if not args.no_cpu:
+        cpu = cpu_baseline(cfg, A.cpu().numpy())
+
+    line = {
+        "metric": "rsvd_wall_time_ms",
+        "value": round(ms_per_step, 4),
+        "unit": "ms",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4),
+        "ms_per_step_mean_std_10": [round(float(per_call.mean()), 4), round(float(per_call.std()), 4)],
+        "higher_is_better": False,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": cfg.dtype,
+        "data": "synthetic",
+        "config": {"workload": cfg.name, "m": cfg.m, "n": cfg.n, "k": cfg.k, "p": cfg.p, "q": cfg.q,
+                   "job": "S,U,Vt", "jacobi_sweeps": info.jacobi_sweeps},
+        "roofline": roof,
+        "kernels": {kname: {a: round(b, 4) for a, b in v.items()} for kname, v in kernels.items()},
+        "stage_roofline": stage_roof,
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

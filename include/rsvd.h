@@ -76,6 +76,17 @@ const char *rsvd_status_string(int code);
 /* Text of the last HIP error seen by this context (host string, owned by ctx). */
 const char *rsvd_last_hip_error(const rsvd_ctx *ctx);
 
+/* Per-kernel timing for benchmarks (host-side state of the context; off by
+ * default).  While enabled, every kernel launch of every call on this context
+ * is bracketed by a pair of HIP events on the call's stream.
+ * rsvd_profile_read waits for the recorded events, sums elapsed milliseconds
+ * and launch counts per kernel class into total_ms / launches (host arrays of
+ * n_kinds >= 12 entries, index = class; names from rsvd_profile_kind_name)
+ * and clears the record. */
+int rsvd_profile_enable(rsvd_ctx *ctx, int on);
+int rsvd_profile_read(rsvd_ctx *ctx, int n_kinds, double *total_ms, int *launches);
+const char *rsvd_profile_kind_name(int kind);
+
 /* Bytes of device workspace that rsvd_run and every stage call need for a
  * problem of this size (one figure covers all of them). */
 int rsvd_workspace_bytes(rsvd_ctx *ctx, rsvd_dtype dtype, int64_t m, int64_t n,

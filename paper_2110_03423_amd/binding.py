@@ -32,6 +32,9 @@ PROTOTYPES = {
     "rsvd_destroy": [_VP],
     "rsvd_status_string": [_INT],
     "rsvd_last_hip_error": [_VP],
+    "rsvd_profile_enable": [_VP, _INT],
+    "rsvd_profile_read": [_VP, _INT, C.POINTER(C.c_double), C.POINTER(_INT)],
+    "rsvd_profile_kind_name": [_INT],
     "rsvd_workspace_bytes": [_VP, _INT, _I64, _I64, _INT, _INT, _INT, _INT, C.POINTER(_SZ)],
     "rsvd_run": [_VP, _VP, _INT, _INT, _I64, _I64, _VP, _I64, _INT, _INT, _INT, _U64,
                  _VP, _VP, _I64, _VP, _I64, _VP, _SZ, C.POINTER(_Info)],
@@ -51,6 +54,9 @@ def load_library():
     """Load librsvd_gfx950.so; raises if it has not been built (no fallback path exists)."""
     global _LIB
     if _LIB is None:
+        # torch first: it brings its own HIP runtime, and the library must bind to that one
+        # (loading the library first pulls in another copy and torch then sees no GPU)
+        import torch  # noqa: F401
         path = library_path()
         if not os.path.exists(path):
             raise RsvdError(-1, f"{path} is missing: build it with `python -m paper_2110_03423_amd.build`")
@@ -58,7 +64,7 @@ def load_library():
         for name, argtypes in PROTOTYPES.items():
             fn = getattr(lib, name)
             fn.argtypes = argtypes
-            fn.restype = C.c_char_p if name in ("rsvd_status_string", "rsvd_last_hip_error") else C.c_int
+            fn.restype = C.c_char_p if name in ("rsvd_status_string", "rsvd_last_hip_error", "rsvd_profile_kind_name") else C.c_int
         _LIB = lib
     return _LIB
 
@@ -110,6 +116,17 @@ class Rsvd:
 
     def _stream(self):
         return C.c_void_p(self.torch.cuda.current_stream(self.device).cuda_stream)
+
+    def rsvd_profile_enable(self, on):
+        self._check(self.lib.rsvd_profile_enable(self.h, int(on)))
+
+    def rsvd_profile_read(self):
+        """{kernel class name: (total ms, launches)} since the last read."""
+        n = 12
+        ms = (C.c_double * n)()
+        cnt = (C.c_int * n)()
+        self._check(self.lib.rsvd_profile_read(self.h, n, ms, cnt))
+        return {self.lib.rsvd_profile_kind_name(i).decode(): (ms[i], cnt[i]) for i in range(n) if cnt[i] > 0}
 
     def workspace_bytes(self, dtype, m, n, k, p, q=0, job=JOB_SUV):
         out = C.c_size_t()

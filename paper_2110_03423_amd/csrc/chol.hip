@@ -12,91 +12,150 @@
 
 namespace rsvd {
 
-hipError_t gemm_launch_f64(const rsvd_ctx *ctx, hipStream_t s, const GemmDesc &d);
+hipError_t gemm_launch_f64(rsvd_ctx *ctx, hipStream_t s, const GemmDesc &d);
 
-constexpr int kCholThreads = 1024;
-
-// One workgroup factors the nb x nb block at G (leading dimension ldg) held in LDS.
-// S (stride nb+1): on exit the upper triangle holds R, the strict lower triangle
-// holds Z = R^-T (row i, columns < i) and dinv[i] = Z[i][i] = 1 / R[i][i].
-//   g0    : original squared column norms for the pivot test, or NULL to use diag(G)
-//   Rinv  : nb x nb block of R^-1 written at Rinv (ld ldri), type TOut, full block
-//           (zeros below the diagonal)
+// One workgroup of TG x TG threads factors an nb x nb block (nb <= TG * NR) that
+// it holds in registers: thread (ty, tx) owns the elements (ty + TG a, tx + TG b).
+// The block is the sum of n_parts matrices spaced part_stride elements apart
+// (split-K partial Gram matrices are added here, in a fixed order).
+// Right-looking elimination, one step per column j: the owners of row j publish
+// it through a double-buffered LDS line (one barrier per step), every thread then
+// updates its own elements.  The same pass carries Z = R^-T along: rows of Z live
+// in the strict lower triangle, its diagonal 1 / R[j][j] in dinv.
+//   g0    : original squared column norms for the pivot test, or NULL to use the diagonal
+//   Rinv  : nb x nb block of R^-1 (ld ldri, type TOut, zeros below the diagonal)
 //   R     : same for R in fp64 (ld ldr), or NULL
-//   dead  : nb flags
-template <typename TOut>
-__global__ __launch_bounds__(kCholThreads) void chol_block_kernel(const double *__restrict__ G, int64_t ldg,
-                                                                  int nb, const double *__restrict__ g0,
-                                                                  double tau, TOut *__restrict__ Rinv,
-                                                                  int64_t ldri, double *__restrict__ R,
-                                                                  int64_t ldr, int *__restrict__ dead,
-                                                                  DevInfo *info) {
-  extern __shared__ double lds[];
-  const int st = nb + 1;
-  double *S = lds;                 // nb * st
-  double *dinv = S + nb * st;      // nb
-  double *d0 = dinv + nb;          // nb
+//   dead  : nb flags (1 = pivot <= tau * original squared norm)
+template <typename TOut, int TG, int NR>
+__global__ __launch_bounds__(TG * TG) void chol_block_kernel(const double *__restrict__ G, int64_t ldg,
+                                                              int n_parts, int64_t part_stride, int nb,
+                                                              const double *__restrict__ g0, double tau,
+                                                              TOut *__restrict__ Rinv, int64_t ldri,
+                                                              double *__restrict__ R, int64_t ldr,
+                                                              int *__restrict__ dead, DevInfo *info) {
+  constexpr int LMAX = TG * NR;
+  __shared__ double rowbuf[2][LMAX];
+  __shared__ double dinv[LMAX];
+  __shared__ double d0[LMAX];
   __shared__ int n_dead, bad;
-  const int tid = threadIdx.x, nt = blockDim.x;
-  const int tx = tid & 63, ty = tid >> 6, nwave = nt >> 6;
+  const int tid = threadIdx.x;
+  const int tx = tid % TG, ty = tid / TG;
+  double S[NR][NR];
 
   if (tid == 0) { n_dead = 0; bad = 0; }
-  for (int idx = tid; idx < nb * nb; idx += nt) {
-    const int r = idx / nb, c = idx - r * nb;
-    S[r * st + c] = G[(int64_t)r * ldg + c];
+#pragma unroll
+  for (int a = 0; a < NR; ++a)
+#pragma unroll
+    for (int b = 0; b < NR; ++b) S[a][b] = 0.0;
+  // all NR*NR loads of a group of four parts are issued before they are added, so the
+  // memory latency is paid once per group and not once per element
+  constexpr int UB = (TG * TG > 256 && NR > 3) ? 2 : 4;   // parts per batch, bounded by the register budget
+  for (int s0 = 0; s0 < n_parts; s0 += UB) {
+    double v[UB][NR][NR];
+#pragma unroll
+    for (int u = 0; u < UB; ++u)
+#pragma unroll
+      for (int a = 0; a < NR; ++a)
+#pragma unroll
+        for (int b = 0; b < NR; ++b) {
+          const int i = ty + TG * a, c = tx + TG * b;
+          v[u][a][b] = (s0 + u < n_parts && i < nb && c < nb)
+                           ? G[(int64_t)(s0 + u) * part_stride + (int64_t)i * ldg + c] : 0.0;
+        }
+#pragma unroll
+    for (int u = 0; u < UB; ++u)
+#pragma unroll
+      for (int a = 0; a < NR; ++a)
+#pragma unroll
+        for (int b = 0; b < NR; ++b) S[a][b] += v[u][a][b];
   }
-  __syncthreads();
-  for (int j = tid; j < nb; j += nt) {
-    const double d = (g0 != nullptr) ? g0[j] : S[j * st + j];
-    d0[j] = d;
-    if (!(fabs(d) <= 1.79e308)) bad = 1;      // NaN or Inf
-  }
-  __syncthreads();
+  __syncthreads();                       // n_dead / bad initialised
+#pragma unroll
+  for (int a = 0; a < NR; ++a)
+#pragma unroll
+    for (int b = 0; b < NR; ++b) {
+      const int i = ty + TG * a, c = tx + TG * b;
+      if (i == c && i < nb) {
+        const double d = (g0 != nullptr) ? g0[i] : S[a][b];
+        d0[i] = d;
+        if (!(fabs(d) <= 1.79e308)) bad = 1;      // NaN or Inf
+      }
+    }
 
   for (int j = 0; j < nb; ++j) {
-    const double d = S[j * st + j];
-    const bool is_dead = !(d > tau * d0[j]) || !(d0[j] > 0.0);
+    double *buf = rowbuf[j & 1];
+#pragma unroll
+    for (int a = 0; a < NR; ++a)
+      if (ty + TG * a == j) {
+#pragma unroll
+        for (int b = 0; b < NR; ++b) {
+          const int c = tx + TG * b;
+          if (c < nb) buf[c] = S[a][b];
+        }
+      }
+    __syncthreads();
+    const double d = buf[j], dj0 = d0[j];
+    const bool is_dead = !(d > tau * dj0) || !(dj0 > 0.0);
     const double rjj = is_dead ? 0.0 : sqrt(d);
     const double rinv = is_dead ? 0.0 : 1.0 / rjj;
-    __syncthreads();                       // everyone has read the pivot
-    // scale row j: R[j][j+1:] and Z[j][:j]
-    for (int c = tid; c < nb; c += nt) {
-      if (c == j) {
-        S[j * st + j] = rjj;
-        dinv[j] = rinv;
-        dead[j] = is_dead ? 1 : 0;
-        if (is_dead) n_dead += 1;          // single writer per step
-      } else {
-        S[j * st + c] *= rinv;
-      }
+    double rowc[NR], rowi[NR];
+#pragma unroll
+    for (int b = 0; b < NR; ++b) {
+      const int c = tx + TG * b;
+      rowc[b] = (c < nb) ? buf[c] * rinv : 0.0;
     }
-    __syncthreads();
-    // rank-one update of the rows below: trailing part of G and rows of Z
-    for (int i = j + 1 + ty; i < nb; i += nwave) {
-      const double lij = S[j * st + i];
-      if (lij != 0.0) {
-        for (int c = tx; c < nb; c += 64) {
-          if (c < j)        S[i * st + c] -= lij * S[j * st + c];
-          else if (c == j)  S[i * st + c] = -lij * dinv[j];
-          else if (c >= i)  S[i * st + c] -= lij * S[j * st + c];
+#pragma unroll
+    for (int a = 0; a < NR; ++a) {
+      const int i = ty + TG * a;
+      rowi[a] = (i < nb) ? buf[i] * rinv : 0.0;
+    }
+#pragma unroll
+    for (int a = 0; a < NR; ++a) {
+      const int i = ty + TG * a;
+      if (i == j) {
+#pragma unroll
+        for (int b = 0; b < NR; ++b) {
+          const int c = tx + TG * b;
+          if (c == j) {
+            S[a][b] = rjj;
+            dinv[j] = rinv;
+            dead[j] = is_dead ? 1 : 0;
+            if (is_dead) n_dead += 1;            // single writer per step
+          } else {
+            S[a][b] = rowc[b];
+          }
         }
-      } else if (tx == 0) {
-        S[i * st + j] = 0.0;
+      } else if (i > j) {
+        const double lij = rowi[a];
+#pragma unroll
+        for (int b = 0; b < NR; ++b) {
+          const int c = tx + TG * b;
+          if (c == j)                S[a][b] = -lij * rinv;
+          else if (c < j || c >= i)  S[a][b] -= lij * rowc[b];
+        }
       }
     }
-    // next iteration starts with a barrier after the pivot read; one more here so
-    // the pivot read sees the finished update
-    __syncthreads();
   }
+  __syncthreads();
 
-  for (int idx = tid; idx < nb * nb; idx += nt) {
-    const int r = idx / nb, c = idx - r * nb;
-    double ri = 0.0, rr = 0.0;
-    if (r < c)       { ri = S[c * st + r]; rr = S[r * st + c]; }
-    else if (r == c) { ri = dinv[r];       rr = S[r * st + r]; }
-    Rinv[(int64_t)r * ldri + c] = (TOut)ri;
-    if (R != nullptr) R[(int64_t)r * ldr + c] = rr;
-  }
+#pragma unroll
+  for (int a = 0; a < NR; ++a)
+#pragma unroll
+    for (int b = 0; b < NR; ++b) {
+      const int i = ty + TG * a, c = tx + TG * b;
+      if (i < nb && c < nb) {
+        if (i < c) {
+          if (R != nullptr) R[(int64_t)i * ldr + c] = S[a][b];
+          Rinv[(int64_t)c * ldri + i] = (TOut)0;
+        } else if (i > c) {
+          if (R != nullptr) R[(int64_t)i * ldr + c] = 0.0;
+          Rinv[(int64_t)c * ldri + i] = (TOut)S[a][b];
+        } else {
+          if (R != nullptr) R[(int64_t)i * ldr + i] = S[a][b];
+          Rinv[(int64_t)i * ldri + i] = (TOut)dinv[i];
+        }
+      }
+    }
   if (tid == 0 && info != nullptr) {
     if (n_dead > 0) atomicAdd(&info->refilled, n_dead);
     if (bad) atomicMax(&info->status, (int)RSVD_ERR_NONFINITE);
@@ -136,50 +195,55 @@ __global__ void zero_ints_kernel(int *p, int n) {
 }
 
 int chol_max_block(const rsvd_ctx *ctx) {
-  // nb * (nb + 1) + 2 nb doubles of dynamic LDS, plus a little static
-  int nb = 128;
-  while (nb > 16 && ((size_t)nb * (nb + 1) + 2 * (size_t)nb) * 8 + 256 > ctx->lds_per_block) nb -= 16;
-  return nb;
+  (void)ctx;
+  return 128;      // 32 x 32 threads, 4 x 4 elements each
 }
 
 size_t chol_scratch_elems(const rsvd_ctx *ctx, int64_t l) {
   if (l <= chol_max_block(ctx)) return 0;
-  // blocked path: g0 (l) + fp64 R^-1 (l*l) + R (l*l) + product scratch (l*l)
-  return (size_t)l + 3 * (size_t)l * (size_t)l;
+  // blocked path: g0 (l, padded to even) + fp64 R^-1 (l*l) + R (l*l) + product scratch (l*l)
+  return (size_t)l + 1 + 3 * (size_t)l * (size_t)l;
 }
 
 template <typename TOut>
-static hipError_t launch_block(hipStream_t s, const double *G, int64_t ldg, int nb, const double *g0, double tau,
-                               TOut *Rinv, int64_t ldri, double *R, int64_t ldr, int *dead, DevInfo *info) {
-  const size_t lds = ((size_t)nb * (nb + 1) + 2 * (size_t)nb) * sizeof(double);
-  const int threads = nb <= 32 ? 256 : (nb <= 64 ? 512 : kCholThreads);
-  static bool attr_set = false;
-  if (!attr_set) {
-    (void)hipFuncSetAttribute(reinterpret_cast<const void *>(&chol_block_kernel<TOut>),
-                              hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 512);
-    (void)hipGetLastError();
-    attr_set = true;
+static hipError_t launch_block(hipStream_t s, const double *G, int64_t ldg, int n_parts, int64_t part_stride, int nb,
+                               const double *g0, double tau, TOut *Rinv, int64_t ldri, double *R, int64_t ldr,
+                               int *dead, DevInfo *info) {
+  if (nb <= 32) {
+    hipLaunchKernelGGL((chol_block_kernel<TOut, 16, 2>), dim3(1), dim3(256), 0, s, G, ldg, n_parts, part_stride, nb,
+                       g0, tau, Rinv, ldri, R, ldr, dead, info);
+  } else if (nb <= 64) {
+    hipLaunchKernelGGL((chol_block_kernel<TOut, 16, 4>), dim3(1), dim3(256), 0, s, G, ldg, n_parts, part_stride, nb,
+                       g0, tau, Rinv, ldri, R, ldr, dead, info);
+  } else if (nb <= 96) {
+    hipLaunchKernelGGL((chol_block_kernel<TOut, 32, 3>), dim3(1), dim3(1024), 0, s, G, ldg, n_parts, part_stride, nb,
+                       g0, tau, Rinv, ldri, R, ldr, dead, info);
+  } else {
+    hipLaunchKernelGGL((chol_block_kernel<TOut, 32, 4>), dim3(1), dim3(1024), 0, s, G, ldg, n_parts, part_stride, nb,
+                       g0, tau, Rinv, ldri, R, ldr, dead, info);
   }
-  hipLaunchKernelGGL((chol_block_kernel<TOut>), dim3(1), dim3(threads), lds, s, G, ldg, nb, g0, tau, Rinv, ldri, R,
-                     ldr, dead, info);
   return hipGetLastError();
 }
 
-hipError_t chol_inverse_launch(const rsvd_ctx *ctx, hipStream_t s, rsvd_dtype out_dtype, int64_t l, double *G,
-                               int64_t ldg, double tau, void *Rinv, double *R, int *dead, DevInfo *info,
-                               double *scratch, void *partial, size_t partial_bytes) {
+hipError_t chol_inverse_launch(rsvd_ctx *ctx, hipStream_t s, rsvd_dtype out_dtype, int64_t l, double *G,
+                               int64_t ldg, int n_parts, int64_t part_stride, double tau, void *Rinv, double *R,
+                               int *dead, DevInfo *info, double *scratch) {
   const int nbmax = chol_max_block(ctx);
   if (l <= nbmax) {
+    ProfScope ps(ctx, s, PK_CHOL);
     if (out_dtype == RSVD_F32)
-      return launch_block<float>(s, G, ldg, (int)l, nullptr, tau, (float *)Rinv, l, R, l, dead, info);
-    return launch_block<double>(s, G, ldg, (int)l, nullptr, tau, (double *)Rinv, l, R, l, dead, info);
+      return launch_block<float>(s, G, ldg, n_parts, part_stride, (int)l, nullptr, tau, (float *)Rinv, l, R, l, dead,
+                                 info);
+    return launch_block<double>(s, G, ldg, n_parts, part_stride, (int)l, nullptr, tau, (double *)Rinv, l, R, l, dead,
+                                info);
   }
+  if (n_parts != 1) return hipErrorInvalidValue;     // the blocked path wants the reduced matrix
 
   // Blocked right-looking factorisation; diagonal blocks by the kernel above,
   // panels and trailing updates by the fp64 GEMM.  Rf/Xf hold R and R^-1 in fp64.
   const int nb = 96 <= nbmax ? 96 : nbmax;
   double *g0 = scratch;
-  double *Xf = g0 + l;
+  double *Xf = g0 + ((l + 1) & ~(int64_t)1);
   double *Rf = Xf + l * l;
   double *T = Rf + l * l;
   hipError_t e;
@@ -191,8 +255,11 @@ hipError_t chol_inverse_launch(const rsvd_ctx *ctx, hipStream_t s, rsvd_dtype ou
     const int64_t b = (l - j0 < nb) ? (l - j0) : nb;
     const int64_t rest = l - j0 - b;
     // diagonal block: R_jj and X_jj = R_jj^-1
-    e = launch_block<double>(s, G + j0 * ldg + j0, ldg, (int)b, g0 + j0, tau, Xf + j0 * l + j0, l,
-                             Rf + j0 * l + j0, l, dead + j0, info);
+    {
+      ProfScope ps(ctx, s, PK_CHOL);
+      e = launch_block<double>(s, G + j0 * ldg + j0, ldg, 1, 0, (int)b, g0 + j0, tau, Xf + j0 * l + j0, l,
+                               Rf + j0 * l + j0, l, dead + j0, info);
+    }
     if (e != hipSuccess) return e;
     if (rest > 0) {
       // panel: R[j, rest] = X_jj^T G[j, rest]
@@ -228,7 +295,6 @@ hipError_t chol_inverse_launch(const rsvd_ctx *ctx, hipStream_t s, rsvd_dtype ou
       if ((e = gemm_launch_f64(ctx, s, c)) != hipSuccess) return e;
     }
   }
-  (void)partial; (void)partial_bytes;
   if (out_dtype == RSVD_F32) {
     hipLaunchKernelGGL((convert_matrix_kernel<float>), dim3(512), dim3(256), 0, s, Xf, l * l, (float *)Rinv);
   } else {

@@ -5,6 +5,8 @@
 #include <stddef.h>
 #include <stdint.h>
 
+#include <vector>
+
 #include "../../include/rsvd.h"
 
 struct rsvd_ctx {
@@ -12,6 +14,11 @@ struct rsvd_ctx {
   int cu_count;
   size_t lds_per_block;     // bytes of LDS one workgroup may use
   char hip_error[256];
+  // optional per-kernel timing (rsvd_profile_*): one event pair per launch
+  bool prof_on;
+  std::vector<hipEvent_t> prof_events;   // pairs: start, stop
+  std::vector<int> prof_kinds;           // one per pair
+  size_t prof_used;                      // pairs recorded since the last read
 };
 
 namespace rsvd {
@@ -21,6 +28,31 @@ constexpr int kWave = 64;
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 inline size_t dtype_size(rsvd_dtype d) { return d == RSVD_F32 ? 4 : 8; }
+
+// Kernel classes reported by the profiling interface.
+enum ProfKind {
+  PK_SKETCH = 0, PK_GEMM_AX, PK_GEMM_AX_REDUCE, PK_GEMM_ATX, PK_GEMM_ATX_REDUCE, PK_GRAM, PK_GRAM_REDUCE,
+  PK_CHOL, PK_APPLY, PK_JACOBI, PK_LIFT, PK_SMALL, PK_COUNT
+};
+
+// Brackets one kernel launch with a HIP event pair when profiling is on.
+struct ProfScope {
+  rsvd_ctx *ctx; hipStream_t s; hipEvent_t stop; bool active;
+  ProfScope(rsvd_ctx *c, hipStream_t st, int kind) : ctx(c), s(st), stop(nullptr), active(false) {
+    if (c == nullptr || !c->prof_on) return;
+    if (c->prof_used * 2 + 2 > c->prof_events.size()) {
+      hipEvent_t a, b;
+      if (hipEventCreate(&a) != hipSuccess || hipEventCreate(&b) != hipSuccess) return;
+      c->prof_events.push_back(a); c->prof_events.push_back(b); c->prof_kinds.push_back(kind);
+    }
+    c->prof_kinds[c->prof_used] = kind;
+    (void)hipEventRecord(c->prof_events[c->prof_used * 2], st);
+    stop = c->prof_events[c->prof_used * 2 + 1];
+    c->prof_used += 1;
+    active = true;
+  }
+  ~ProfScope() { if (active) (void)hipEventRecord(stop, s); }
+};
 
 // Device-side diagnostics block (4 x int32), same field order as rsvd_info.
 struct DevInfo {
@@ -50,13 +82,19 @@ struct GemmDesc {
   uint64_t seed = 0; uint32_t refill_stream = 0; double refill_scale = 1.0; int64_t refill_ld = 0;
   void *partial = nullptr; size_t partial_bytes = 0;   // split-K scratch
   int force_splits = 0;                                 // 0 = heuristic
+  int prof_kind = PK_SMALL;                             // class of the main kernel; the split-K reduction is +1
+  // skip_reduce: leave split-K partials ([splits][M][N], accumulator type) unreduced in
+  // `partial` for the consumer to add up; *splits_out receives their number (1 = C was written).
+  int skip_reduce = 0;
+  int skip_reduce_max = 1 << 30;                        // ... only when there are at most this many partials
+  int *splits_out = nullptr;
 };
 
 enum GemmKind { GEMM_F32 = 0, GEMM_F64 = 1, GEMM_F32_ACC64 = 2 };  // last: fp32 inputs, fp64 MFMA and output
 
 // Bytes of split-K scratch the heuristic would use for this shape.
 size_t gemm_partial_bytes(const rsvd_ctx *ctx, GemmKind kind, int trans_a, int64_t M, int64_t N, int64_t K);
-hipError_t gemm_launch(const rsvd_ctx *ctx, hipStream_t s, GemmKind kind, const GemmDesc &d);
+hipError_t gemm_launch(rsvd_ctx *ctx, hipStream_t s, GemmKind kind, const GemmDesc &d);
 
 // ---------------------------------------------------------------- sketch
 hipError_t sketch_launch(hipStream_t s, rsvd_dtype dtype, uint64_t seed, uint32_t stream_id,
@@ -75,9 +113,11 @@ int chol_max_block(const rsvd_ctx *ctx);
 //   dead (l ints), info->refilled += number of flagged columns
 //   scratch: fp64 scratch of at least chol_scratch_elems(l) elements (blocked path)
 size_t chol_scratch_elems(const rsvd_ctx *ctx, int64_t l);
-hipError_t chol_inverse_launch(const rsvd_ctx *ctx, hipStream_t s, rsvd_dtype out_dtype, int64_t l,
-                               double *G, int64_t ldg, double tau, void *Rinv, double *R, int *dead,
-                               DevInfo *info, double *scratch, void *partial, size_t partial_bytes);
+//   G may be given as n_parts matrices part_stride elements apart whose sum is the
+//   Gram matrix (unreduced split-K partials; single-block orders only).
+hipError_t chol_inverse_launch(rsvd_ctx *ctx, hipStream_t s, rsvd_dtype out_dtype, int64_t l,
+                               double *G, int64_t ldg, int n_parts, int64_t part_stride, double tau,
+                               void *Rinv, double *R, int *dead, DevInfo *info, double *scratch);
 // Rb = R2 * R1 for upper triangular fp64 l x l matrices (ld l).
 hipError_t triu_product_launch(hipStream_t s, int64_t l, const double *R2, const double *R1, double *Rb);
 hipError_t zero_ints_launch(hipStream_t s, int *p, int n);
@@ -88,7 +128,7 @@ int jacobi_max_lds_order(const rsvd_ctx *ctx, rsvd_dtype dtype);
 size_t jacobi_scratch_bytes(const rsvd_ctx *ctx, rsvd_dtype dtype, int64_t l);
 // One-sided Jacobi SVD  M = X diag(sigma) W^T  of the l x l row-major matrix M
 // (ld l; fp64 when m_is_f64 else `dtype`).  Outputs in `dtype`, sigma descending.
-hipError_t jacobi_launch(const rsvd_ctx *ctx, hipStream_t s, rsvd_dtype dtype, int64_t l,
+hipError_t jacobi_launch(rsvd_ctx *ctx, hipStream_t s, rsvd_dtype dtype, int64_t l,
                          const void *M, int m_is_f64, void *sigma, void *X, void *W,
                          DevInfo *info, void *scratch, size_t scratch_bytes);
 

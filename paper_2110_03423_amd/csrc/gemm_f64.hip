@@ -5,7 +5,7 @@ namespace rsvd {
 size_t gemm_partial_bytes_f64(const rsvd_ctx *ctx, int64_t M, int64_t N, int64_t K) {
   return GemmDispatch<double, double, double>::partial_bytes(ctx, M, N, K);
 }
-hipError_t gemm_launch_f64(const rsvd_ctx *ctx, hipStream_t s, const GemmDesc &d) {
+hipError_t gemm_launch_f64(rsvd_ctx *ctx, hipStream_t s, const GemmDesc &d) {
   return GemmDispatch<double, double, double>::launch(ctx, s, d);
 }
 }  // namespace rsvd

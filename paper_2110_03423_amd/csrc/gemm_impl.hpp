@@ -307,7 +307,7 @@ struct GemmDispatch {
     return c.splits > 1 ? (size_t)c.splits * (size_t)M * (size_t)N * sizeof(TAcc) : 0;
   }
 
-  static hipError_t launch(const rsvd_ctx *ctx, hipStream_t s, const GemmDesc &d) {
+  static hipError_t launch(rsvd_ctx *ctx, hipStream_t s, const GemmDesc &d) {
     if (d.M <= 0 || d.N <= 0) return hipSuccess;
     const TileChoice t = choose_tile(d.M, d.N);
     SplitChoice c = choose_split(ctx, t, d.M, d.N, d.K, d.force_splits);
@@ -328,9 +328,15 @@ struct GemmDispatch {
     const int64_t a_contig = d.trans_a ? d.M : d.K;
     const bool vec = ((uintptr_t)d.A % 16 == 0) && ((uintptr_t)d.B % 16 == 0) && d.lda % V == 0 &&
                      d.ldb % V == 0 && a_contig % V == 0 && d.N % V == 0;
-    hipError_t e = d.trans_a ? by_tile<true>(s, P, t, vec) : by_tile<false>(s, P, t, vec);
+    hipError_t e;
+    {
+      ProfScope ps(ctx, s, d.prof_kind);
+      e = d.trans_a ? by_tile<true>(s, P, t, vec) : by_tile<false>(s, P, t, vec);
+    }
     if (e != hipSuccess) return e;
-    if (c.splits > 1) {
+    if (d.splits_out != nullptr) *d.splits_out = c.splits;
+    if (c.splits > 1 && !(d.skip_reduce && c.splits <= d.skip_reduce_max)) {
+      ProfScope ps(ctx, s, d.prof_kind + 1);
       int64_t blocks = ceil_div(d.M * d.N, 256);
       if (blocks > 8192) blocks = 8192;
       hipLaunchKernelGGL((splitk_reduce_kernel<TIn, TAcc, TOut>), dim3((unsigned)blocks), dim3(256), 0, s, P);

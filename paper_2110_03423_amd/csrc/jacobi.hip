@@ -10,6 +10,11 @@
 //
 // Stopping rule (the paper gives none): a sweep in which every pair satisfies
 // |a_p . a_q| <= tol * ||a_p|| * ||a_q||, tol = eps * sqrt(l); at most 30 sweeps.
+// A column whose norm has fallen below eps * ||M||_F counts as zero and is no
+// longer rotated (rotating it would change its partner by less than the
+// rounding level); without this floor the surplus columns of a rank-deficient M
+// keep shrinking by a factor eps per sweep until they underflow.  Its singular
+// value is reported as that norm and its column of X is set to zero.
 #include "common.hpp"
 
 namespace rsvd {
@@ -34,17 +39,27 @@ __device__ __forceinline__ void tournament_pair(int n2, int r, int i, int &a, in
 }
 
 // Rotate columns p, q of M (and of J) held column-major with stride ldm; the G
-// lanes of one group share the work.  Returns true when a rotation was applied.
-template <typename T, int G>
-__device__ __forceinline__ bool rotate_pair(T *Mc, T *Jc, int ldm, int rows_m, int rows_j, int p, int q,
-                                            int lg, T tol) {
+// lanes of one group share the work, each holding up to RPL elements of either
+// column in registers between the inner products and the update.  Returns true
+// when a rotation was applied.
+template <typename T, int G, int RPL>
+__device__ __forceinline__ bool rotate_pair(T *Mc, T *Jc, int ldm, int rows, int p, int q, int lg, T tol,
+                                            T floor2) {
   T *mp = Mc + p * ldm, *mq = Mc + q * ldm;
+  T x[RPL], y[RPL];
   T alpha = 0, beta = 0, gamma = 0;
-  for (int i = lg; i < rows_m; i += G) {
-    const T x = mp[i], y = mq[i];
-    alpha += x * x;
-    beta += y * y;
-    gamma += x * y;
+#pragma unroll
+  for (int r = 0; r < RPL; ++r) {
+    const int i = lg + G * r;
+    const bool ok = i < rows;
+    x[r] = ok ? mp[i] : (T)0;
+    y[r] = ok ? mq[i] : (T)0;
+  }
+#pragma unroll
+  for (int r = 0; r < RPL; ++r) {
+    alpha += x[r] * x[r];
+    beta += y[r] * y[r];
+    gamma += x[r] * y[r];
   }
 #pragma unroll
   for (int off = G / 2; off > 0; off >>= 1) {
@@ -52,8 +67,18 @@ __device__ __forceinline__ bool rotate_pair(T *Mc, T *Jc, int ldm, int rows_m, i
     beta += __shfl_xor(beta, off, G);
     gamma += __shfl_xor(gamma, off, G);
   }
-  const T limit = tol * sqrt(alpha * beta);
-  if (!(fabs(gamma) > limit) || gamma == (T)0) return false;
+  if (alpha <= floor2 || beta <= floor2) return false;
+  const T limit = tol * sqrt(alpha) * sqrt(beta);
+  if (!(fabs(gamma) > limit)) return false;
+  T *jp = Jc + p * ldm, *jq = Jc + q * ldm;
+  T u[RPL], v[RPL];
+#pragma unroll
+  for (int r = 0; r < RPL; ++r) {
+    const int i = lg + G * r;
+    const bool ok = i < rows;
+    u[r] = ok ? jp[i] : (T)0;
+    v[r] = ok ? jq[i] : (T)0;
+  }
   const T zeta = (beta - alpha) / ((T)2 * gamma);
   T t;
   if (fabs(zeta) > (T)1e7) {
@@ -62,16 +87,15 @@ __device__ __forceinline__ bool rotate_pair(T *Mc, T *Jc, int ldm, int rows_m, i
     t = (zeta >= 0 ? (T)1 : (T)-1) / (fabs(zeta) + sqrt((T)1 + zeta * zeta));
   }
   const T c = (T)1 / sqrt((T)1 + t * t), s = c * t;
-  for (int i = lg; i < rows_m; i += G) {
-    const T x = mp[i], y = mq[i];
-    mp[i] = c * x - s * y;
-    mq[i] = s * x + c * y;
-  }
-  T *jp = Jc + p * ldm, *jq = Jc + q * ldm;
-  for (int i = lg; i < rows_j; i += G) {
-    const T x = jp[i], y = jq[i];
-    jp[i] = c * x - s * y;
-    jq[i] = s * x + c * y;
+#pragma unroll
+  for (int r = 0; r < RPL; ++r) {
+    const int i = lg + G * r;
+    if (i < rows) {
+      mp[i] = c * x[r] - s * y[r];
+      mq[i] = s * x[r] + c * y[r];
+      jp[i] = c * u[r] - s * v[r];
+      jq[i] = s * u[r] + c * v[r];
+    }
   }
   return true;
 }
@@ -86,15 +110,25 @@ __global__ __launch_bounds__(1024) void jacobi_lds_kernel(const TIn *__restrict_
   T *nrm = Jc + (size_t)l * ldm;
   int *rnk = reinterpret_cast<int *>(nrm + l);
   __shared__ int rotations;
+  __shared__ T wave_sum[16];
 
   const int tid = threadIdx.x, nt = blockDim.x;
+  T fro2 = 0;
   for (int idx = tid; idx < l * l; idx += nt) {
     const int r = idx / l, c = idx - r * l;
-    Mc[c * ldm + r] = (T)M[idx];
+    const T v = (T)M[idx];
+    Mc[c * ldm + r] = v;
     Jc[c * ldm + r] = (r == c) ? (T)1 : (T)0;
+    fro2 += v * v;
   }
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) fro2 += __shfl_xor(fro2, off, 64);
+  if ((tid & 63) == 0) wave_sum[tid >> 6] = fro2;
   if (tid == 0) rotations = 0;
   __syncthreads();
+  fro2 = 0;
+  for (int w = 0; w < (nt >> 6); ++w) fro2 += wave_sum[w];
+  const T floor2 = Eps<T>::value * Eps<T>::value * fro2;
 
   const int n2 = l + (l & 1), npairs = n2 / 2;
   const int group = tid / G, lg = tid % G, ngroups = nt / G;
@@ -109,7 +143,7 @@ __global__ __launch_bounds__(1024) void jacobi_lds_kernel(const TIn *__restrict_
         tournament_pair(n2, r, pi, a, b);
         if (a < l && b < l) {
           const int p = a < b ? a : b, q = a < b ? b : a;
-          const bool rot = rotate_pair<T, G>(Mc, Jc, ldm, l, l, p, q, lg, tol);
+          const bool rot = rotate_pair<T, G, (128 + G - 1) / G>(Mc, Jc, ldm, l, p, q, lg, tol, floor2);
           if (rot && lg == 0) atomicAdd(&rotations, 1);
         }
       }
@@ -142,7 +176,7 @@ __global__ __launch_bounds__(1024) void jacobi_lds_kernel(const TIn *__restrict_
     const int r = idx / l, c = idx - r * l;
     const int dst = r * l + rnk[c];
     const T s = nrm[c];
-    X[dst] = (s > (T)0) ? Mc[c * ldm + r] / s : (T)0;
+    X[dst] = (s * s > floor2) ? Mc[c * ldm + r] / s : (T)0;
     W[dst] = Jc[c * ldm + r];
   }
   if (tid == 0 && info != nullptr) {
@@ -159,8 +193,8 @@ static size_t jacobi_lds_bytes(rsvd_dtype dtype, int64_t l) {
 
 int jacobi_max_lds_order(const rsvd_ctx *ctx, rsvd_dtype dtype) {
   int l = 2;
-  while (jacobi_lds_bytes(dtype, l + 1) + 512 <= ctx->lds_per_block) ++l;
-  return l;
+  while (l < 128 && jacobi_lds_bytes(dtype, l + 1) + 512 <= ctx->lds_per_block) ++l;
+  return l;      // 128 = lanes per pair x elements each lane keeps in registers
 }
 
 size_t jacobi_scratch_bytes(const rsvd_ctx *ctx, rsvd_dtype dtype, int64_t l) {
@@ -189,12 +223,11 @@ static hipError_t launch_lds_g(hipStream_t s, int nt, int g, size_t lds, const v
   switch (g) {
     case 64: return launch_lds<T, TIn, 64>(s, nt, lds, M, l, sigma, X, W, info);
     case 32: return launch_lds<T, TIn, 32>(s, nt, lds, M, l, sigma, X, W, info);
-    case 16: return launch_lds<T, TIn, 16>(s, nt, lds, M, l, sigma, X, W, info);
-    default: return launch_lds<T, TIn, 8>(s, nt, lds, M, l, sigma, X, W, info);
+    default: return launch_lds<T, TIn, 16>(s, nt, lds, M, l, sigma, X, W, info);
   }
 }
 
-hipError_t jacobi_launch(const rsvd_ctx *ctx, hipStream_t s, rsvd_dtype dtype, int64_t l, const void *M,
+hipError_t jacobi_launch(rsvd_ctx *ctx, hipStream_t s, rsvd_dtype dtype, int64_t l, const void *M,
                          int m_is_f64, void *sigma, void *X, void *W, DevInfo *info, void *scratch,
                          size_t scratch_bytes) {
   (void)scratch; (void)scratch_bytes;
@@ -202,8 +235,9 @@ hipError_t jacobi_launch(const rsvd_ctx *ctx, hipStream_t s, rsvd_dtype dtype, i
   const int nt = l > 64 ? 1024 : (l > 32 ? 512 : 256);
   const int npairs = (int)((l + 1) / 2);
   int g = 64;
-  while (g > 8 && nt / g < npairs) g /= 2;
+  while (g > 16 && nt / g < npairs) g /= 2;
   const size_t lds = jacobi_lds_bytes(dtype, l);
+  ProfScope ps(ctx, s, PK_JACOBI);
   if (dtype == RSVD_F32) {
     if (m_is_f64) return launch_lds_g<float, double>(s, nt, g, lds, M, (int)l, sigma, X, W, info);
     return launch_lds_g<float, float>(s, nt, g, lds, M, (int)l, sigma, X, W, info);

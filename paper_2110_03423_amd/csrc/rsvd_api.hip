@@ -14,9 +14,9 @@ namespace rsvd {
 size_t gemm_partial_bytes_f32(const rsvd_ctx *, int64_t, int64_t, int64_t);
 size_t gemm_partial_bytes_f64(const rsvd_ctx *, int64_t, int64_t, int64_t);
 size_t gemm_partial_bytes_f32acc64(const rsvd_ctx *, int64_t, int64_t, int64_t);
-hipError_t gemm_launch_f32(const rsvd_ctx *, hipStream_t, const GemmDesc &);
-hipError_t gemm_launch_f64(const rsvd_ctx *, hipStream_t, const GemmDesc &);
-hipError_t gemm_launch_f32acc64(const rsvd_ctx *, hipStream_t, const GemmDesc &);
+hipError_t gemm_launch_f32(rsvd_ctx *, hipStream_t, const GemmDesc &);
+hipError_t gemm_launch_f64(rsvd_ctx *, hipStream_t, const GemmDesc &);
+hipError_t gemm_launch_f32acc64(rsvd_ctx *, hipStream_t, const GemmDesc &);
 
 size_t gemm_partial_bytes(const rsvd_ctx *ctx, GemmKind kind, int trans_a, int64_t M, int64_t N, int64_t K) {
   (void)trans_a;
@@ -27,7 +27,7 @@ size_t gemm_partial_bytes(const rsvd_ctx *ctx, GemmKind kind, int trans_a, int64
   }
 }
 
-hipError_t gemm_launch(const rsvd_ctx *ctx, hipStream_t s, GemmKind kind, const GemmDesc &d) {
+hipError_t gemm_launch(rsvd_ctx *ctx, hipStream_t s, GemmKind kind, const GemmDesc &d) {
   switch (kind) {
     case GEMM_F32: return gemm_launch_f32(ctx, s, d);
     case GEMM_F64: return gemm_launch_f64(ctx, s, d);
@@ -118,10 +118,15 @@ static int fail_hip(rsvd_ctx *ctx, hipError_t e, const char *where) {
 
 // ---------------------------------------------------------------- building blocks
 
-// Y (rows x l, ld ldy) -> Q in place by two rounds of CholeskyQR; `tmp` is a
-// rows x l panel (ld l).  Rout (fp64, l x l) receives R with Y = Q R, or NULL.
+// Y (rows x l, ld ldy) -> Q by `rounds` (1 or 2) rounds of CholeskyQR; `tmp` is a
+// rows x l panel (ld l).  Two rounds leave Q in Y with columns orthonormal to
+// working precision.  One round leaves it in `tmp`: a well-conditioned basis of
+// the same range (orthonormal to about cond(Y) * eps), which is all the power
+// scheme needs between two products.  Rout (fp64, l x l, two rounds only)
+// receives R with Y = Q R, or NULL.
 static int orthonormalize(rsvd_ctx *ctx, hipStream_t s, rsvd_dtype dtype, const Ws &w, int64_t rows, int64_t l,
-                          void *Y, int64_t ldy, void *tmp, double *Rout, uint64_t seed, uint32_t refill_stream) {
+                          void *Y, int64_t ldy, void *tmp, double *Rout, uint64_t seed, uint32_t refill_stream,
+                          int rounds = 2) {
   const GemmKind kind = dtype == RSVD_F32 ? GEMM_F32 : GEMM_F64;
   const GemmKind gram = dtype == RSVD_F32 ? GEMM_F32_ACC64 : GEMM_F64;
   const Layout &L = w.L;
@@ -129,17 +134,24 @@ static int orthonormalize(rsvd_ctx *ctx, hipStream_t s, rsvd_dtype dtype, const 
   const double tau = 32.0 * 2.220446049250313e-16 * ((double)l + sqrt((double)rows));
   void *src = Y; int64_t lds_ = ldy;
   void *dst = tmp; int64_t ldd = l;
-  for (int round = 0; round < 2; ++round) {
+  for (int round = 0; round < rounds; ++round) {
     GemmDesc g;
     g.trans_a = 1; g.M = l; g.N = l; g.K = rows;
     g.A = src; g.lda = lds_; g.B = src; g.ldb = lds_;
     g.C = w.at<double>(L.G); g.ldc = l;
     g.partial = w.at<void>(L.partial); g.partial_bytes = L.partial_bytes;
+    g.prof_kind = PK_GRAM;
+    // small orders: the Cholesky kernel adds the split-K partials itself
+    int splits = 1;
+    g.skip_reduce = (l <= chol_max_block(ctx)) ? 1 : 0;
+    g.skip_reduce_max = 4;          // more partials than this are cheaper to add in their own kernel
+    g.splits_out = &splits;
     RSVD_TRY(gemm_launch(ctx, s, gram, g), "gram");
     double *R = Rout ? w.at<double>(round == 0 ? L.R1 : L.R2) : nullptr;
-    RSVD_TRY(chol_inverse_launch(ctx, s, dtype, l, w.at<double>(L.G), l, tau, w.at<void>(L.Rinv), R,
-                                 w.at<int>(L.dead), w.at<DevInfo>(L.info), w.at<double>(L.chol_scratch),
-                                 w.at<void>(L.partial), L.partial_bytes),
+    const bool parts = g.skip_reduce && splits > 1 && splits <= g.skip_reduce_max;
+    RSVD_TRY(chol_inverse_launch(ctx, s, dtype, l, parts ? w.at<double>(L.partial) : w.at<double>(L.G), l,
+                                 parts ? splits : 1, l * l, tau, w.at<void>(L.Rinv), R, w.at<int>(L.dead),
+                                 w.at<DevInfo>(L.info), w.at<double>(L.chol_scratch)),
              "cholesky");
     GemmDesc a;
     a.M = rows; a.N = l; a.K = l;
@@ -148,18 +160,23 @@ static int orthonormalize(rsvd_ctx *ctx, hipStream_t s, rsvd_dtype dtype, const 
     a.dead = w.at<int>(L.dead); a.seed = seed; a.refill_stream = refill_stream + (uint32_t)round;
     a.refill_scale = 1.0 / sqrt((double)rows); a.refill_ld = l;
     a.force_splits = 1;
+    a.prof_kind = PK_APPLY;
     RSVD_TRY(gemm_launch(ctx, s, kind, a), "apply R^-1");
     void *tp = src; src = dst; dst = tp;
     int64_t tl = lds_; lds_ = ldd; ldd = tl;
   }
-  if (Rout) RSVD_TRY(triu_product_launch(s, l, w.at<double>(L.R2), w.at<double>(L.R1), Rout), "R product");
+  if (Rout) {
+    ProfScope ps(ctx, s, PK_SMALL);
+    RSVD_TRY(triu_product_launch(s, l, w.at<double>(L.R2), w.at<double>(L.R1), Rout), "R product");
+  }
   return 0;
 }
 
 static int product(rsvd_ctx *ctx, hipStream_t s, rsvd_dtype dtype, const Ws &w, int trans_a, int64_t M, int64_t N,
                    int64_t K, const void *A, int64_t lda, const void *B, int64_t ldb, void *C, int64_t ldc,
-                   int trans_c, bool allow_split) {
+                   int trans_c, bool allow_split, int prof_kind) {
   GemmDesc d;
+  d.prof_kind = prof_kind;
   d.trans_a = trans_a; d.trans_c = trans_c; d.M = M; d.N = N; d.K = K;
   d.A = A; d.lda = lda; d.B = B; d.ldb = ldb; d.C = C; d.ldc = ldc;
   if (allow_split) { d.partial = w.at<void>(w.L.partial); d.partial_bytes = w.L.partial_bytes; }
@@ -220,11 +237,15 @@ int rsvd_create(rsvd_ctx **out, int device) {
   if (lds < 32 * 1024) lds = 32 * 1024;
   c->lds_per_block = lds;
   c->hip_error[0] = 0;
+  c->prof_on = false;
+  c->prof_used = 0;
   *out = c;
   return 0;
 }
 
 int rsvd_destroy(rsvd_ctx *ctx) {
+  if (ctx != nullptr)
+    for (hipEvent_t e : ctx->prof_events) (void)hipEventDestroy(e);
   delete ctx;
   return 0;
 }
@@ -241,6 +262,36 @@ const char *rsvd_status_string(int code) {
 }
 
 const char *rsvd_last_hip_error(const rsvd_ctx *ctx) { return ctx ? ctx->hip_error : ""; }
+
+int rsvd_profile_enable(rsvd_ctx *ctx, int on) {
+  if (ctx == nullptr) return -1;
+  ctx->prof_on = on != 0;
+  ctx->prof_used = 0;
+  return 0;
+}
+
+const char *rsvd_profile_kind_name(int kind) {
+  static const char *names[PK_COUNT] = {"sketch", "gemm_ax", "gemm_ax_reduce", "gemm_atx", "gemm_atx_reduce",
+                                        "gram", "gram_reduce", "cholesky", "apply_rinv", "jacobi", "lift", "small"};
+  return (kind >= 0 && kind < PK_COUNT) ? names[kind] : "?";
+}
+
+int rsvd_profile_read(rsvd_ctx *ctx, int n_kinds, double *total_ms, int *launches) {
+  if (ctx == nullptr) return -1;
+  if (n_kinds < PK_COUNT) return -2;
+  if (total_ms == nullptr) return -3;
+  if (launches == nullptr) return -4;
+  for (int i = 0; i < n_kinds; ++i) { total_ms[i] = 0.0; launches[i] = 0; }
+  for (size_t i = 0; i < ctx->prof_used; ++i) {
+    float ms = 0.f;
+    RSVD_TRY(hipEventSynchronize(ctx->prof_events[2 * i + 1]), "event sync");
+    RSVD_TRY(hipEventElapsedTime(&ms, ctx->prof_events[2 * i], ctx->prof_events[2 * i + 1]), "event time");
+    total_ms[ctx->prof_kinds[i]] += ms;
+    launches[ctx->prof_kinds[i]] += 1;
+  }
+  ctx->prof_used = 0;
+  return 0;
+}
 
 int rsvd_workspace_bytes(rsvd_ctx *ctx, rsvd_dtype dtype, int64_t m, int64_t n, int k, int p, int q, rsvd_job job,
                          size_t *bytes) {
@@ -290,33 +341,43 @@ int rsvd_run(rsvd_ctx *ctx, void *stream, rsvd_dtype dtype, rsvd_job job, int64_
 
   RSVD_TRY(zero_ints_launch(s, w.at<int>(L.info), 4), "zero info");
   // step 1
-  RSVD_TRY(sketch_launch(s, dtype, seed, 0u, n, l, bN0, l), "sketch");
-  // step 2: Y = A Omega, then q rounds of Z = A^T Q, Y = A Z, each re-orthonormalised
-  if ((rc = product(ctx, s, dtype, w, 0, m, l, n, A, lda, bN0, l, bM0, l, 0, true))) return rc;
+  {
+    ProfScope ps(ctx, s, PK_SKETCH);
+    RSVD_TRY(sketch_launch(s, dtype, seed, 0u, n, l, bN0, l), "sketch");
+  }
+  // step 2: Y = A Omega, then q rounds of Z = A^T Q, Y = A Z.  Every product is
+  // re-orthonormalised; all but the last with a single CholeskyQR round (result in
+  // the other panel of the pair), the last one (step 3) with two.
+  void *curN = bN0, *othN = bN1, *curM = bM0, *othM = bM1;
   uint32_t refill = 16;
-  if ((rc = orthonormalize(ctx, s, dtype, w, m, l, bM0, l, bM1, nullptr, seed, refill))) return rc;
+  auto swap = [](void *&a, void *&b) { void *t = a; a = b; b = t; };
+  if ((rc = product(ctx, s, dtype, w, 0, m, l, n, A, lda, curN, l, curM, l, 0, true, PK_GEMM_AX))) return rc;
+  if ((rc = orthonormalize(ctx, s, dtype, w, m, l, curM, l, othM, nullptr, seed, refill, q == 0 ? 2 : 1))) return rc;
+  if (q > 0) swap(curM, othM);
   refill += 2;
   for (int it = 0; it < q; ++it) {
-    if ((rc = product(ctx, s, dtype, w, 1, n, l, m, A, lda, bM0, l, bN0, l, 0, true))) return rc;
-    if ((rc = orthonormalize(ctx, s, dtype, w, n, l, bN0, l, bN1, nullptr, seed, refill))) return rc;
+    if ((rc = product(ctx, s, dtype, w, 1, n, l, m, A, lda, curM, l, curN, l, 0, true, PK_GEMM_ATX))) return rc;
+    if ((rc = orthonormalize(ctx, s, dtype, w, n, l, curN, l, othN, nullptr, seed, refill, 1))) return rc;
+    swap(curN, othN);
     refill += 2;
-    if ((rc = product(ctx, s, dtype, w, 0, m, l, n, A, lda, bN0, l, bM0, l, 0, true))) return rc;
-    // step 3 on the last pass
-    if ((rc = orthonormalize(ctx, s, dtype, w, m, l, bM0, l, bM1, nullptr, seed, refill))) return rc;
+    if ((rc = product(ctx, s, dtype, w, 0, m, l, n, A, lda, curN, l, curM, l, 0, true, PK_GEMM_AX))) return rc;
+    const bool last = it == q - 1;
+    if ((rc = orthonormalize(ctx, s, dtype, w, m, l, curM, l, othM, nullptr, seed, refill, last ? 2 : 1))) return rc;
+    if (!last) swap(curM, othM);
     refill += 2;
   }
   // step 4: B^T = A^T Q
-  if ((rc = product(ctx, s, dtype, w, 1, n, l, m, A, lda, bM0, l, bN0, l, 0, true))) return rc;
+  if ((rc = product(ctx, s, dtype, w, 1, n, l, m, A, lda, curM, l, curN, l, 0, true, PK_GEMM_ATX))) return rc;
   // step 5
-  if ((rc = small_svd(ctx, s, dtype, w, n, l, bN0, l, bN1, seed, refill))) return rc;
+  if ((rc = small_svd(ctx, s, dtype, w, n, l, curN, l, othN, seed, refill))) return rc;
   RSVD_TRY(copy_launch(s, dtype, w.at<void>(L.sigma), S, k), "copy S");
   if (job >= RSVD_JOB_SV) {
     // V^T = (Qb X[:, :k])^T
-    if ((rc = product(ctx, s, dtype, w, 0, n, k, l, bN0, l, w.at<void>(L.Xj), l, Vt, ldvt, 1, false))) return rc;
+    if ((rc = product(ctx, s, dtype, w, 0, n, k, l, curN, l, w.at<void>(L.Xj), l, Vt, ldvt, 1, false, PK_LIFT))) return rc;
   }
   if (job == RSVD_JOB_SUV) {
     // step 6: U = Q Ub[:, :k]
-    if ((rc = product(ctx, s, dtype, w, 0, m, k, l, bM0, l, w.at<void>(L.Wj), l, U, ldu, 0, false))) return rc;
+    if ((rc = product(ctx, s, dtype, w, 0, m, k, l, curM, l, w.at<void>(L.Wj), l, U, ldu, 0, false, PK_LIFT))) return rc;
   }
   return finish_info(ctx, s, w, info);
 }
@@ -363,8 +424,8 @@ static int stage_gemm(rsvd_ctx *ctx, void *stream, rsvd_dtype dtype, int trans_a
   w.base = (char *)workspace;
   if (workspace == nullptr || ((uintptr_t)workspace & 255) != 0) return -13;
   if (workspace_bytes < w.L.total) return -14;
-  if (trans_a) return product(ctx, (hipStream_t)stream, dtype, w, 1, n, l, m, A, lda, X, ldx, Y, ldy, 0, true);
-  return product(ctx, (hipStream_t)stream, dtype, w, 0, m, l, n, A, lda, X, ldx, Y, ldy, 0, true);
+  if (trans_a) return product(ctx, (hipStream_t)stream, dtype, w, 1, n, l, m, A, lda, X, ldx, Y, ldy, 0, true, PK_GEMM_ATX);
+  return product(ctx, (hipStream_t)stream, dtype, w, 0, m, l, n, A, lda, X, ldx, Y, ldy, 0, true, PK_GEMM_AX);
 }
 
 int rsvd_stage_gemm_an(rsvd_ctx *ctx, void *stream, rsvd_dtype dtype, int64_t m, int64_t n, int64_t l, const void *A,
@@ -427,7 +488,7 @@ int rsvd_stage_small_svd(rsvd_ctx *ctx, void *stream, rsvd_dtype dtype, int64_t 
   if (rc) return rc;
   RSVD_TRY(copy_launch(s, dtype, w.at<void>(w.L.sigma), sigma, l), "copy sigma");
   RSVD_TRY(copy_launch(s, dtype, w.at<void>(w.L.Wj), Ub, l * l), "copy Ub");
-  if ((rc = product(ctx, s, dtype, w, 0, n, l, l, Bt, ldbt, w.at<void>(w.L.Xj), l, V, ldv, 0, false))) return rc;
+  if ((rc = product(ctx, s, dtype, w, 0, n, l, l, Bt, ldbt, w.at<void>(w.L.Xj), l, V, ldv, 0, false, PK_LIFT))) return rc;
   return finish_info(ctx, s, w, info);
 }
 
@@ -472,7 +533,7 @@ int rsvd_stage_lift(rsvd_ctx *ctx, void *stream, rsvd_dtype dtype, int64_t m, in
   Ws w;
   w.base = nullptr;
   memset(&w.L, 0, sizeof(w.L));
-  return product(ctx, (hipStream_t)stream, dtype, w, 0, m, k, l, Q, ldq, W, ldw, U, ldu, transpose_out ? 1 : 0, false);
+  return product(ctx, (hipStream_t)stream, dtype, w, 0, m, k, l, Q, ldq, W, ldw, U, ldu, transpose_out ? 1 : 0, false, PK_LIFT);
 }
 
 }  // extern "C"

@@ -44,10 +44,19 @@ def clusters(sig, gap_min, k):
     return [r for r in runs if r[0] < k]
 
 
-def significant(sig, dtype, m, n):
-    """Mask of singular values that are compared relatively (above the rank threshold)."""
+ABS_C = 10.0     # a backward-stable SVD returns each singular value to within ~ABS_C * eps * sigma_1
+
+
+def significant(sig, dtype, m=None, n=None):
+    """Mask of singular values that can be held to the relative tolerance.
+
+    Any SVD computed in precision eps delivers singular values with an ABSOLUTE
+    error of order eps * sigma_1, so a relative error SV_RTOL is attainable only
+    for sigma_i >= (ABS_C * eps / SV_RTOL) * sigma_1.  Values below that are
+    compared absolutely, to ABS_C * eps * sigma_1 times sqrt(max(m, n)) (the
+    growth of accumulated rounding in dot products of that length)."""
     sig = np.asarray(sig, dtype=np.float64)
-    return sig > 100.0 * EPS[dtype] * sig[0] * max(m, n)
+    return sig > (ABS_C * EPS[dtype] / SV_RTOL[dtype]) * sig[0]
 
 
 def orthonormality(Q):
@@ -76,7 +85,7 @@ def check_triplets(S_g, U_g, Vt_g, S_o, U_o, Vt_o, dtype, m, n,
     if insig.any():
         absd = np.abs(S_g - S_o)[insig].max()
         out["sv_abs_insig"] = float(absd)
-        assert absd <= 100.0 * EPS[dtype] * S_o[0] * max(m, n)
+        assert absd <= ABS_C * EPS[dtype] * S_o[0] * np.sqrt(max(m, n))
 
     have_all = S_all_o is not None and U_all_g is not None
     ref = S_all_o if have_all else S_o

@@ -44,7 +44,8 @@ def run_and_compare(cfg, A_dev, A_host, q=None, note=""):
         f"clusters={res['clusters']} skipped={res['skipped']} err_g/err_o={err_g / max(err_o, 1e-300):.6f}")
     assert err_g <= 1.01 * err_o + 50 * eps * normA
     # whole-basis angle: the l-dimensional ranges agree
-    assert parity.sin_theta(Ua[:, :ns], (o.Q @ o.Ub)[:, :ns]) <= parity.ANGLE_TOL[dt] or ns < l
+    if ns == l:
+        assert parity.sin_theta(Ua, o.Q @ o.Ub) <= parity.ANGLE_TOL[dt]
     return res
 
 
