@@ -52,6 +52,16 @@ static hipError_t copy_launch(hipStream_t s, rsvd_dtype dtype, const void *src, 
   return hipGetLastError();
 }
 
+__global__ void widen_kernel(const float *__restrict__ src, double *__restrict__ dst, int64_t n) {
+  for (int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; e < n; e += (int64_t)gridDim.x * blockDim.x)
+    dst[e] = (double)src[e];
+}
+
+static hipError_t widen_launch(hipStream_t s, const float *src, double *dst, int64_t n) {
+  hipLaunchKernelGGL(widen_kernel, dim3(256), dim3(256), 0, s, src, dst, n);
+  return hipGetLastError();
+}
+
 // ---------------------------------------------------------------- workspace
 
 // Offsets (bytes) into the caller's workspace.  Depends on (dtype, m, n, l) only.
@@ -508,7 +518,15 @@ int rsvd_stage_jacobi(rsvd_ctx *ctx, void *stream, rsvd_dtype dtype, int64_t l, 
   if (workspace_bytes < w.L.total) return -10;
   hipStream_t s = (hipStream_t)stream;
   RSVD_TRY(zero_ints_launch(s, w.at<int>(w.L.info), 4), "zero info");
-  hipError_t e = jacobi_launch(ctx, s, dtype, l, M, dtype == RSVD_F64, sigma, X, W, w.at<DevInfo>(w.L.info),
+  const void *Min = M;
+  int min_f64 = dtype == RSVD_F64;
+  if (dtype == RSVD_F32 && l > jacobi_max_lds_order(ctx, dtype)) {
+    // the block path reads an fp64 matrix: widen M into the slot of the triangular factor
+    RSVD_TRY(widen_launch(s, (const float *)M, w.at<double>(w.L.Rb), l * l), "widen");
+    Min = w.at<void>(w.L.Rb);
+    min_f64 = 1;
+  }
+  hipError_t e = jacobi_launch(ctx, s, dtype, l, Min, min_f64, sigma, X, W, w.at<DevInfo>(w.L.info),
                                w.at<void>(w.L.jac_scratch), w.L.jac_scratch_bytes);
   if (e == hipErrorNotSupported) return RSVD_ERR_UNSUPPORTED;
   RSVD_TRY(e, "jacobi");

@@ -59,6 +59,15 @@ def significant(sig, dtype, m=None, n=None):
     return sig > (ABS_C * EPS[dtype] / SV_RTOL[dtype]) * sig[0]
 
 
+def jacobi_tol(l, dtype):
+    """Frobenius-norm bound for orthogonality defects and residuals of vectors that
+    went through the Jacobi SVD: every column is hit by about l rotations per sweep
+    for a handful of sweeps, each adding one rounding error, so a single inner
+    product drifts by ~sqrt(l * sweeps) * eps and the l x l Frobenius norm by l
+    times that.  8 * l^1.5 * eps covers up to ~16 sweeps with a factor 2 to spare."""
+    return 8.0 * float(l) ** 1.5 * EPS[dtype]
+
+
 def orthonormality(Q):
     Q = np.asarray(Q, dtype=np.float64)
     return float(np.linalg.norm(Q.T @ Q - np.eye(Q.shape[1])))

@@ -123,7 +123,8 @@ def test_lift(dt, m, l, k, tr):
 # ---------------------------------------------------------------- step 3: orthonormalisation
 @pytest.mark.parametrize("dt", ["f32", "f64"])
 @pytest.mark.parametrize("rows,l,cond", [(512, 20, 10.0), (3000, 80, 1e3), (1000, 120, 50.0), (129, 33, 5.0),
-                                         (10000, 64, 1e2)])
+                                         (10000, 64, 1e2), (2000, 160, 30.0), (3000, 288, 1e2), (5000, 576, 10.0),
+                                         (1500, 200, 1e3)])
 def test_orth_full_rank_matches_householder(dt, rows, l, cond):
     say("orth", dt, rows, l, cond)
     Y = workloads.graded_matrix(rows, l, cond, seed=20, dtype=NPDT[dt])
@@ -175,27 +176,27 @@ def test_orth_zero_and_nonfinite_input():
 
 # ---------------------------------------------------------------- step 5: small SVD
 def _svd_check(sig, X, W, M, dt, name):
-    eps = np.finfo(NPDT[dt]).eps
     l = M.shape[0]
+    tol = parity.jacobi_tol(l, dt)
     want = np.linalg.svd(M, compute_uv=False)
     smax = want[0]
-    assert np.abs(sig - want).max() <= 20 * l * eps * smax, (name, np.abs(sig - want).max())
+    assert np.abs(sig - want).max() <= tol * smax, (name, np.abs(sig - want).max())
     assert (np.diff(sig) <= 0).all()
-    assert np.linalg.norm(W.T @ W - np.eye(l)) <= 20 * l * eps
-    nz = sig > 100 * l * eps * smax
-    assert np.linalg.norm((X.T @ X)[np.ix_(nz, nz)] - np.eye(nz.sum())) <= 50 * l * eps
-    assert np.linalg.norm(X * sig @ W.T - M) <= 20 * l * eps * smax
+    assert np.linalg.norm(W.T @ W - np.eye(l)) <= tol
+    nz = sig > 100 * l * np.finfo(NPDT[dt]).eps * smax
+    assert np.linalg.norm((X.T @ X)[np.ix_(nz, nz)] - np.eye(nz.sum())) <= tol
+    assert np.linalg.norm(X * sig @ W.T - M) <= tol * smax
 
 
 @pytest.mark.parametrize("dt", ["f32", "f64"])
-@pytest.mark.parametrize("l", [2, 5, 20, 33, 64, 80, 96])
+@pytest.mark.parametrize("l", [2, 5, 20, 33, 64, 80, 96, 128, 129, 160, 288, 576])
 def test_jacobi_matches_oracle(dt, l):
     say("jacobi", dt, l)
     M = workloads.gaussian_matrix(l, l, 40 + l, NPDT[dt])
     sig, X, W, info = ctx().rsvd_stage_jacobi(to_dev(M))
     sig, X, W = (to_np(t).astype(np.float64) for t in (sig, X, W))
     say("  sweeps", info.jacobi_sweeps)
-    assert info.status == 0 and 1 <= info.jacobi_sweeps <= 15
+    assert info.status == 0 and 1 <= info.jacobi_sweeps <= 20
     M64 = M.astype(np.float64)
     _svd_check(sig, X, W, M64, dt, "gaussian")
     if l <= 33:       # brute-force Jacobi oracle on the small ones: vectors up to sign
@@ -230,20 +231,19 @@ def test_jacobi_special_matrices(dt):
 
 
 @pytest.mark.parametrize("dt", ["f32", "f64"])
-@pytest.mark.parametrize("n,l", [(256, 20), (2000, 80), (1000, 120), (300, 33)])
+@pytest.mark.parametrize("n,l", [(256, 20), (2000, 80), (1000, 120), (300, 33), (2000, 288), (1000, 160)])
 def test_small_svd_of_projected_factor(dt, n, l):
     say("small_svd", dt, n, l)
-    if dt == "f64" and l > 98:
-        pytest.skip("fp64 order above the LDS-resident limit is covered by the block path tests")
     Bt = workloads.graded_matrix(n, l, 100.0, seed=50, dtype=NPDT[dt])
     sig, Ub, V, info = ctx().rsvd_stage_small_svd(to_dev(Bt))
     sig, Ub, V = (to_np(t).astype(np.float64) for t in (sig, Ub, V))
     B = Bt.astype(np.float64).T
     Uo, so, Vto = orc.small_svd(B)
     eps = np.finfo(NPDT[dt]).eps
-    assert np.abs(sig - so).max() <= 20 * l * eps * so[0]
-    assert np.linalg.norm(Ub * sig @ V.T - B) <= 20 * l * eps * so[0]
-    assert parity.orthonormality(V) <= 20 * l * eps and parity.orthonormality(Ub) <= 20 * l * eps
+    tol = parity.jacobi_tol(l, dt)
+    assert np.abs(sig - so).max() <= tol * so[0]
+    assert np.linalg.norm(Ub * sig @ V.T - B) <= tol * so[0]
+    assert parity.orthonormality(V) <= tol and parity.orthonormality(Ub) <= tol
     # graded spectrum 1 .. 1/100 in l steps: relative gaps ~ ln(100)/l, vectors well defined
     gap = np.log(100.0) / l
     assert np.abs(np.abs(np.sum(Ub * Uo, axis=0)) - 1).max() <= 100 * l * eps / gap
