@@ -14,14 +14,25 @@ namespace rsvd {
 
 hipError_t gemm_launch_f64(rsvd_ctx *ctx, hipStream_t s, const GemmDesc &d);
 
+// 1 / sqrt(d) for d > 0: hardware estimate refined by two Newton steps (error below
+// 2 ulp); the pivot chain is the serial bottleneck, so it must be short.
+__device__ __forceinline__ double fast_rsqrt(double d) {
+  double y = __builtin_amdgcn_rsq(d);
+  y = y * (1.5 - 0.5 * d * y * y);
+  y = y * (1.5 - 0.5 * d * y * y);
+  return y;
+}
+
 // One workgroup of TG x TG threads factors an nb x nb block (nb <= TG * NR) that
-// it holds in registers: thread (ty, tx) owns the elements (ty + TG a, tx + TG b).
-// The block is the sum of n_parts matrices spaced part_stride elements apart
-// (split-K partial Gram matrices are added here, in a fixed order).
+// it holds in registers: thread (ty, tx) owns the elements (ty + TG a, tx + TG b)
+// of the symmetric matrix S and of Z = R^-T.  The block is the sum of n_parts
+// matrices spaced part_stride elements apart (split-K partial Gram matrices are
+// added here, in a fixed order).
 // Right-looking elimination, one step per column j: the owners of row j publish
-// it through a double-buffered LDS line (one barrier per step), every thread then
-// updates its own elements.  The same pass carries Z = R^-T along: rows of Z live
-// in the strict lower triangle, its diagonal 1 / R[j][j] in dinv.
+// it through double-buffered LDS lines (one barrier per step); every thread then
+// applies the rank-one update to its elements of S (both triangles, so the inner
+// loop carries no masks) and of Z.  Row j of R and column j of R^-1 are final at
+// step j and go straight to global memory.
 //   g0    : original squared column norms for the pivot test, or NULL to use the diagonal
 //   Rinv  : nb x nb block of R^-1 (ld ldri, type TOut, zeros below the diagonal)
 //   R     : same for R in fp64 (ld ldr), or NULL
@@ -34,22 +45,25 @@ __global__ __launch_bounds__(TG * TG) void chol_block_kernel(const double *__res
                                                               double *__restrict__ R, int64_t ldr,
                                                               int *__restrict__ dead, DevInfo *info) {
   constexpr int LMAX = TG * NR;
-  __shared__ double rowbuf[2][LMAX];
-  __shared__ double dinv[LMAX];
+  __shared__ double bufS[2][LMAX];
+  __shared__ double bufZ[2][LMAX];
   __shared__ double d0[LMAX];
+  __shared__ double zdiag[LMAX];
   __shared__ int n_dead, bad;
+  extern __shared__ double outm[];       // nb x (LMAX + 1): finished rows of R and Z
+  constexpr int ost = LMAX + 1;
   const int tid = threadIdx.x;
   const int tx = tid % TG, ty = tid / TG;
-  double S[NR][NR];
+  double S[NR][NR], Z[NR][NR];
 
   if (tid == 0) { n_dead = 0; bad = 0; }
 #pragma unroll
   for (int a = 0; a < NR; ++a)
 #pragma unroll
-    for (int b = 0; b < NR; ++b) S[a][b] = 0.0;
-  // all NR*NR loads of a group of four parts are issued before they are added, so the
-  // memory latency is paid once per group and not once per element
-  constexpr int UB = (TG * TG > 256 && NR > 3) ? 2 : 4;   // parts per batch, bounded by the register budget
+    for (int b = 0; b < NR; ++b) { S[a][b] = 0.0; Z[a][b] = 0.0; }
+  // all loads of a batch of parts are issued before they are added, so the memory
+  // latency is paid once per batch and not once per element
+  constexpr int UB = NR > 4 ? 1 : (NR > 2 ? 2 : 4);
   for (int s0 = 0; s0 < n_parts; s0 += UB) {
     double v[UB][NR][NR];
 #pragma unroll
@@ -82,80 +96,75 @@ __global__ __launch_bounds__(TG * TG) void chol_block_kernel(const double *__res
       }
     }
 
-  for (int j = 0; j < nb; ++j) {
-    double *buf = rowbuf[j & 1];
+  // The step loop is unrolled over the 16-wide row blocks (A0 is a compile-time
+  // constant inside), so the register that holds row j is addressed statically and
+  // blocks that can no longer change are dropped at compile time: branches inside
+  // the step cost more than the arithmetic they would save.
 #pragma unroll
-    for (int a = 0; a < NR; ++a)
-      if (ty + TG * a == j) {
+  for (int A0 = 0; A0 < NR; ++A0) {
+    for (int jj = 0; jj < TG; ++jj) {
+      const int j = A0 * TG + jj;
+      if (j >= nb) break;
+      double *bs = bufS[j & 1], *bz = bufZ[j & 1];
+      const bool own_row = (jj == ty);
+      if (own_row) {
 #pragma unroll
         for (int b = 0; b < NR; ++b) {
           const int c = tx + TG * b;
-          if (c < nb) buf[c] = S[a][b];
+          bs[c] = S[A0][b];
+          bz[c] = Z[A0][b];
         }
       }
-    __syncthreads();
-    const double d = buf[j], dj0 = d0[j];
-    const bool is_dead = !(d > tau * dj0) || !(dj0 > 0.0);
-    const double rjj = is_dead ? 0.0 : sqrt(d);
-    const double rinv = is_dead ? 0.0 : 1.0 / rjj;
-    double rowc[NR], rowi[NR];
+      __syncthreads();
+      const double d = bs[j], dj0 = d0[j];
+      const bool is_dead = !(d > tau * dj0) || !(dj0 > 0.0);
+      const double rinv = is_dead ? 0.0 : fast_rsqrt(d);
+      double srow[NR], zrow[NR], lcol[NR];
 #pragma unroll
-    for (int b = 0; b < NR; ++b) {
-      const int c = tx + TG * b;
-      rowc[b] = (c < nb) ? buf[c] * rinv : 0.0;
-    }
+      for (int b = 0; b < NR; ++b) {
+        const int c = tx + TG * b;
+        srow[b] = (b >= A0 && c > j) ? bs[c] * rinv : 0.0;     // R[j][c]; columns >= nb hold zeros
+        zrow[b] = (b <= A0 && c <= j) ? ((c == j) ? rinv : bz[c] * rinv) : 0.0;          // Z[j][c]
+      }
 #pragma unroll
-    for (int a = 0; a < NR; ++a) {
-      const int i = ty + TG * a;
-      rowi[a] = (i < nb) ? buf[i] * rinv : 0.0;
-    }
+      for (int a = 0; a < NR; ++a) {
+        const int i = ty + TG * a;
+        lcol[a] = (a >= A0 && i > j) ? bs[i] * rinv : 0.0;     // R[j][i]
+      }
 #pragma unroll
-    for (int a = 0; a < NR; ++a) {
-      const int i = ty + TG * a;
-      if (i == j) {
+      for (int a = A0; a < NR; ++a)
 #pragma unroll
         for (int b = 0; b < NR; ++b) {
-          const int c = tx + TG * b;
-          if (c == j) {
-            S[a][b] = rjj;
-            dinv[j] = rinv;
-            dead[j] = is_dead ? 1 : 0;
-            if (is_dead) n_dead += 1;            // single writer per step
-          } else {
-            S[a][b] = rowc[b];
-          }
+          if (b >= A0) S[a][b] = fma(-lcol[a], srow[b], S[a][b]);
+          if (b <= A0) Z[a][b] = fma(-lcol[a], zrow[b], Z[a][b]);
         }
-      } else if (i > j) {
-        const double lij = rowi[a];
+      if (own_row) {
+        // row j of R and row j of Z (= column j of R^-1) are final: park them in LDS
+        const double rjj = is_dead ? 0.0 : d * rinv;
 #pragma unroll
         for (int b = 0; b < NR; ++b) {
           const int c = tx + TG * b;
-          if (c == j)                S[a][b] = -lij * rinv;
-          else if (c < j || c >= i)  S[a][b] -= lij * rowc[b];
+          outm[j * ost + c] = (c > j) ? srow[b] : ((c == j) ? rjj : zrow[b]);
+        }
+        if (tx == jj) {
+          zdiag[j] = rinv;
+          dead[j] = is_dead ? 1 : 0;
+          if (is_dead) n_dead += 1;                                // single writer per step
         }
       }
     }
   }
   __syncthreads();
-
-#pragma unroll
-  for (int a = 0; a < NR; ++a)
-#pragma unroll
-    for (int b = 0; b < NR; ++b) {
-      const int i = ty + TG * a, c = tx + TG * b;
-      if (i < nb && c < nb) {
-        if (i < c) {
-          if (R != nullptr) R[(int64_t)i * ldr + c] = S[a][b];
-          Rinv[(int64_t)c * ldri + i] = (TOut)0;
-        } else if (i > c) {
-          if (R != nullptr) R[(int64_t)i * ldr + c] = 0.0;
-          Rinv[(int64_t)c * ldri + i] = (TOut)S[a][b];
-        } else {
-          if (R != nullptr) R[(int64_t)i * ldr + i] = S[a][b];
-          Rinv[(int64_t)i * ldri + i] = (TOut)dinv[i];
-        }
-      }
-    }
+  // outm: upper triangle = R, strict lower triangle = Z (row i holds Z[i][:i]), zdiag = diagonal of Z
+  for (int idx = tid; idx < nb * nb; idx += TG * TG) {
+    const int r = idx / nb, c = idx - r * nb;
+    double rr = 0.0, ri = 0.0;
+    if (r < c)       { rr = outm[r * ost + c]; ri = outm[c * ost + r]; }
+    else if (r == c) { rr = outm[r * ost + r]; ri = zdiag[r]; }
+    if (R != nullptr) R[(int64_t)r * ldr + c] = rr;
+    Rinv[(int64_t)r * ldri + c] = (TOut)ri;
+  }
+  __syncthreads();
   if (tid == 0 && info != nullptr) {
     if (n_dead > 0) atomicAdd(&info->refilled, n_dead);
     if (bad) atomicMax(&info->status, (int)RSVD_ERR_NONFINITE);
@@ -196,7 +205,7 @@ __global__ void zero_ints_kernel(int *p, int n) {
 
 int chol_max_block(const rsvd_ctx *ctx) {
   (void)ctx;
-  return 128;      // 32 x 32 threads, 4 x 4 elements each
+  return 128;      // 16 x 16 threads, up to 8 x 8 elements each
 }
 
 size_t chol_scratch_elems(const rsvd_ctx *ctx, int64_t l) {
@@ -209,19 +218,32 @@ template <typename TOut>
 static hipError_t launch_block(hipStream_t s, const double *G, int64_t ldg, int n_parts, int64_t part_stride, int nb,
                                const double *g0, double tau, TOut *Rinv, int64_t ldri, double *R, int64_t ldr,
                                int *dead, DevInfo *info) {
-  if (nb <= 32) {
-    hipLaunchKernelGGL((chol_block_kernel<TOut, 16, 2>), dim3(1), dim3(256), 0, s, G, ldg, n_parts, part_stride, nb,
-                       g0, tau, Rinv, ldri, R, ldr, dead, info);
-  } else if (nb <= 64) {
-    hipLaunchKernelGGL((chol_block_kernel<TOut, 16, 4>), dim3(1), dim3(256), 0, s, G, ldg, n_parts, part_stride, nb,
-                       g0, tau, Rinv, ldri, R, ldr, dead, info);
-  } else if (nb <= 96) {
-    hipLaunchKernelGGL((chol_block_kernel<TOut, 32, 3>), dim3(1), dim3(1024), 0, s, G, ldg, n_parts, part_stride, nb,
-                       g0, tau, Rinv, ldri, R, ldr, dead, info);
-  } else {
-    hipLaunchKernelGGL((chol_block_kernel<TOut, 32, 4>), dim3(1), dim3(1024), 0, s, G, ldg, n_parts, part_stride, nb,
-                       g0, tau, Rinv, ldri, R, ldr, dead, info);
+  // 256 threads (one wavefront per SIMD) keep the per-step barrier cheap; each thread
+  // holds NR x NR elements of S and of Z, NR = ceil(nb / 16); above 96 the register
+  // budget asks for 1024 threads with 4 x 4 elements.
+  const size_t lds = (size_t)nb * ((size_t)((nb + 15) / 16 > 6 ? 128 : ((nb + 15) / 16) * 16) + 1) * sizeof(double);
+#define RSVD_CHOL_CASE(TGV, NRV)                                                                                    \
+  do {                                                                                                              \
+    static bool attr_set = false;                                                                                   \
+    if (!attr_set) {                                                                                                \
+      (void)hipFuncSetAttribute(reinterpret_cast<const void *>(&chol_block_kernel<TOut, TGV, NRV>),                 \
+                                hipFuncAttributeMaxDynamicSharedMemorySize, 150 * 1024);                            \
+      (void)hipGetLastError();                                                                                      \
+      attr_set = true;                                                                                              \
+    }                                                                                                               \
+    hipLaunchKernelGGL((chol_block_kernel<TOut, TGV, NRV>), dim3(1), dim3(TGV * TGV), lds, s, G, ldg, n_parts,      \
+                       part_stride, nb, g0, tau, Rinv, ldri, R, ldr, dead, info);                                   \
+  } while (0)
+  switch ((nb + 15) / 16) {
+    case 1: RSVD_CHOL_CASE(16, 1); break;
+    case 2: RSVD_CHOL_CASE(16, 2); break;
+    case 3: RSVD_CHOL_CASE(16, 3); break;
+    case 4: RSVD_CHOL_CASE(16, 4); break;
+    case 5: RSVD_CHOL_CASE(16, 5); break;
+    case 6: RSVD_CHOL_CASE(16, 6); break;
+    default: RSVD_CHOL_CASE(32, 4); break;
   }
+#undef RSVD_CHOL_CASE
   return hipGetLastError();
 }
 

@@ -212,7 +212,16 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const GemmParams P) 
        e += (int64_t)gridDim.x * blockDim.x) {
     const TAcc *p = (const TAcc *)P.partial + e;
     TAcc sum = (TAcc)0;
-    for (int s = 0; s < P.splits; ++s) sum += p[(int64_t)s * total];
+    // eight loads in flight per step; the additions keep their fixed order
+    int s = 0;
+    for (; s + 8 <= P.splits; s += 8) {
+      TAcc v[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) v[u] = p[(int64_t)(s + u) * total];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) sum += v[u];
+    }
+    for (; s < P.splits; ++s) sum += p[(int64_t)s * total];
     const int64_t row = e / P.N;
     store_result<TOut, TAcc, sizeof(TIn) == 4>(P, row, e - row * P.N, sum);
   }

@@ -25,100 +25,151 @@ template <typename T> struct Eps;
 template <> struct Eps<float>  { static constexpr float  value = 1.1920929e-07f; };
 template <> struct Eps<double> { static constexpr double value = 2.220446049250313e-16; };
 
+// DPP lane moves: no LDS traffic, unlike a shuffle.
+template <int CTRL> __device__ __forceinline__ float dpp_mov(float v) {
+  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xF, 0xF, false));
+}
+template <int CTRL> __device__ __forceinline__ double dpp_mov(double v) {
+  const long long b = __double_as_longlong(v);
+  const int lo = __builtin_amdgcn_update_dpp(0, (int)b, CTRL, 0xF, 0xF, false);
+  const int hi = __builtin_amdgcn_update_dpp(0, (int)(b >> 32), CTRL, 0xF, 0xF, false);
+  return __longlong_as_double(((long long)hi << 32) | (long long)(unsigned int)lo);
+}
+// Sum over the 8 lanes of a half row: neighbours (quad_perm 1,0,3,2), pairs
+// (quad_perm 2,3,0,1), then the other quad (row_half_mirror).  Every lane adds
+// the same two partial sums at each step, so all 8 end with identical bits.
+template <typename T> __device__ __forceinline__ T half_row_sum(T v) {
+  v += dpp_mov<0xB1>(v);
+  v += dpp_mov<0x4E>(v);
+  v += dpp_mov<0x141>(v);
+  return v;
+}
+
+// Reciprocal, square root and reciprocal square root from the hardware estimates
+// (1 ulp in fp32; refined by Newton steps in fp64).  The rotation parameters sit
+// on the serial path of every pair, so their instruction count matters.
+__device__ __forceinline__ float fast_rcp(float x) { return __builtin_amdgcn_rcpf(x); }
+__device__ __forceinline__ float fast_rsq(float x) { return __builtin_amdgcn_rsqf(x); }
+__device__ __forceinline__ float fast_sqrt(float x) { return __builtin_amdgcn_sqrtf(x); }
+__device__ __forceinline__ double fast_rcp(double x) {
+  double y = __builtin_amdgcn_rcp(x);
+  y = y * (2.0 - x * y);
+  y = y * (2.0 - x * y);
+  return y;
+}
+__device__ __forceinline__ double fast_rsq(double x) {
+  double y = __builtin_amdgcn_rsq(x);
+  y = y * (1.5 - 0.5 * x * y * y);
+  y = y * (1.5 - 0.5 * x * y * y);
+  return y;
+}
+__device__ __forceinline__ double fast_sqrt(double x) { return x * fast_rsq(x); }
+
+// Rotation (c, s) that orthogonalises two columns with squared norms alpha, beta
+// and inner product gamma != 0:  zeta = (beta - alpha) / (2 gamma),
+// t = sign(zeta) / (|zeta| + sqrt(1 + zeta^2)), c = 1 / sqrt(1 + t^2), s = c t.
+template <typename T>
+__device__ __forceinline__ void rotation_params(T alpha, T beta, T gamma, T &c, T &s) {
+  const T zeta = (beta - alpha) * fast_rcp((T)2 * gamma);
+  const T az = fabs(zeta);
+  T t;
+  if (az > (T)1e7) t = (T)0.5 * fast_rcp(az);                   // avoids overflow of zeta^2
+  else t = fast_rcp(az + fast_sqrt((T)1 + zeta * zeta));
+  t = zeta < (T)0 ? -t : t;
+  c = fast_rsq((T)1 + t * t);
+  s = c * t;
+}
+
 // Pair i of round r in a tournament of n2 (even) players: player n2-1 stays,
-// the others rotate (circle method).
+// the others rotate (circle method).  Requires r < n2 - 1 and i < n2 / 2.
 __device__ __forceinline__ void tournament_pair(int n2, int r, int i, int &a, int &b) {
   const int nm1 = n2 - 1;
   if (i == 0) {
     a = nm1;
-    b = r % nm1;
+    b = r;
   } else {
-    a = (r + i) % nm1;
-    b = (r - i + nm1) % nm1;
+    a = r + i;
+    if (a >= nm1) a -= nm1;
+    b = r - i;
+    if (b < 0) b += nm1;
   }
 }
 
-// Rotate columns p, q of M (and of J) held column-major with stride ldm; the G
-// lanes of one group share the work, each holding up to RPL elements of either
-// column in registers between the inner products and the update.  Returns true
-// when a rotation was applied.
-template <typename T, int G, int RPL>
-__device__ __forceinline__ bool rotate_pair(T *Mc, T *Jc, int ldm, int rows, int p, int q, int lg, T tol,
-                                            T floor2) {
-  T *mp = Mc + p * ldm, *mq = Mc + q * ldm;
-  T x[RPL], y[RPL];
+// Rotate columns p, q of M (and of J), stored column-major with stride ldm and
+// zero-padded to 8 * RPL rows.  LDS is accessed in 8-byte units (two floats or one
+// double): lane lg of the group's 8 lanes owns units lg, lg + 8, lg + 16, ... of a
+// column (the 8 lanes read one contiguous 64-byte run, free of bank conflicts) and
+// keeps them in registers between the inner products and the update.  Returns
+// true when a rotation was applied.
+template <typename T, int RPL>
+__device__ __forceinline__ bool rotate_pair(T *Mc, T *Jc, int ldm, int p, int q, int lg, T tol, T floor2) {
+  constexpr int V = 8 / sizeof(T);          // elements per LDS access
+  constexpr int NV = RPL / V;               // accesses per column per lane
+  typedef T unit __attribute__((ext_vector_type(V)));
+  unit *mp = reinterpret_cast<unit *>(Mc + p * ldm) + lg;
+  unit *mq = reinterpret_cast<unit *>(Mc + q * ldm) + lg;
+  unit x[NV], y[NV];
+#pragma unroll
+  for (int r = 0; r < NV; ++r) { x[r] = mp[8 * r]; y[r] = mq[8 * r]; }
   T alpha = 0, beta = 0, gamma = 0;
 #pragma unroll
-  for (int r = 0; r < RPL; ++r) {
-    const int i = lg + G * r;
-    const bool ok = i < rows;
-    x[r] = ok ? mp[i] : (T)0;
-    y[r] = ok ? mq[i] : (T)0;
-  }
+  for (int r = 0; r < NV; ++r)
 #pragma unroll
-  for (int r = 0; r < RPL; ++r) {
-    alpha += x[r] * x[r];
-    beta += y[r] * y[r];
-    gamma += x[r] * y[r];
-  }
-#pragma unroll
-  for (int off = G / 2; off > 0; off >>= 1) {
-    alpha += __shfl_xor(alpha, off, G);
-    beta += __shfl_xor(beta, off, G);
-    gamma += __shfl_xor(gamma, off, G);
-  }
-  if (alpha <= floor2 || beta <= floor2) return false;
-  const T limit = tol * sqrt(alpha) * sqrt(beta);
-  if (!(fabs(gamma) > limit)) return false;
-  T *jp = Jc + p * ldm, *jq = Jc + q * ldm;
-  T u[RPL], v[RPL];
-#pragma unroll
-  for (int r = 0; r < RPL; ++r) {
-    const int i = lg + G * r;
-    const bool ok = i < rows;
-    u[r] = ok ? jp[i] : (T)0;
-    v[r] = ok ? jq[i] : (T)0;
-  }
-  const T zeta = (beta - alpha) / ((T)2 * gamma);
-  T t;
-  if (fabs(zeta) > (T)1e7) {
-    t = (T)0.5 / zeta;                         // avoids overflow of zeta^2
-  } else {
-    t = (zeta >= 0 ? (T)1 : (T)-1) / (fabs(zeta) + sqrt((T)1 + zeta * zeta));
-  }
-  const T c = (T)1 / sqrt((T)1 + t * t), s = c * t;
-#pragma unroll
-  for (int r = 0; r < RPL; ++r) {
-    const int i = lg + G * r;
-    if (i < rows) {
-      mp[i] = c * x[r] - s * y[r];
-      mq[i] = s * x[r] + c * y[r];
-      jp[i] = c * u[r] - s * v[r];
-      jq[i] = s * u[r] + c * v[r];
+    for (int e = 0; e < V; ++e) {
+      alpha += x[r][e] * x[r][e];
+      beta += y[r][e] * y[r][e];
+      gamma += x[r][e] * y[r][e];
     }
+  alpha = half_row_sum(alpha);
+  beta = half_row_sum(beta);
+  gamma = half_row_sum(gamma);
+  if (alpha <= floor2 || beta <= floor2) return false;
+  const T limit = tol * fast_sqrt(alpha * beta);
+  if (!(fabs(gamma) > limit)) return false;
+  unit *jp = reinterpret_cast<unit *>(Jc + p * ldm) + lg;
+  unit *jq = reinterpret_cast<unit *>(Jc + q * ldm) + lg;
+  unit u[NV], v[NV];
+#pragma unroll
+  for (int r = 0; r < NV; ++r) { u[r] = jp[8 * r]; v[r] = jq[8 * r]; }
+  T c, s;
+  rotation_params(alpha, beta, gamma, c, s);
+#pragma unroll
+  for (int r = 0; r < NV; ++r) {
+    mp[8 * r] = c * x[r] - s * y[r];
+    mq[8 * r] = s * x[r] + c * y[r];
+  }
+#pragma unroll
+  for (int r = 0; r < NV; ++r) {
+    jp[8 * r] = c * u[r] - s * v[r];
+    jq[8 * r] = s * u[r] + c * v[r];
   }
   return true;
 }
 
-template <typename T, typename TIn, int G>
-__global__ __launch_bounds__(1024) void jacobi_lds_kernel(const TIn *__restrict__ M, int l, T *__restrict__ sigma,
-                                                          T *__restrict__ X, T *__restrict__ W, DevInfo *info) {
-  extern __shared__ double lds_raw[];
-  const int ldm = l | 1;
+// Padded row count and column stride of the LDS layout for order l.
+__host__ __device__ inline int jacobi_rows_padded(int l) { return ((l + 15) / 16) * 16; }
+__host__ __device__ inline int jacobi_ldm(int l) { return jacobi_rows_padded(l) + 2; }
+
+template <typename T, typename TIn, int RPL>
+__global__ __launch_bounds__(512) void jacobi_lds_kernel(const TIn *__restrict__ M, int l, T *__restrict__ sigma,
+                                                         T *__restrict__ X, T *__restrict__ W, DevInfo *info) {
+  extern __shared__ __attribute__((aligned(16))) double lds_raw[];
+  const int ldm = jacobi_ldm(l);
   T *Mc = reinterpret_cast<T *>(lds_raw);
   T *Jc = Mc + (size_t)l * ldm;
   T *nrm = Jc + (size_t)l * ldm;
   int *rnk = reinterpret_cast<int *>(nrm + l);
   __shared__ int rotations;
-  __shared__ T wave_sum[16];
+  __shared__ T wave_sum[8];
 
   const int tid = threadIdx.x, nt = blockDim.x;
   T fro2 = 0;
-  for (int idx = tid; idx < l * l; idx += nt) {
-    const int r = idx / l, c = idx - r * l;
-    const T v = (T)M[idx];
-    Mc[c * ldm + r] = v;
-    Jc[c * ldm + r] = (r == c) ? (T)1 : (T)0;
+  for (int idx = tid; idx < l * ldm; idx += nt) {
+    const int c = idx / ldm, r = idx - c * ldm;
+    T v = (T)0;
+    if (r < l) v = (T)M[r * l + c];
+    Mc[idx] = v;
+    Jc[idx] = (r == c) ? (T)1 : (T)0;
     fro2 += v * v;
   }
 #pragma unroll
@@ -130,25 +181,29 @@ __global__ __launch_bounds__(1024) void jacobi_lds_kernel(const TIn *__restrict_
   for (int w = 0; w < (nt >> 6); ++w) fro2 += wave_sum[w];
   const T floor2 = Eps<T>::value * Eps<T>::value * fro2;
 
+  constexpr int G = 8;           // lanes per column pair
   const int n2 = l + (l & 1), npairs = n2 / 2;
   const int group = tid / G, lg = tid % G, ngroups = nt / G;
   const T tol = Eps<T>::value * sqrt((T)l);
   int sweeps = 0;
   bool converged = (l < 2);
+  // nt >= 8 * npairs: every pair of a round has its own lane group
+  const bool has_pair = group < npairs;
+  (void)ngroups;
   while (!converged && sweeps < kJacobiMaxSweeps) {
     ++sweeps;
+    bool rotated = false;
     for (int r = 0; r < n2 - 1; ++r) {
-      for (int pi = group; pi < npairs; pi += ngroups) {
-        int a, b;
-        tournament_pair(n2, r, pi, a, b);
-        if (a < l && b < l) {
-          const int p = a < b ? a : b, q = a < b ? b : a;
-          const bool rot = rotate_pair<T, G, (128 + G - 1) / G>(Mc, Jc, ldm, l, p, q, lg, tol, floor2);
-          if (rot && lg == 0) atomicAdd(&rotations, 1);
-        }
+      int a, b;
+      tournament_pair(n2, r, has_pair ? group : 0, a, b);
+      if (has_pair && a < l && b < l) {
+        const int p = a < b ? a : b, q = a < b ? b : a;
+        rotated |= rotate_pair<T, RPL>(Mc, Jc, ldm, p, q, lg, tol, floor2);
       }
       __syncthreads();
     }
+    if (rotated) rotations = 1;             // same value from every writer
+    __syncthreads();
     converged = (rotations == 0);
     __syncthreads();
     if (tid == 0) rotations = 0;
@@ -220,11 +275,8 @@ __device__ __forceinline__ bool rotate_pair_loop(T *Pc, T *Tc, int ldp, int ldt,
   if (alpha <= floor2 || beta <= floor2) return false;
   const T limit = tol * sqrt(alpha) * sqrt(beta);
   if (!(fabs(gamma) > limit)) return false;
-  const T zeta = (beta - alpha) / ((T)2 * gamma);
-  T t;
-  if (fabs(zeta) > (T)1e7) t = (T)0.5 / zeta;
-  else t = (zeta >= 0 ? (T)1 : (T)-1) / (fabs(zeta) + sqrt((T)1 + zeta * zeta));
-  const T c = (T)1 / sqrt((T)1 + t * t), s = c * t;
+  T c, s;
+  rotation_params(alpha, beta, gamma, c, s);
   for (int i = lg; i < rows_m; i += G) {
     const T x = mp[i], y = mq[i];
     mp[i] = c * x - s * y;
@@ -416,14 +468,14 @@ static int jb_block_width(const rsvd_ctx *ctx, rsvd_dtype dtype, int64_t l) {
 
 static size_t jacobi_lds_bytes(rsvd_dtype dtype, int64_t l) {
   const size_t es = dtype_size(dtype);
-  const size_t ldm = (size_t)(l | 1);
+  const size_t ldm = (size_t)jacobi_ldm((int)l);
   return align_up(2 * (size_t)l * ldm * es + (size_t)l * (es + sizeof(int)), 16);
 }
 
 int jacobi_max_lds_order(const rsvd_ctx *ctx, rsvd_dtype dtype) {
   int l = 2;
   while (l < 128 && jacobi_lds_bytes(dtype, l + 1) + 512 <= ctx->lds_per_block) ++l;
-  return l;      // 128 = lanes per pair x elements each lane keeps in registers
+  return l;      // 128 = 8 lanes per pair x 16 rows each lane keeps in registers
 }
 
 // Scratch of the block path: header, Mt, Jt, norms, ranks.
@@ -470,27 +522,33 @@ static hipError_t jacobi_block_launch(rsvd_ctx *ctx, hipStream_t s, rsvd_dtype d
   return hipGetLastError();
 }
 
-template <typename T, typename TIn, int G>
+template <typename T, typename TIn, int RPL>
 static hipError_t launch_lds(hipStream_t s, int nt, size_t lds, const void *M, int l, void *sigma, void *X, void *W,
                              DevInfo *info) {
   static bool attr_set = false;
   if (!attr_set) {
-    (void)hipFuncSetAttribute(reinterpret_cast<const void *>(&jacobi_lds_kernel<T, TIn, G>),
+    (void)hipFuncSetAttribute(reinterpret_cast<const void *>(&jacobi_lds_kernel<T, TIn, RPL>),
                               hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 512);
     (void)hipGetLastError();
     attr_set = true;
   }
-  hipLaunchKernelGGL((jacobi_lds_kernel<T, TIn, G>), dim3(1), dim3(nt), lds, s, (const TIn *)M, l, (T *)sigma,
+  hipLaunchKernelGGL((jacobi_lds_kernel<T, TIn, RPL>), dim3(1), dim3(nt), lds, s, (const TIn *)M, l, (T *)sigma,
                      (T *)X, (T *)W, info);
   return hipGetLastError();
 }
 
+// rows per lane = padded rows / 8: 2, 4, ..., 16
 template <typename T, typename TIn>
-static hipError_t launch_lds_g(hipStream_t s, int nt, int g, size_t lds, const void *M, int l, void *sigma, void *X,
+static hipError_t launch_lds_g(hipStream_t s, int nt, int rpl, size_t lds, const void *M, int l, void *sigma, void *X,
                                void *W, DevInfo *info) {
-  switch (g) {
-    case 64: return launch_lds<T, TIn, 64>(s, nt, lds, M, l, sigma, X, W, info);
-    case 32: return launch_lds<T, TIn, 32>(s, nt, lds, M, l, sigma, X, W, info);
+  switch (rpl) {
+    case 2: return launch_lds<T, TIn, 2>(s, nt, lds, M, l, sigma, X, W, info);
+    case 4: return launch_lds<T, TIn, 4>(s, nt, lds, M, l, sigma, X, W, info);
+    case 6: return launch_lds<T, TIn, 6>(s, nt, lds, M, l, sigma, X, W, info);
+    case 8: return launch_lds<T, TIn, 8>(s, nt, lds, M, l, sigma, X, W, info);
+    case 10: return launch_lds<T, TIn, 10>(s, nt, lds, M, l, sigma, X, W, info);
+    case 12: return launch_lds<T, TIn, 12>(s, nt, lds, M, l, sigma, X, W, info);
+    case 14: return launch_lds<T, TIn, 14>(s, nt, lds, M, l, sigma, X, W, info);
     default: return launch_lds<T, TIn, 16>(s, nt, lds, M, l, sigma, X, W, info);
   }
 }
@@ -508,10 +566,11 @@ hipError_t jacobi_launch(rsvd_ctx *ctx, hipStream_t s, rsvd_dtype dtype, int64_t
     return jacobi_block_launch<double>(ctx, s, dtype, (int)l, (const double *)M, (double *)sigma, (double *)X,
                                        (double *)W, info, (char *)scratch);
   }
-  const int nt = l > 64 ? 1024 : (l > 32 ? 512 : 256);
+  // one 8-lane group per column pair of a round, all pairs of a round at once
   const int npairs = (int)((l + 1) / 2);
-  int g = 64;
-  while (g > 16 && nt / g < npairs) g /= 2;
+  int nt = (int)align_up((size_t)npairs * 8, 64);
+  if (nt > 512) nt = 512;
+  const int g = jacobi_rows_padded((int)l) / 8;          // rows per lane
   const size_t lds = jacobi_lds_bytes(dtype, l);
   ProfScope ps(ctx, s, PK_JACOBI);
   if (dtype == RSVD_F32) {

@@ -110,7 +110,7 @@ def test_seed_changes_the_sketch_not_the_answer():
     np.testing.assert_allclose(to_np(S0), 10.0 ** (-np.arange(9) / 5.0), rtol=1e-11)
 
 
-@pytest.mark.parametrize("cid", [1, 2, 3])
+@pytest.mark.parametrize("cid", [1, 2, 3, 4, 5])
 def test_full_size_configs(cid):
     """The benchmark's configurations at full size, oracle run in full beside the HIP path."""
     cfg = CONFIGS[cid]
