@@ -26,21 +26,25 @@ PEAK_MFMA = {"f32": 157.3e12, "f64": 78.6e12}    # dense matrix FLOP/s
 PEAK_VALU = {"f32": 157.3e12, "f64": 78.6e12}    # vector FLOP/s (256 CUs, 2.4 GHz)
 
 
+# HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this script at configuration 2,
+# scaled by the same counters on a plain 1 GiB copy (figures and commands: profiles/rsvd_run_cfg2_hbm_counters.md).
+MEASURED_TRAFFIC = {2: {"cholesky": 0.26e6, "jacobi": 0.12e6, "gemm_atx": 136.8e6, "gemm_ax": 101.2e6,
+                        "gram": 10.1e6}}
+
+
 def kernel_models(cfg):
     """Algorithmic flops and HBM bytes of ONE launch of each kernel class (unit: one launch)."""
     m, n, l, k = cfg.m, cfg.n, cfg.l, cfg.k
     sz = 4 if cfg.dtype == "f32" else 8
-    rows_avg = None
     models = {
         # products with A: read A once, read the skinny operand, write the result
         "gemm_ax": dict(flops=2.0 * m * n * l, bytes=(m * n + n * l + m * l) * sz, mfma=cfg.dtype),
         "gemm_atx": dict(flops=2.0 * m * n * l, bytes=(m * n + m * l + n * l) * sz, mfma=cfg.dtype),
         # small dense stages (latency / ALU bound): flops of the textbook algorithm
-        "cholesky": dict(flops=(2.0 / 3.0) * l ** 3, bytes=2 * l * l * 8, alu="f64"),
-        "jacobi": dict(flops=None, bytes=3 * l * l * sz, alu=cfg.dtype),
+        "cholesky": dict(flops=(5.0 / 3.0) * l ** 3, bytes=2 * l * l * 8, alu="f64"),
         "sketch": dict(flops=None, bytes=n * l * sz),
     }
-    return models, rows_avg
+    return models
 
 
 def per_launch_model(name, cfg, launches_per_call):
@@ -58,12 +62,15 @@ def per_launch_model(name, cfg, launches_per_call):
     if name == "lift":
         rows = (m + n) / 2.0
         return dict(flops=2.0 * rows * l * k, bytes=rows * (l + k) * sz, mfma=cfg.dtype)
-    models, _ = kernel_models(cfg)
-    return models.get(name)
+    if name == "jacobi":
+        # one sweep = l(l-1)/2 pair visits, each 3 inner products and 2 rotated column pairs of length l
+        sweeps = launches_per_call if launches_per_call else 1
+        return dict(flops=9.0 * l ** 3 * sweeps, bytes=3 * l * l * sz, alu=cfg.dtype)
+    return kernel_models(cfg).get(name)
 
 
-def roofline_for(name, avg_ms, cfg):
-    mod = per_launch_model(name, cfg, None)
+def roofline_for(name, avg_ms, cfg, sweeps=None):
+    mod = per_launch_model(name, cfg, sweeps)
     if mod is None or avg_ms <= 0:
         return None
     t = avg_ms * 1e-3
@@ -110,6 +117,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", type=int, default=2, help="benchmark configuration 1..5 (default 2)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain 1 GiB device-to-device copy (reference dispatch for HBM counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1",
@@ -135,6 +144,12 @@ def main():
 
     for _ in range(args.warmup):
         step()
+    if args.calibrate_copy:
+        src = torch.ones(1 << 28, dtype=torch.float32, device=dev)      # 1 GiB read + 1 GiB written
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     _, _, _, info = ctx.rsvd_run(A, cfg.k, cfg.p, cfg.q, seed=cfg.seed, workspace=ws, out=out)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -160,10 +175,12 @@ def main():
     kernels = {name: dict(ms_per_call=tot / args.steps, launches_per_call=cnt / args.steps,
                           avg_us=tot / cnt * 1e3) for name, (tot, cnt) in prof.items()}
     dominant = max(kernels, key=lambda kname: kernels[kname]["ms_per_call"])
-    roof = roofline_for(dominant, kernels[dominant]["avg_us"] * 1e-3, cfg)
+    roof = roofline_for(dominant, kernels[dominant]["avg_us"] * 1e-3, cfg, info.jacobi_sweeps)
+    if roof is not None:
+        roof["traffic"] = MEASURED_TRAFFIC.get(args.config, {}).get(dominant)
     stage_roof = {}
     for name in kernels:
-        r = roofline_for(name, kernels[name]["avg_us"] * 1e-3, cfg)
+        r = roofline_for(name, kernels[name]["avg_us"] * 1e-3, cfg, info.jacobi_sweeps)
         if r is not None:
             stage_roof[name] = dict(bound=r["bound"], achieved=round(r["achieved"], 3), unit=r["unit"],
                                     frac=round(r["frac"], 4))
