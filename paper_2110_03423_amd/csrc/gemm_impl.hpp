@@ -17,30 +17,10 @@
 #pragma once
 
 #include "common.hpp"
+#include "mfma.hpp"
 #include "philox_dev.hpp"
 
 namespace rsvd {
-
-typedef float f32x4 __attribute__((ext_vector_type(4)));
-typedef double f64x4 __attribute__((ext_vector_type(4)));
-
-// 16x16x4 MFMA: lane L supplies A[L % 16][L / 16] and B[L / 16][L % 16];
-// the 4 accumulator registers of lane L hold column L % 16 and the rows given by row().
-template <typename TAcc> struct Mfma;
-template <> struct Mfma<float> {
-  typedef f32x4 vec;
-  static __device__ __forceinline__ vec run(float a, float b, vec c) {
-    return __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, c, 0, 0, 0);
-  }
-  static __device__ __forceinline__ int row(int lane, int v) { return 4 * (lane >> 4) + v; }
-};
-template <> struct Mfma<double> {
-  typedef f64x4 vec;
-  static __device__ __forceinline__ vec run(double a, double b, vec c) {
-    return __builtin_amdgcn_mfma_f64_16x16x4f64(a, b, c, 0, 0, 0);
-  }
-  static __device__ __forceinline__ int row(int lane, int v) { return 4 * v + (lane >> 4); }
-};
 
 struct GemmParams {
   int64_t M, N, K;
@@ -50,6 +30,7 @@ struct GemmParams {
   void *partial;            // [splits][M][N] accumulator-typed, used when splits > 1
   int64_t k_per_split;
   int splits;
+  int tiles_n, tiles_m;     // grid shape in tiles; the launch is one-dimensional
   int trans_c;
   double alpha, beta;
   const int *dead;
@@ -138,9 +119,22 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmParams P) {
   const int wm0 = (wave / WGN) * WM, wn0 = (wave % WGN) * WN;
   const int r16 = lane & 15, kq = lane >> 4;
 
-  const int64_t m0 = (int64_t)blockIdx.y * BM;
-  const int64_t n0 = (int64_t)blockIdx.x * BN;
-  const int64_t k_begin = (int64_t)blockIdx.z * P.k_per_split;
+  // Workgroups are handed to the 8 XCDs round-robin by launch index, and each XCD has
+  // its own L2.  Renumber so that one XCD receives a contiguous run of tile indices:
+  // the column tiles of one row tile (which all read the same rows of A) then share an L2.
+  const int total = (int)gridDim.x;
+  const int pid = (int)blockIdx.x;
+  const int per_xcd = (total + 7) >> 3;
+  const int tall = (total & 7) ? (total & 7) : 8;        // XCDs that receive per_xcd workgroups
+  const int xcd = pid & 7, local = pid >> 3;
+  const int tile = (xcd < tall) ? xcd * per_xcd + local
+                                : tall * per_xcd + (xcd - tall) * (per_xcd - 1) + local;
+  const int tile_n = tile % P.tiles_n;
+  const int tile_m = (tile / P.tiles_n) % P.tiles_m;
+  const int split = tile / (P.tiles_n * P.tiles_m);
+  const int64_t m0 = (int64_t)tile_m * BM;
+  const int64_t n0 = (int64_t)tile_n * BN;
+  const int64_t k_begin = (int64_t)split * P.k_per_split;
   const int64_t k_end = (k_begin + P.k_per_split < P.K) ? (k_begin + P.k_per_split) : P.K;
 
   const TIn *A = (const TIn *)P.A;
@@ -197,7 +191,7 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmParams P) {
         const int64_t col = n0 + wn0 + j * 16 + r16;
         if (row < P.M && col < P.N) {
           if (P.splits > 1) {
-            ((TAcc *)P.partial)[((int64_t)blockIdx.z * P.M + row) * P.N + col] = acc[i][j][v];
+            ((TAcc *)P.partial)[((int64_t)split * P.M + row) * P.N + col] = acc[i][j][v];
           } else {
             store_result<TOut, TAcc, sizeof(TIn) == 4>(P, row, col, acc[i][j][v]);
           }
@@ -234,11 +228,17 @@ struct TileChoice {
 };
 
 // Tile shapes instantiated below (see the dispatch switch).
-inline TileChoice choose_tile(int64_t M, int64_t N) {
+inline TileChoice choose_tile(int64_t M, int64_t N, size_t acc_size) {
   TileChoice t;
   if (N <= 128) {
     t.bm = 64;
     t.bn = (int)(ceil_div(N, 16) * 16);
+  } else if (acc_size == 8) {
+    // fp64 accumulators: the 64-row tile with one wavefront per 16 rows keeps the register
+    // count low enough for two workgroups per CU, which measured faster than 128-row tiles
+    t.bm = 64;
+    const int64_t pad64 = ceil_div(N, 64) * 64 - N, pad128 = ceil_div(N, 128) * 128 - N;
+    t.bn = (pad128 < pad64) ? 128 : 64;
   } else {
     // wide outputs: 128-row tiles, column tile with the least padding
     t.bm = 128;
@@ -280,12 +280,15 @@ template <typename TIn, typename TAcc, typename TOut>
 struct GemmDispatch {
   template <bool TA, int BM, int BN, int WGM, int WGN>
   static hipError_t run(hipStream_t s, const GemmParams &P, bool vec) {
-    dim3 grid((unsigned)ceil_div(P.N, BN), (unsigned)ceil_div(P.M, BM), (unsigned)P.splits);
+    GemmParams Q = P;
+    Q.tiles_n = (int)ceil_div(P.N, BN);
+    Q.tiles_m = (int)ceil_div(P.M, BM);
+    dim3 grid((unsigned)((int64_t)Q.tiles_n * Q.tiles_m * P.splits));
     constexpr int V = 16 / sizeof(TIn);
     if (vec) {
-      hipLaunchKernelGGL((gemm_kernel<TIn, TAcc, TOut, TA, BM, BN, WGM, WGN, V>), grid, dim3(256), 0, s, P);
+      hipLaunchKernelGGL((gemm_kernel<TIn, TAcc, TOut, TA, BM, BN, WGM, WGN, V>), grid, dim3(256), 0, s, Q);
     } else {
-      hipLaunchKernelGGL((gemm_kernel<TIn, TAcc, TOut, TA, BM, BN, WGM, WGN, 1>), grid, dim3(256), 0, s, P);
+      hipLaunchKernelGGL((gemm_kernel<TIn, TAcc, TOut, TA, BM, BN, WGM, WGN, 1>), grid, dim3(256), 0, s, Q);
     }
     return hipGetLastError();
   }
@@ -311,14 +314,14 @@ struct GemmDispatch {
   }
 
   static size_t partial_bytes(const rsvd_ctx *ctx, int64_t M, int64_t N, int64_t K) {
-    const TileChoice t = choose_tile(M, N);
+    const TileChoice t = choose_tile(M, N, sizeof(TAcc));
     const SplitChoice c = choose_split(ctx, t, M, N, K, 0);
     return c.splits > 1 ? (size_t)c.splits * (size_t)M * (size_t)N * sizeof(TAcc) : 0;
   }
 
   static hipError_t launch(rsvd_ctx *ctx, hipStream_t s, const GemmDesc &d) {
     if (d.M <= 0 || d.N <= 0) return hipSuccess;
-    const TileChoice t = choose_tile(d.M, d.N);
+    const TileChoice t = choose_tile(d.M, d.N, sizeof(TAcc));
     SplitChoice c = choose_split(ctx, t, d.M, d.N, d.K, d.force_splits);
     if (c.splits > 1) {
       const size_t need = (size_t)c.splits * (size_t)d.M * (size_t)d.N * sizeof(TAcc);

@@ -16,6 +16,7 @@
 // keep shrinking by a factor eps per sweep until they underflow.  Its singular
 // value is reported as that norm and its column of X is set to zero.
 #include "common.hpp"
+#include "mfma.hpp"
 
 namespace rsvd {
 
@@ -255,38 +256,57 @@ __global__ __launch_bounds__(512) void jacobi_lds_kernel(const TIn *__restrict__
 // that finds counters[s-1] == 0 returns at once (converged), which keeps the
 // whole sequence free of host synchronisation.
 
-template <typename T, int G>
-__device__ __forceinline__ bool rotate_pair_loop(T *Pc, T *Tc, int ldp, int ldt, int rows_m, int rows_t, int p,
-                                                 int q, int lg, T tol, T floor2) {
-  T *mp = Pc + p * ldp, *mq = Pc + q * ldp;
-  T alpha = 0, beta = 0, gamma = 0;
-  for (int i = lg; i < rows_m; i += G) {
-    const T x = mp[i], y = mq[i];
-    alpha += x * x;
-    beta += y * y;
-    gamma += x * y;
-  }
+// Sum over the 32 lanes of a pair group: the 16-lane row by DPP (neighbours, pairs,
+// half-row mirror, row mirror), then one exchange with the partner row.
+template <typename T> __device__ __forceinline__ T group32_sum(T v) {
+  v += dpp_mov<0xB1>(v);
+  v += dpp_mov<0x4E>(v);
+  v += dpp_mov<0x141>(v);
+  v += dpp_mov<0x140>(v);
+  v += __shfl_xor(v, 16, 32);
+  return v;
+}
+
+// Panel version of rotate_pair: columns of length up to 32 * NV units held in LDS
+// (stride ldp, zero padded), 32 lanes per pair, the accumulated rotation T
+// (rows_t x rows_t, stride ldt) instead of J.
+template <typename T, int NV>
+__device__ __forceinline__ bool rotate_pair_panel(T *Pc, T *Tc, int ldp, int ldt, int rows_t, int p, int q, int lg,
+                                                  T tol, T floor2) {
+  constexpr int V = 8 / sizeof(T);
+  typedef T unit __attribute__((ext_vector_type(V)));
+  unit *mp = reinterpret_cast<unit *>(Pc + p * ldp) + lg;
+  unit *mq = reinterpret_cast<unit *>(Pc + q * ldp) + lg;
+  unit x[NV], y[NV];
 #pragma unroll
-  for (int off = G / 2; off > 0; off >>= 1) {
-    alpha += __shfl_xor(alpha, off, G);
-    beta += __shfl_xor(beta, off, G);
-    gamma += __shfl_xor(gamma, off, G);
-  }
+  for (int r = 0; r < NV; ++r) { x[r] = mp[32 * r]; y[r] = mq[32 * r]; }
+  T alpha = 0, beta = 0, gamma = 0;
+#pragma unroll
+  for (int r = 0; r < NV; ++r)
+#pragma unroll
+    for (int e = 0; e < V; ++e) {
+      alpha += x[r][e] * x[r][e];
+      beta += y[r][e] * y[r][e];
+      gamma += x[r][e] * y[r][e];
+    }
+  alpha = group32_sum(alpha);
+  beta = group32_sum(beta);
+  gamma = group32_sum(gamma);
   if (alpha <= floor2 || beta <= floor2) return false;
-  const T limit = tol * sqrt(alpha) * sqrt(beta);
+  const T limit = tol * fast_sqrt(alpha * beta);
   if (!(fabs(gamma) > limit)) return false;
   T c, s;
   rotation_params(alpha, beta, gamma, c, s);
-  for (int i = lg; i < rows_m; i += G) {
-    const T x = mp[i], y = mq[i];
-    mp[i] = c * x - s * y;
-    mq[i] = s * x + c * y;
+#pragma unroll
+  for (int r = 0; r < NV; ++r) {
+    mp[32 * r] = c * x[r] - s * y[r];
+    mq[32 * r] = s * x[r] + c * y[r];
   }
   T *tp = Tc + p * ldt, *tq = Tc + q * ldt;
-  for (int i = lg; i < rows_t; i += G) {
-    const T x = tp[i], y = tq[i];
-    tp[i] = c * x - s * y;
-    tq[i] = s * x + c * y;
+  for (int i = lg; i < rows_t; i += 32) {
+    const T a = tp[i], bq = tq[i];
+    tp[i] = c * a - s * bq;
+    tq[i] = s * a + c * bq;
   }
   return true;
 }
@@ -322,63 +342,85 @@ __global__ __launch_bounds__(1024) void jb_init_kernel(const double *__restrict_
   if (tid < 64) hdr->counters[tid] = 0;
 }
 
-template <typename T, int G>
+// Padded column length (elements) of the panel layout: 32 lanes x NV units.
+template <typename T, int NV> __host__ __device__ constexpr int jb_ldp() { return 32 * NV * (8 / (int)sizeof(T)) + 2; }
+
+// phase 0 ("diagonal"): workgroup g rotates the pairs inside column block g
+//   (cols - 1 rounds of the circle tournament).
+// phase 1 ("cross"): workgroup g takes the block pair g of tournament round `round`
+//   and rotates only pairs with one column in each block: b rounds, pair i of
+//   round r is (i, (i + r) mod b) - every column of one block meets every column of
+//   the other exactly once.
+// One outer sweep = one diagonal launch + (nblk - 1) cross launches = l - 1 rounds
+// in all, the same count as the plain tournament.
+template <typename T, int NV>
 __global__ __launch_bounds__(1024) void jb_panel_kernel(T *__restrict__ Mt, T *__restrict__ Jt, int l, int b,
-                                                        int nblk, int round, int sweep, int inner_sweeps,
-                                                        JbHeader *hdr) {
+                                                        int nblk, int phase, int round, int sweep, JbHeader *hdr) {
   if (sweep > 0 && hdr->counters[sweep - 1] == 0) return;      // converged in the previous sweep
-  const int nblk2 = nblk + (nblk & 1);
-  int ba, bb;
-  tournament_pair(nblk2, round, blockIdx.x, ba, bb);
-  if (ba >= nblk || bb >= nblk) return;                        // bye
-  const int bi = ba < bb ? ba : bb, bj = ba < bb ? bb : ba;
-  const int cols_i = (l - bi * b < b) ? (l - bi * b) : b;
-  const int cols_j = (l - bj * b < b) ? (l - bj * b) : b;
+  int bi, bj, cols_i, cols_j;
+  if (phase == 0) {
+    bi = bj = (int)blockIdx.x;
+    cols_i = (l - bi * b < b) ? (l - bi * b) : b;
+    cols_j = 0;
+  } else {
+    const int nblk2 = nblk + (nblk & 1);
+    int ba, bb;
+    tournament_pair(nblk2, round, blockIdx.x, ba, bb);
+    if (ba >= nblk || bb >= nblk) return;                      // bye
+    bi = ba < bb ? ba : bb;
+    bj = ba < bb ? bb : ba;
+    cols_i = (l - bi * b < b) ? (l - bi * b) : b;
+    cols_j = (l - bj * b < b) ? (l - bj * b) : b;
+  }
   const int ncols = cols_i + cols_j;
 
-  extern __shared__ double lds_raw[];
-  const int ldp = l | 1, ldt = (2 * b) | 1;
+  extern __shared__ __attribute__((aligned(16))) double lds_raw[];
+  constexpr int ldp = jb_ldp<T, NV>();
+  const int ldt = (2 * b) + 2;
   T *Pc = reinterpret_cast<T *>(lds_raw);
   T *Tc = Pc + (size_t)(2 * b) * ldp;
-  __shared__ int rotations, total;
+  __shared__ int rotations;
 
   const int tid = threadIdx.x, nt = blockDim.x;
   auto gcol = [&](int c) { return c < cols_i ? bi * b + c : bj * b + (c - cols_i); };
-  for (int c = tid / 64; c < ncols; c += nt / 64) {
-    const T *src = Mt + (int64_t)gcol(c) * l;
-    for (int r = tid & 63; r < l; r += 64) Pc[c * ldp + r] = src[r];
+  for (int c = tid / 64; c < 2 * b; c += nt / 64) {
+    const T *src = Mt + (int64_t)gcol(c < ncols ? c : 0) * l;
+    for (int r = tid & 63; r < ldp; r += 64) Pc[c * ldp + r] = (c < ncols && r < l) ? src[r] : (T)0;
   }
-  for (int idx = tid; idx < ncols * ncols; idx += nt) {
-    const int c = idx / ncols, r = idx - c * ncols;
-    Tc[c * ldt + r] = (r == c) ? (T)1 : (T)0;
+  for (int idx = tid; idx < 2 * b * ldt; idx += nt) {
+    const int c = idx / ldt, r = idx - c * ldt;
+    Tc[idx] = (r == c && c < ncols) ? (T)1 : (T)0;
   }
-  if (tid == 0) { rotations = 0; total = 0; }
+  if (tid == 0) rotations = 0;
   __syncthreads();
 
   const T floor2 = (T)(Eps<T>::value * Eps<T>::value * hdr->fro2);
   const T tol = Eps<T>::value * sqrt((T)l);
-  const int n2 = ncols + (ncols & 1), npairs = n2 / 2;
-  const int group = tid / G, lg = tid % G, ngroups = nt / G;
-  for (int isw = 0; isw < inner_sweeps; ++isw) {
+  const int group = tid >> 5, lg = tid & 31;                   // 32 groups of 32 lanes, b <= 32
+  bool rotated = false;
+  if (phase == 0) {
+    const int n2 = ncols + (ncols & 1);
     for (int r = 0; r < n2 - 1; ++r) {
-      for (int pi = group; pi < npairs; pi += ngroups) {
+      if (group < n2 / 2) {
         int a, c2;
-        tournament_pair(n2, r, pi, a, c2);
+        tournament_pair(n2, r, group, a, c2);
         if (a < ncols && c2 < ncols) {
           const int p = a < c2 ? a : c2, q = a < c2 ? c2 : a;
-          const bool rot = rotate_pair_loop<T, G>(Pc, Tc, ldp, ldt, l, ncols, p, q, lg, tol, floor2);
-          if (rot && lg == 0) atomicAdd(&rotations, 1);
+          rotated |= rotate_pair_panel<T, NV>(Pc, Tc, ldp, ldt, ncols, p, q, lg, tol, floor2);
         }
       }
       __syncthreads();
     }
-    const int done = rotations;
-    __syncthreads();
-    if (tid == 0) { total += rotations; rotations = 0; }
-    __syncthreads();
-    if (done == 0) break;
+  } else {
+    for (int r = 0; r < b; ++r) {
+      int qi = group + r;
+      if (qi >= b) qi -= b;
+      if (group < cols_i && qi < cols_j)
+        rotated |= rotate_pair_panel<T, NV>(Pc, Tc, ldp, ldt, ncols, group, cols_i + qi, lg, tol, floor2);
+      __syncthreads();
+    }
   }
-  const int n_rot = total;
+  const int n_rot = __syncthreads_count(rotated && lg == 0);
   if (n_rot == 0) return;                                     // nothing changed: leave M and J alone
 
   for (int c = tid / 64; c < ncols; c += nt / 64) {
@@ -386,18 +428,32 @@ __global__ __launch_bounds__(1024) void jb_panel_kernel(T *__restrict__ Mt, T *_
     for (int r = tid & 63; r < l; r += 64) dst[r] = Pc[c * ldp + r];
   }
   __syncthreads();
-  // J[:, panel] <- J[:, panel] T, staged through the LDS space of the panel
+  // J[:, panel] <- J[:, panel] T on the matrix cores, the old columns staged through the
+  // LDS space of the panel: an (l x 2b) by (2b x 2b) product in 16 x 16 blocks, K = 2b.
   for (int c = tid / 64; c < ncols; c += nt / 64) {
     const T *src = Jt + (int64_t)gcol(c) * l;
     for (int r = tid & 63; r < l; r += 64) Pc[c * ldp + r] = src[r];
   }
   __syncthreads();
-  for (int r = tid; r < l; r += nt) {
-    for (int cn = 0; cn < ncols; ++cn) {
-      T acc = 0;
-      const T *tcol = Tc + cn * ldt;                           // column cn of T: new column = sum_c T[c][cn] * old column c
-      for (int c = 0; c < ncols; ++c) acc += tcol[c] * Pc[c * ldp + r];
-      Jt[(int64_t)gcol(cn) * l + r] = acc;
+  {
+    typedef typename Mfma<T>::vec acc_t;
+    const int lane = tid & 63, wave = tid >> 6, nwave = nt >> 6;
+    const int r16 = lane & 15, kq = lane >> 4;
+    const int row_blocks = (l + 15) / 16, col_blocks = (2 * b) / 16;
+    for (int blk = wave; blk < row_blocks * col_blocks; blk += nwave) {
+      const int rb = blk / col_blocks, cb = blk - rb * col_blocks;
+      acc_t acc = (acc_t)(T)0;
+      for (int k0 = 0; k0 < 2 * b; k0 += 4) {
+        const T av = Pc[(k0 + kq) * ldp + rb * 16 + r16];           // Jold[row][k]
+        const T bv = Tc[(cb * 16 + r16) * ldt + k0 + kq];            // T[k][col]
+        acc = Mfma<T>::run(av, bv, acc);
+      }
+      const int cn = cb * 16 + r16;
+#pragma unroll
+      for (int v = 0; v < 4; ++v) {
+        const int r = rb * 16 + Mfma<T>::row(lane, v);
+        if (r < l && cn < ncols) Jt[(int64_t)gcol(cn) * l + r] = acc[v];
+      }
     }
   }
   if (tid == 0) atomicAdd(&hdr->counters[sweep], n_rot);
@@ -456,16 +512,6 @@ __global__ __launch_bounds__(256) void jb_scatter_kernel(const T *__restrict__ M
 
 constexpr int kJbMaxSweeps = 24;
 
-// block width for the panel kernel: 2b columns of length l plus T must fit in LDS
-static int jb_block_width(const rsvd_ctx *ctx, rsvd_dtype dtype, int64_t l) {
-  const size_t es = dtype_size(dtype);
-  for (int b = 32; b >= 8; b -= 8) {
-    const size_t need = ((size_t)(2 * b) * (size_t)(l | 1) + (size_t)(2 * b) * ((2 * b) | 1)) * es + 1024;
-    if (need <= ctx->lds_per_block) return b;
-  }
-  return 0;
-}
-
 static size_t jacobi_lds_bytes(rsvd_dtype dtype, int64_t l) {
   const size_t es = dtype_size(dtype);
   const size_t ldm = (size_t)jacobi_ldm((int)l);
@@ -476,6 +522,29 @@ int jacobi_max_lds_order(const rsvd_ctx *ctx, rsvd_dtype dtype) {
   int l = 2;
   while (l < 128 && jacobi_lds_bytes(dtype, l + 1) + 512 <= ctx->lds_per_block) ++l;
   return l;      // 128 = 8 lanes per pair x 16 rows each lane keeps in registers
+}
+
+// Units (8 bytes) per lane for order l: ceil(l / V / 32), rounded up to an instantiated value.
+static int jb_units_per_lane(rsvd_dtype dtype, int64_t l) {
+  const int v = 8 / (int)dtype_size(dtype);
+  const int need = (int)ceil_div(ceil_div(l, v), 32);
+  static const int avail[] = {2, 3, 4, 5, 6, 7, 8, 9, 10, 12, 14, 16, 18, 20, 24};
+  for (int a : avail)
+    if (a >= need) return a;
+  return 0;
+}
+
+// block width for the panel kernel: 2b padded columns plus T must fit in LDS
+static int jb_block_width(const rsvd_ctx *ctx, rsvd_dtype dtype, int64_t l) {
+  const size_t es = dtype_size(dtype);
+  const int nv = jb_units_per_lane(dtype, l);
+  if (nv == 0) return 0;
+  const size_t ldp = (size_t)32 * nv * (8 / es) + 2;
+  for (int b = 32; b >= 8; b -= 8) {
+    const size_t need = ((size_t)(2 * b) * ldp + (size_t)(2 * b) * (2 * b + 2)) * es + 1024;
+    if (need <= ctx->lds_per_block) return b;
+  }
+  return 0;
 }
 
 // Scratch of the block path: header, Mt, Jt, norms, ranks.
@@ -501,20 +570,35 @@ static hipError_t jacobi_block_launch(rsvd_ctx *ctx, hipStream_t s, rsvd_dtype d
   int *rnk = reinterpret_cast<int *>(p);
   const int nblk = (l + b - 1) / b;
   const int nblk2 = nblk + (nblk & 1);
-  const size_t lds = ((size_t)(2 * b) * (size_t)(l | 1) + (size_t)(2 * b) * ((2 * b) | 1)) * es;
-  static bool attr_set = false;
-  if (!attr_set) {
-    (void)hipFuncSetAttribute(reinterpret_cast<const void *>(&jb_panel_kernel<T, 32>),
-                              hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 512);
-    (void)hipGetLastError();
-    attr_set = true;
-  }
+  const int nv = jb_units_per_lane(dtype, l);
+  const size_t ldp = (size_t)32 * nv * (8 / es) + 2;
+  const size_t lds = ((size_t)(2 * b) * ldp + (size_t)(2 * b) * (2 * b + 2)) * es;
   ProfScope ps(ctx, s, PK_JACOBI);
   hipLaunchKernelGGL((jb_init_kernel<T>), dim3(1), dim3(1024), 0, s, M, l, Mt, Jt, hdr);
-  for (int sweep = 0; sweep < kJbMaxSweeps; ++sweep)
-    for (int round = 0; round < nblk2 - 1; ++round)
-      hipLaunchKernelGGL((jb_panel_kernel<T, 32>), dim3(nblk2 / 2), dim3(1024), lds, s, Mt, Jt, l, b, nblk, round,
-                         sweep, 2, hdr);
+#define RSVD_JB_CASE(NVV)                                                                                        \
+  case NVV: {                                                                                                    \
+    static bool attr_set = false;                                                                                \
+    if (!attr_set) {                                                                                             \
+      (void)hipFuncSetAttribute(reinterpret_cast<const void *>(&jb_panel_kernel<T, NVV>),                        \
+                                hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 512);                   \
+      (void)hipGetLastError();                                                                                   \
+      attr_set = true;                                                                                           \
+    }                                                                                                            \
+    for (int sweep = 0; sweep < kJbMaxSweeps; ++sweep) {                                                         \
+      hipLaunchKernelGGL((jb_panel_kernel<T, NVV>), dim3(nblk), dim3(1024), lds, s, Mt, Jt, l, b, nblk, 0, 0,    \
+                         sweep, hdr);                                                                            \
+      for (int round = 0; round < nblk2 - 1; ++round)                                                            \
+        hipLaunchKernelGGL((jb_panel_kernel<T, NVV>), dim3(nblk2 / 2), dim3(1024), lds, s, Mt, Jt, l, b, nblk,   \
+                           1, round, sweep, hdr);                                                                \
+    }                                                                                                            \
+  } break
+  switch (nv) {
+    RSVD_JB_CASE(2); RSVD_JB_CASE(3); RSVD_JB_CASE(4); RSVD_JB_CASE(5); RSVD_JB_CASE(6); RSVD_JB_CASE(7);
+    RSVD_JB_CASE(8); RSVD_JB_CASE(9); RSVD_JB_CASE(10); RSVD_JB_CASE(12); RSVD_JB_CASE(14); RSVD_JB_CASE(16);
+    RSVD_JB_CASE(18); RSVD_JB_CASE(20); RSVD_JB_CASE(24);
+    default: return hipErrorNotSupported;
+  }
+#undef RSVD_JB_CASE
   hipLaunchKernelGGL((jb_norms_kernel<T>), dim3((l + 3) / 4), dim3(256), 0, s, Mt, l, nrm);
   hipLaunchKernelGGL((jb_rank_kernel<T>), dim3((l + 255) / 256), dim3(256), 0, s, nrm, l, rnk, sigma, hdr,
                      kJbMaxSweeps, info);
