@@ -10,6 +10,10 @@
 //
 // Stopping rule (the paper gives none): a sweep in which every pair satisfies
 // |a_p . a_q| <= tol * ||a_p|| * ||a_q||, tol = eps * sqrt(l); at most 30 sweeps.
+// Jacobi converges quadratically (the paper: "3-4 iterations ... converges
+// quadratically"), so a sweep whose largest relative inner product rho was at
+// most sqrt(tol) / 4 leaves at most ~rho^2 < tol behind and is taken as the last
+// one, which saves the sweep that would only confirm it.
 // A column whose norm has fallen below eps * ||M||_F counts as zero and is no
 // longer rotated (rotating it would change its partner by less than the
 // rounding level); without this floor the surplus columns of a rank-deficient M
@@ -124,9 +128,10 @@ __device__ __forceinline__ bool rotate_pair(T *Mc, T *Jc, int ldm, int p, int q,
   alpha = half_row_sum(alpha);
   beta = half_row_sum(beta);
   gamma = half_row_sum(gamma);
-  if (alpha <= floor2 || beta <= floor2) return false;
+  if (alpha <= floor2 || beta <= floor2) return 0.f;
   const T limit = tol * fast_sqrt(alpha * beta);
-  if (!(fabs(gamma) > limit)) return false;
+  if (!(fabs(gamma) > limit)) return 0.f;
+  const float ratio = (float)(fabs(gamma) * fast_rsq(alpha * beta));
   unit *jp = reinterpret_cast<unit *>(Jc + p * ldm) + lg;
   unit *jq = reinterpret_cast<unit *>(Jc + q * ldm) + lg;
   unit u[NV], v[NV];
@@ -144,7 +149,7 @@ __device__ __forceinline__ bool rotate_pair(T *Mc, T *Jc, int ldm, int p, int q,
     jp[8 * r] = c * u[r] - s * v[r];
     jq[8 * r] = s * u[r] + c * v[r];
   }
-  return true;
+  return ratio;
 }
 
 // Padded row count and column stride of the LDS layout for order l.
@@ -191,21 +196,22 @@ __global__ __launch_bounds__(512) void jacobi_lds_kernel(const TIn *__restrict__
   // nt >= 8 * npairs: every pair of a round has its own lane group
   const bool has_pair = group < npairs;
   (void)ngroups;
+  const float rho_last = 0.25f * sqrtf((float)tol);
   while (!converged && sweeps < kJacobiMaxSweeps) {
     ++sweeps;
-    bool rotated = false;
+    float rho = 0.f;
     for (int r = 0; r < n2 - 1; ++r) {
       int a, b;
       tournament_pair(n2, r, has_pair ? group : 0, a, b);
       if (has_pair && a < l && b < l) {
         const int p = a < b ? a : b, q = a < b ? b : a;
-        rotated |= rotate_pair<T, RPL>(Mc, Jc, ldm, p, q, lg, tol, floor2);
+        rho = fmaxf(rho, rotate_pair<T, RPL>(Mc, Jc, ldm, p, q, lg, tol, floor2));
       }
       __syncthreads();
     }
-    if (rotated) rotations = 1;             // same value from every writer
+    if (rho > 0.f) atomicMax(&rotations, __float_as_int(rho));   // positive floats order like their bit patterns
     __syncthreads();
-    converged = (rotations == 0);
+    converged = (__int_as_float(rotations) <= rho_last);
     __syncthreads();
     if (tid == 0) rotations = 0;
     __syncthreads();
@@ -271,7 +277,7 @@ template <typename T> __device__ __forceinline__ T group32_sum(T v) {
 // (stride ldp, zero padded), 32 lanes per pair, the accumulated rotation T
 // (rows_t x rows_t, stride ldt) instead of J.
 template <typename T, int NV>
-__device__ __forceinline__ bool rotate_pair_panel(T *Pc, T *Tc, int ldp, int ldt, int rows_t, int p, int q, int lg,
+__device__ __forceinline__ float rotate_pair_panel(T *Pc, T *Tc, int ldp, int ldt, int rows_t, int p, int q, int lg,
                                                   T tol, T floor2) {
   constexpr int V = 8 / sizeof(T);
   typedef T unit __attribute__((ext_vector_type(V)));
@@ -292,9 +298,10 @@ __device__ __forceinline__ bool rotate_pair_panel(T *Pc, T *Tc, int ldp, int ldt
   alpha = group32_sum(alpha);
   beta = group32_sum(beta);
   gamma = group32_sum(gamma);
-  if (alpha <= floor2 || beta <= floor2) return false;
+  if (alpha <= floor2 || beta <= floor2) return 0.f;
   const T limit = tol * fast_sqrt(alpha * beta);
-  if (!(fabs(gamma) > limit)) return false;
+  if (!(fabs(gamma) > limit)) return 0.f;
+  const float ratio = (float)(fabs(gamma) * fast_rsq(alpha * beta));
   T c, s;
   rotation_params(alpha, beta, gamma, c, s);
 #pragma unroll
@@ -308,13 +315,13 @@ __device__ __forceinline__ bool rotate_pair_panel(T *Pc, T *Tc, int ldp, int ldt
     tp[i] = c * a - s * bq;
     tq[i] = s * a + c * bq;
   }
-  return true;
+  return ratio;
 }
 
 // scratch header shared by the block-Jacobi kernels
 struct JbHeader {
   double fro2;            // ||M||_F^2
-  int counters[64];       // rotations per outer sweep
+  int counters[64];       // per outer sweep: bit pattern of the largest relative inner product rotated away
 };
 
 template <typename T>
@@ -356,7 +363,9 @@ template <typename T, int NV> __host__ __device__ constexpr int jb_ldp() { retur
 template <typename T, int NV>
 __global__ __launch_bounds__(1024) void jb_panel_kernel(T *__restrict__ Mt, T *__restrict__ Jt, int l, int b,
                                                         int nblk, int phase, int round, int sweep, JbHeader *hdr) {
-  if (sweep > 0 && hdr->counters[sweep - 1] == 0) return;      // converged in the previous sweep
+  const T tol = Eps<T>::value * sqrt((T)l);
+  // converged in the previous sweep (see the stopping rule at the top of this file)
+  if (sweep > 0 && __int_as_float(hdr->counters[sweep - 1]) <= 0.25f * sqrtf((float)tol)) return;
   int bi, bj, cols_i, cols_j;
   if (phase == 0) {
     bi = bj = (int)blockIdx.x;
@@ -395,9 +404,8 @@ __global__ __launch_bounds__(1024) void jb_panel_kernel(T *__restrict__ Mt, T *_
   __syncthreads();
 
   const T floor2 = (T)(Eps<T>::value * Eps<T>::value * hdr->fro2);
-  const T tol = Eps<T>::value * sqrt((T)l);
   const int group = tid >> 5, lg = tid & 31;                   // 32 groups of 32 lanes, b <= 32
-  bool rotated = false;
+  float rho = 0.f;
   if (phase == 0) {
     const int n2 = ncols + (ncols & 1);
     for (int r = 0; r < n2 - 1; ++r) {
@@ -406,7 +414,7 @@ __global__ __launch_bounds__(1024) void jb_panel_kernel(T *__restrict__ Mt, T *_
         tournament_pair(n2, r, group, a, c2);
         if (a < ncols && c2 < ncols) {
           const int p = a < c2 ? a : c2, q = a < c2 ? c2 : a;
-          rotated |= rotate_pair_panel<T, NV>(Pc, Tc, ldp, ldt, ncols, p, q, lg, tol, floor2);
+          rho = fmaxf(rho, rotate_pair_panel<T, NV>(Pc, Tc, ldp, ldt, ncols, p, q, lg, tol, floor2));
         }
       }
       __syncthreads();
@@ -416,12 +424,14 @@ __global__ __launch_bounds__(1024) void jb_panel_kernel(T *__restrict__ Mt, T *_
       int qi = group + r;
       if (qi >= b) qi -= b;
       if (group < cols_i && qi < cols_j)
-        rotated |= rotate_pair_panel<T, NV>(Pc, Tc, ldp, ldt, ncols, group, cols_i + qi, lg, tol, floor2);
+        rho = fmaxf(rho, rotate_pair_panel<T, NV>(Pc, Tc, ldp, ldt, ncols, group, cols_i + qi, lg, tol, floor2));
       __syncthreads();
     }
   }
-  const int n_rot = __syncthreads_count(rotated && lg == 0);
-  if (n_rot == 0) return;                                     // nothing changed: leave M and J alone
+  if (rho > 0.f) atomicMax(&rotations, __float_as_int(rho));
+  __syncthreads();
+  const int rho_bits = rotations;
+  if (rho_bits == 0) return;                                  // nothing changed: leave M and J alone
 
   for (int c = tid / 64; c < ncols; c += nt / 64) {
     T *dst = Mt + (int64_t)gcol(c) * l;
@@ -456,7 +466,7 @@ __global__ __launch_bounds__(1024) void jb_panel_kernel(T *__restrict__ Mt, T *_
       }
     }
   }
-  if (tid == 0) atomicAdd(&hdr->counters[sweep], n_rot);
+  if (tid == 0) atomicMax(&hdr->counters[sweep], rho_bits);
 }
 
 // Column norms (one wavefront per column), then ranks by counting, then the scatter.
@@ -487,11 +497,12 @@ __global__ __launch_bounds__(256) void jb_rank_kernel(const T *__restrict__ nrm,
     sigma[rank] = mine;
   }
   if (j == 0 && info != nullptr) {
+    const float rho_last = 0.25f * sqrtf((float)(Eps<T>::value * sqrt((T)l)));
     int used = max_sweeps;
     for (int s = 0; s < max_sweeps; ++s)
-      if (hdr->counters[s] == 0) { used = s + 1; break; }
+      if (__int_as_float(hdr->counters[s]) <= rho_last) { used = s + 1; break; }
     atomicMax(&info->jacobi_sweeps, used);
-    if (hdr->counters[max_sweeps - 1] != 0) atomicMax(&info->status, (int)RSVD_ERR_NO_CONVERGENCE);
+    if (__int_as_float(hdr->counters[max_sweeps - 1]) > rho_last) atomicMax(&info->status, (int)RSVD_ERR_NO_CONVERGENCE);
   }
 }
 

@@ -120,3 +120,42 @@ def test_full_size_configs(cid):
     if cid == 1:      # planted spectrum, exact recovery expected
         S, _, _, _ = ctx().rsvd_run(A_dev, cfg.k, cfg.p, cfg.q, seed=cfg.seed)
         np.testing.assert_allclose(to_np(S), 10.0 ** (-np.arange(10) / 5.0), rtol=1e-11)
+
+
+@pytest.mark.parametrize("m,n,k,p", [(40, 12, 5, 7), (12, 40, 12, 0), (3, 5, 1, 0), (5, 3, 2, 1), (1, 1, 1, 0),
+                                     (17, 17, 17, 0), (2, 64, 1, 1)])
+@pytest.mark.parametrize("dt", ["f32", "f64"])
+def test_tiny_and_full_sketch_shapes(m, n, k, p, dt):
+    """Degenerate sizes; with l = min(m, n) the result is the plain SVD (no approximation left)."""
+    say("tiny", m, n, k, p, dt)
+    npdt = np.float32 if dt == "f32" else np.float64
+    A = workloads.gaussian_matrix(m, n, seed=m * 100 + n, dtype=npdt)
+    S, U, Vt, info = ctx().rsvd_run(to_dev(A), k, p, 1, seed=3)
+    S, U, Vt = (to_np(t).astype(np.float64) for t in (S, U, Vt))
+    assert info.status == 0
+    A64 = A.astype(np.float64)
+    o = orc.rsvd(A64, k, p, 1, 3, npdt)
+    eps = parity.EPS[dt]
+    np.testing.assert_allclose(S, o.S, rtol=parity.SV_RTOL[dt], atol=10 * eps * o.S[0])
+    if k + p == min(m, n):
+        np.testing.assert_allclose(S, np.linalg.svd(A64, compute_uv=False)[:k], rtol=parity.SV_RTOL[dt],
+                                   atol=10 * eps * o.S[0])
+    err_g = orc.reconstruction_error(A64, U, S, Vt)
+    err_o = orc.reconstruction_error(A64, o.U, o.S, o.Vt)
+    assert err_g <= 1.01 * err_o + 50 * eps * np.linalg.norm(A64)
+
+
+def test_unaligned_views():
+    """Base pointers and leading dimensions that defeat the 16-byte load path."""
+    import torch
+    cfg = scaled(CONFIGS[2], 301, 203, k=9, p=6)
+    A = workloads.build(cfg)
+    big = torch.zeros((302, 207), dtype=torch.float32, device="cuda:0")
+    view = big[1:, 3:206]                     # offset by 3 floats, ld 207
+    view.copy_(to_dev(A))
+    c = ctx()
+    S0, U0, Vt0, _ = c.rsvd_run(to_dev(A), cfg.k, cfg.p, cfg.q)
+    S1, U1, Vt1, _ = c.rsvd_run(view, cfg.k, cfg.p, cfg.q)
+    np.testing.assert_allclose(to_np(S1), to_np(S0), rtol=1e-5)
+    assert parity.sin_theta(to_np(U1), to_np(U0)) <= 1e-3
+    run_and_compare(cfg, view, A)
