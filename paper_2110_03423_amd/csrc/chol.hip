@@ -30,8 +30,8 @@ __device__ __forceinline__ double fast_rsqrt(double d) {
 // added here, in a fixed order).
 // Right-looking elimination, one step per column j: the owners of row j publish
 // it through double-buffered LDS lines (one barrier per step); every thread then
-// applies the rank-one update to its elements of S (both triangles, so the inner
-// loop carries no masks) and of Z.  Row j of R and column j of R^-1 are final at
+// applies the update to its elements of S (blocks on or above the block diagonal,
+// whole 16 x 16 blocks so the inner loop carries no masks) and of Z.  Row j of R and column j of R^-1 are final at
 // step j and go straight to global memory.
 //   g0    : original squared column norms for the pivot test, or NULL to use the diagonal
 //   Rinv  : nb x nb block of R^-1 (ld ldri, type TOut, zeros below the diagonal)
@@ -45,18 +45,18 @@ __global__ __launch_bounds__(TG * TG) void chol_block_kernel(const double *__res
                                                               double *__restrict__ R, int64_t ldr,
                                                               int *__restrict__ dead, DevInfo *info) {
   constexpr int LMAX = TG * NR;
-  __shared__ double bufS[2][LMAX];
-  __shared__ double bufZ[2][LMAX];
+  __shared__ double bufS[2][LMAX], bufS1[2][LMAX];    // rows j and j+1 of S, double buffered
+  __shared__ double bufZ[2][LMAX], bufZ1[2][LMAX];    // the same rows of Z
   __shared__ double d0[LMAX];
   __shared__ double zdiag[LMAX];
-  __shared__ int n_dead, bad;
+  __shared__ int n_dead, n_dead2, bad;
   extern __shared__ double outm[];       // nb x (LMAX + 1): finished rows of R and Z
   constexpr int ost = LMAX + 1;
   const int tid = threadIdx.x;
   const int tx = tid % TG, ty = tid / TG;
   double S[NR][NR], Z[NR][NR];
 
-  if (tid == 0) { n_dead = 0; bad = 0; }
+  if (tid == 0) { n_dead = 0; n_dead2 = 0; bad = 0; }
 #pragma unroll
   for (int a = 0; a < NR; ++a)
 #pragma unroll
@@ -94,62 +94,90 @@ __global__ __launch_bounds__(TG * TG) void chol_block_kernel(const double *__res
         d0[i] = d;
         if (!(fabs(d) <= 1.79e308)) bad = 1;      // NaN or Inf
       }
+      if (i == c && i == nb) { S[a][b] = 1.0; d0[i] = 1.0; }      // padding column of an odd order
     }
 
-  // The step loop is unrolled over the 16-wide row blocks (A0 is a compile-time
-  // constant inside), so the register that holds row j is addressed statically and
-  // blocks that can no longer change are dropped at compile time: branches inside
-  // the step cost more than the arithmetic they would save.
+  // Two columns per step (a 2 x 2 pivot block): half as many barriers and LDS round
+  // trips as column-by-column elimination, same arithmetic.  The loop is unrolled over
+  // the 16-wide row blocks (A0 is a compile-time constant inside), so the registers that
+  // hold rows j, j+1 are addressed statically and blocks that can no longer change are
+  // dropped at compile time: branches inside a step cost more than the arithmetic they
+  // would save.  An odd order is padded with a unit diagonal entry.
 #pragma unroll
   for (int A0 = 0; A0 < NR; ++A0) {
-    for (int jj = 0; jj < TG; ++jj) {
+    for (int jj = 0; jj < TG; jj += 2) {
       const int j = A0 * TG + jj;
       if (j >= nb) break;
-      double *bs = bufS[j & 1], *bz = bufZ[j & 1];
-      const bool own_row = (jj == ty);
-      if (own_row) {
+      const int par = (j >> 1) & 1;
+      double *bs0 = bufS[par], *bz0 = bufZ[par], *bs1 = bufS1[par], *bz1 = bufZ1[par];
+      if (ty == jj) {
 #pragma unroll
-        for (int b = 0; b < NR; ++b) {
-          const int c = tx + TG * b;
-          bs[c] = S[A0][b];
-          bz[c] = Z[A0][b];
-        }
+        for (int b = 0; b < NR; ++b) { bs0[tx + TG * b] = S[A0][b]; bz0[tx + TG * b] = Z[A0][b]; }
+      }
+      if (ty == jj + 1) {
+#pragma unroll
+        for (int b = 0; b < NR; ++b) { bs1[tx + TG * b] = S[A0][b]; bz1[tx + TG * b] = Z[A0][b]; }
       }
       __syncthreads();
-      const double d = bs[j], dj0 = d0[j];
-      const bool is_dead = !(d > tau * dj0) || !(dj0 > 0.0);
-      const double rinv = is_dead ? 0.0 : fast_rsqrt(d);
-      double srow[NR], zrow[NR], lcol[NR];
+      const double d00 = bs0[j], d01 = bs0[j + 1], d11 = bs1[j + 1];
+      const double dj0 = d0[j], dj1 = d0[j + 1];
+      const bool dead0 = !(d00 > tau * dj0) || !(dj0 > 0.0);
+      const double rinv0 = dead0 ? 0.0 : fast_rsqrt(d00);
+      const double r01 = d01 * rinv0;
+      const double d11p = d11 - r01 * r01;
+      const bool dead1 = !(d11p > tau * dj1) || !(dj1 > 0.0);
+      const double rinv1 = dead1 ? 0.0 : fast_rsqrt(d11p);
+      double s0[NR], s1[NR], z0[NR], z1[NR], l0[NR], l1[NR];
 #pragma unroll
       for (int b = 0; b < NR; ++b) {
         const int c = tx + TG * b;
-        srow[b] = (b >= A0 && c > j) ? bs[c] * rinv : 0.0;     // R[j][c]; columns >= nb hold zeros
-        zrow[b] = (b <= A0 && c <= j) ? ((c == j) ? rinv : bz[c] * rinv) : 0.0;          // Z[j][c]
+        const double t0 = (b >= A0) ? bs0[c] * rinv0 : 0.0;                    // R[j][c] for c > j
+        s0[b] = (c > j) ? t0 : 0.0;
+        s1[b] = (b >= A0 && c > j + 1) ? (bs1[c] - r01 * t0) * rinv1 : 0.0;    // R[j+1][c]
+        const double u0 = (b <= A0) ? ((c < j) ? bz0[c] * rinv0 : ((c == j) ? rinv0 : 0.0)) : 0.0;   // Z[j][c]
+        z0[b] = u0;
+        z1[b] = (b <= A0) ? ((c <= j) ? (bz1[c] - r01 * u0) * rinv1 : ((c == j + 1) ? rinv1 : 0.0)) : 0.0;
       }
 #pragma unroll
       for (int a = 0; a < NR; ++a) {
         const int i = ty + TG * a;
-        lcol[a] = (a >= A0 && i > j) ? bs[i] * rinv : 0.0;     // R[j][i]
+        const bool below = (a >= A0) && (i > j + 1);
+        const double t0 = below ? bs0[i] * rinv0 : 0.0;                        // R[j][i]
+        l0[a] = t0;
+        l1[a] = below ? (bs1[i] - r01 * t0) * rinv1 : 0.0;                     // R[j+1][i]
       }
 #pragma unroll
       for (int a = A0; a < NR; ++a)
 #pragma unroll
         for (int b = 0; b < NR; ++b) {
-          if (b >= A0) S[a][b] = fma(-lcol[a], srow[b], S[a][b]);
-          if (b <= A0) Z[a][b] = fma(-lcol[a], zrow[b], Z[a][b]);
+          if (b >= a) S[a][b] = fma(-l1[a], s1[b], fma(-l0[a], s0[b], S[a][b]));   // upper block triangle only
+          if (b <= A0) Z[a][b] = fma(-l1[a], z1[b], fma(-l0[a], z0[b], Z[a][b]));
         }
-      if (own_row) {
-        // row j of R and row j of Z (= column j of R^-1) are final: park them in LDS
-        const double rjj = is_dead ? 0.0 : d * rinv;
+      // rows j, j+1 of R and of Z (= columns of R^-1) are final: park them in LDS
+      if (ty == jj) {
+        const double r00 = dead0 ? 0.0 : d00 * rinv0;
 #pragma unroll
         for (int b = 0; b < NR; ++b) {
           const int c = tx + TG * b;
-          outm[j * ost + c] = (c > j) ? srow[b] : ((c == j) ? rjj : zrow[b]);
+          outm[j * ost + c] = (c > j) ? s0[b] : ((c == j) ? r00 : z0[b]);
         }
         if (tx == jj) {
-          zdiag[j] = rinv;
-          dead[j] = is_dead ? 1 : 0;
-          if (is_dead) n_dead += 1;                                // single writer per step
+          zdiag[j] = rinv0;
+          dead[j] = dead0 ? 1 : 0;
+          if (dead0) n_dead += 1;                                  // single writer
+        }
+      }
+      if (ty == jj + 1) {
+        const double r11 = dead1 ? 0.0 : d11p * rinv1;
+#pragma unroll
+        for (int b = 0; b < NR; ++b) {
+          const int c = tx + TG * b;
+          outm[(j + 1) * ost + c] = (c > j + 1) ? s1[b] : ((c == j + 1) ? r11 : z1[b]);
+        }
+        if (tx == jj + 1 && j + 1 < nb) {
+          zdiag[j + 1] = rinv1;
+          dead[j + 1] = dead1 ? 1 : 0;
+          if (dead1) n_dead2 += 1;                                 // single writer
         }
       }
     }
@@ -166,7 +194,7 @@ __global__ __launch_bounds__(TG * TG) void chol_block_kernel(const double *__res
   }
   __syncthreads();
   if (tid == 0 && info != nullptr) {
-    if (n_dead > 0) atomicAdd(&info->refilled, n_dead);
+    if (n_dead + n_dead2 > 0) atomicAdd(&info->refilled, n_dead + n_dead2);
     if (bad) atomicMax(&info->status, (int)RSVD_ERR_NONFINITE);
   }
 }
@@ -221,7 +249,7 @@ static hipError_t launch_block(hipStream_t s, const double *G, int64_t ldg, int 
   // 256 threads (one wavefront per SIMD) keep the per-step barrier cheap; each thread
   // holds NR x NR elements of S and of Z, NR = ceil(nb / 16); above 96 the register
   // budget asks for 1024 threads with 4 x 4 elements.
-  const size_t lds = (size_t)nb * ((size_t)((nb + 15) / 16 > 6 ? 128 : ((nb + 15) / 16) * 16) + 1) * sizeof(double);
+  const size_t lds = (size_t)(nb + 1) * ((size_t)((nb + 15) / 16 > 6 ? 128 : ((nb + 15) / 16) * 16) + 1) * sizeof(double);
 #define RSVD_CHOL_CASE(TGV, NRV)                                                                                    \
   do {                                                                                                              \
     static bool attr_set = false;                                                                                   \

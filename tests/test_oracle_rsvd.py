@@ -147,3 +147,19 @@ def test_parity_metric_helpers():
     assert parity.sin_theta(Q, Q @ workloads.orthonormal_factor(4, 4, 2)) < 1e-14
     P = workloads.orthonormal_factor(30, 30, 3)
     assert parity.sin_theta(P[:, :4], P[:, 4:8]) == pytest.approx(1.0)
+
+
+def test_paper_fast_decay_accuracy_claim():
+    """Experiments, performance comparison: on the fast-decay spectrum the randomized values can be held within
+    1e-8 (relative) of a full SVD; how many power iterations that takes follows (sigma_l / sigma_i)^(4q+2)."""
+    cfg = workloads.paper_case("fast", 300, 0.05, m=600)
+    A = workloads.build(cfg)
+    true = np.linalg.svd(A, compute_uv=False)[:cfg.k]
+    np.testing.assert_allclose(true, workloads.PAPER_SPECTRA["fast"](np.arange(cfg.k)), rtol=1e-10)
+    worst = []
+    for q in (1, 2, 4):
+        out = orc.rsvd(A, cfg.k, 10, q, 0, np.float64)
+        worst.append(np.max(np.abs(out.S - true) / true))
+    assert worst[0] > worst[1] > worst[2] and worst[2] <= 1e-8       # q = 4, p = 10 reaches the paper's level
+    out = orc.rsvd(A, cfg.k, 30, 2, 0, np.float64)                    # so does q = 2 with more oversampling
+    assert np.max(np.abs(out.S - true) / true) <= 1e-8

@@ -62,6 +62,21 @@ CONFIGS = {
 }
 
 
+# The three spectra of the paper's performance comparison (Experiments section), 1-based there, 0-based index i here.
+PAPER_SPECTRA = {
+    "fast": lambda i: 1.0 / (1.0 + i) ** 2,                                   # sigma_ii = 1 / i^2
+    "sharp": lambda i, beta=20.0: 1e-4 + 1.0 / (1.0 + np.exp(i + 2.0 - beta)),  # 0.0001 + 1/(1 + exp(i + 1 - beta))
+    "slow": lambda i: 1.0 / (1.0 + i) ** 0.1,                                 # sigma_ii = 1 / i^0.1
+}
+
+
+def paper_case(kind: str, n: int, frac: float, dtype: str = "f64", m: int = 2000, p: int = 10, q: int = 2) -> Config:
+    """A = U Sigma V^T of size m x n (the paper uses A^{2000 x n}) with one of its spectra, k = ceil(frac * n)."""
+    k = int(np.ceil(frac * n))
+    return Config(10 + list(PAPER_SPECTRA).index(kind), f"paper-{kind}-{m}x{n}-k{k}", dtype, m, n, min(m, n), k, p, q,
+                  spectrum=PAPER_SPECTRA[kind])
+
+
 def scaled(cfg: Config, m: int, n: int, rank=None, k=None, p=None) -> Config:
     """Same recipe at another size (parity cases and CPU-side replicas)."""
     rank = min(cfg.rank if rank is None else rank, m, n)
