@@ -108,6 +108,21 @@ int rsvd_run(rsvd_ctx *ctx, void *stream, rsvd_dtype dtype, rsvd_job job,
              void *S, void *U, int64_t ldu, void *Vt, int64_t ldvt,
              void *workspace, size_t workspace_bytes, rsvd_info *info);
 
+/*
+ * The paper's PCA application: the same decomposition of the column-centred
+ * matrix A - 1 mu^T (mu = column means of A, rows = observations), computed
+ * without forming that matrix - every product with A or A^T gets its rank-one
+ * correction in the epilogue of the product kernel.  S^2 / (m - 1) are the
+ * variances along the principal axes, the rows of Vt the axes, U diag(S) the
+ * scores.  Arguments as rsvd_run, positions 1-20 unchanged; `mean` (device,
+ * n values, may be NULL) receives mu.
+ */
+int rsvd_run_centered(rsvd_ctx *ctx, void *stream, rsvd_dtype dtype, rsvd_job job,
+                      int64_t m, int64_t n, const void *A, int64_t lda,
+                      int k, int p, int q, uint64_t seed,
+                      void *S, void *U, int64_t ldu, void *Vt, int64_t ldvt,
+                      void *workspace, size_t workspace_bytes, rsvd_info *info, void *mean);
+
 /* ---- stage entry points: each step of Algorithm 1 on its own, for per-stage
  * parity tests and timing.  They run the same kernels as rsvd_run. ---- */
 

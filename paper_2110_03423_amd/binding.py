@@ -38,6 +38,8 @@ PROTOTYPES = {
     "rsvd_workspace_bytes": [_VP, _INT, _I64, _I64, _INT, _INT, _INT, _INT, C.POINTER(_SZ)],
     "rsvd_run": [_VP, _VP, _INT, _INT, _I64, _I64, _VP, _I64, _INT, _INT, _INT, _U64,
                  _VP, _VP, _I64, _VP, _I64, _VP, _SZ, C.POINTER(_Info)],
+    "rsvd_run_centered": [_VP, _VP, _INT, _INT, _I64, _I64, _VP, _I64, _INT, _INT, _INT, _U64,
+                          _VP, _VP, _I64, _VP, _I64, _VP, _SZ, C.POINTER(_Info), _VP],
     "rsvd_stage_sketch": [_VP, _VP, _INT, _U64, _U32, _I64, _I64, _VP, _I64],
     "rsvd_stage_philox_raw": [_VP, _VP, _U64, _U32, _U64, _I64, _VP],
     "rsvd_stage_gemm_an": [_VP, _VP, _INT, _I64, _I64, _I64, _VP, _I64, _VP, _I64, _VP, _I64, _VP, _SZ],
@@ -145,7 +147,13 @@ class Rsvd:
         return self.torch.empty(shape, dtype=like.dtype, device=self.device)
 
     # ---- Algorithm 1
-    def rsvd_run(self, A, k, p, q, seed=0, job=JOB_SUV, workspace=None, want_info=True, out=None):
+    def rsvd_run_centered(self, A, k, p, q, seed=0, job=JOB_SUV, workspace=None, want_info=True, out=None):
+        """PCA front end: decomposition of A minus its column means.  Returns (S, U, Vt, info, mean)."""
+        mean = self._empty((A.shape[1],), A)
+        S, U, Vt, info = self.rsvd_run(A, k, p, q, seed, job, workspace, want_info, out, _mean=mean)
+        return S, U, Vt, info, mean
+
+    def rsvd_run(self, A, k, p, q, seed=0, job=JOB_SUV, workspace=None, want_info=True, out=None, _mean=None):
         """Returns (S, U, Vt, info).  A: row-major (m, n) device tensor, stride(1) == 1."""
         assert A.is_cuda and A.dim() == 2 and A.stride(1) == 1
         m, n = A.shape
@@ -158,10 +166,14 @@ class Rsvd:
         else:
             S, U, Vt = out
         info = _Info()
-        rc = self.lib.rsvd_run(self.h, self._stream(), dt, job, m, n, _ptr(A), A.stride(0), k, p, q, seed,
-                               _ptr(S), _ptr(U), U.stride(0) if U is not None else 0,
-                               _ptr(Vt), Vt.stride(0) if Vt is not None else 0,
-                               _ptr(ws), ws.numel(), C.byref(info) if want_info else None)
+        args = (self.h, self._stream(), dt, job, m, n, _ptr(A), A.stride(0), k, p, q, seed,
+                _ptr(S), _ptr(U), U.stride(0) if U is not None else 0,
+                _ptr(Vt), Vt.stride(0) if Vt is not None else 0,
+                _ptr(ws), ws.numel(), C.byref(info) if want_info else None)
+        if _mean is None:
+            rc = self.lib.rsvd_run(*args)
+        else:
+            rc = self.lib.rsvd_run_centered(*args, _ptr(_mean))
         self._check(rc)
         return S, U, Vt, (info if want_info else None)
 

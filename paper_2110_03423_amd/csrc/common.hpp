@@ -32,7 +32,7 @@ inline size_t dtype_size(rsvd_dtype d) { return d == RSVD_F32 ? 4 : 8; }
 // Kernel classes reported by the profiling interface.
 enum ProfKind {
   PK_SKETCH = 0, PK_GEMM_AX, PK_GEMM_AX_REDUCE, PK_GEMM_ATX, PK_GEMM_ATX_REDUCE, PK_GRAM, PK_GRAM_REDUCE,
-  PK_CHOL, PK_APPLY, PK_JACOBI, PK_LIFT, PK_SMALL, PK_COUNT
+  PK_CHOL, PK_APPLY, PK_JACOBI, PK_LIFT, PK_SMALL, PK_COUNT      // PK_SMALL also covers the mean / shift vectors of the centred variant
 };
 
 // Brackets one kernel launch with a HIP event pair when profiling is on.
@@ -78,6 +78,9 @@ struct GemmDesc {
   const void *B = nullptr; int64_t ldb = 0;
   void *C = nullptr;       int64_t ldc = 0;
   double alpha = 1.0, beta = 0.0;
+  // r1_v != NULL: C[i][j] += r1_alpha * u[i] * v[j] with u = r1_u (length M) or all ones when
+  // r1_u == NULL, v = r1_v (length N), both in the output type; applied once, after any split-K sum.
+  const void *r1_u = nullptr; const void *r1_v = nullptr; double r1_alpha = 0.0;
   const int *dead = nullptr;
   uint64_t seed = 0; uint32_t refill_stream = 0; double refill_scale = 1.0; int64_t refill_ld = 0;
   void *partial = nullptr; size_t partial_bytes = 0;   // split-K scratch

@@ -33,6 +33,7 @@ struct GemmParams {
   int tiles_n, tiles_m;     // grid shape in tiles; the launch is one-dimensional
   int trans_c;
   double alpha, beta;
+  const void *r1_u; const void *r1_v; double r1_alpha;
   const int *dead;
   uint64_t seed; uint32_t refill_stream; double refill_scale; int64_t refill_ld;
 };
@@ -42,6 +43,10 @@ template <typename TOut, typename TAcc, bool F32STREAM>
 __device__ __forceinline__ void store_result(const GemmParams &P, int64_t row, int64_t col, TAcc acc) {
   TOut *C = (TOut *)P.C;
   double v = P.alpha * (double)acc;
+  if (P.r1_v != nullptr) {
+    const double u = (P.r1_u != nullptr) ? (double)((const TOut *)P.r1_u)[row] : 1.0;
+    v += P.r1_alpha * u * (double)((const TOut *)P.r1_v)[col];
+  }
   if (P.dead != nullptr && P.dead[col] != 0) {
     v = P.refill_scale *
         philox_normal_at<F32STREAM>((uint64_t)(row * P.refill_ld + col), P.refill_stream, P.seed);
@@ -333,6 +338,7 @@ struct GemmDispatch {
     P.A = d.A; P.lda = d.lda; P.B = d.B; P.ldb = d.ldb; P.C = d.C; P.ldc = d.ldc;
     P.partial = d.partial; P.k_per_split = c.k_per_split; P.splits = c.splits;
     P.trans_c = d.trans_c; P.alpha = d.alpha; P.beta = d.beta;
+    P.r1_u = d.r1_u; P.r1_v = d.r1_v; P.r1_alpha = d.r1_alpha;
     P.dead = d.dead; P.seed = d.seed; P.refill_stream = d.refill_stream;
     P.refill_scale = d.refill_scale; P.refill_ld = d.refill_ld;
     // 16-byte vector loads need aligned bases, leading dimensions and extents.

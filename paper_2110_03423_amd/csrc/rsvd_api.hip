@@ -41,6 +41,61 @@ __global__ void copy_kernel(const T *__restrict__ src, T *__restrict__ dst, int6
     dst[e] = src[e];
 }
 
+// out[j] = alpha * sum_i w[i] * X[i][j] (w == NULL: all ones), accumulated in fp64 in two
+// deterministic stages: row chunks of kColsumRows, then the chunks in order.  Serves the
+// column means and the shift vectors of the centred variant.
+constexpr int kColsumRows = 512;
+
+template <typename T>
+__global__ __launch_bounds__(256) void colsum_partial_kernel(const T *__restrict__ X, int64_t ldx, int64_t rows,
+                                                             int64_t cols, const T *__restrict__ w,
+                                                             double *__restrict__ partial) {
+  const int64_t j = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  const int64_t r0 = (int64_t)blockIdx.y * kColsumRows;
+  const int64_t r1 = (r0 + kColsumRows < rows) ? r0 + kColsumRows : rows;
+  if (j >= cols) return;
+  double acc = 0.0;
+  for (int64_t i = r0; i < r1; ++i) {
+    const double x = (double)X[i * ldx + j];
+    acc += (w != nullptr) ? (double)w[i] * x : x;
+  }
+  partial[(int64_t)blockIdx.y * cols + j] = acc;
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void colsum_final_kernel(const double *__restrict__ partial, int chunks, int64_t cols,
+                                                           double alpha, T *__restrict__ out) {
+  const int64_t j = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (j >= cols) return;
+  double acc = 0.0;
+  for (int c = 0; c < chunks; ++c) acc += partial[(int64_t)c * cols + j];
+  out[j] = (T)(alpha * acc);
+}
+
+static size_t colsum_partial_bytes(int64_t rows, int64_t cols) {
+  return (size_t)ceil_div(rows, kColsumRows) * (size_t)cols * sizeof(double);
+}
+
+static hipError_t colsum_launch(hipStream_t s, rsvd_dtype dtype, const void *X, int64_t ldx, int64_t rows, int64_t cols,
+                                const void *w, double alpha, void *out, void *partial, size_t partial_bytes) {
+  const int chunks = (int)ceil_div(rows, kColsumRows);
+  if (partial == nullptr || partial_bytes < colsum_partial_bytes(rows, cols)) return hipErrorInvalidValue;
+  dim3 grid((unsigned)ceil_div(cols, 256), (unsigned)chunks);
+  dim3 grid2((unsigned)ceil_div(cols, 256));
+  if (dtype == RSVD_F32) {
+    hipLaunchKernelGGL(colsum_partial_kernel<float>, grid, dim3(256), 0, s, (const float *)X, ldx, rows, cols,
+                       (const float *)w, (double *)partial);
+    hipLaunchKernelGGL(colsum_final_kernel<float>, grid2, dim3(256), 0, s, (const double *)partial, chunks, cols,
+                       alpha, (float *)out);
+  } else {
+    hipLaunchKernelGGL(colsum_partial_kernel<double>, grid, dim3(256), 0, s, (const double *)X, ldx, rows, cols,
+                       (const double *)w, (double *)partial);
+    hipLaunchKernelGGL(colsum_final_kernel<double>, grid2, dim3(256), 0, s, (const double *)partial, chunks, cols,
+                       alpha, (double *)out);
+  }
+  return hipGetLastError();
+}
+
 static hipError_t copy_launch(hipStream_t s, rsvd_dtype dtype, const void *src, void *dst, int64_t n) {
   if (n <= 0) return hipSuccess;
   int64_t blocks = ceil_div(n, 256);
@@ -73,6 +128,7 @@ struct Layout {
   size_t dead, info;                // flags per column, DevInfo
   size_t sigma, Wj, Xj;             // all l triplets of step 5: sigma, Ub (= W), X
   size_t jac_scratch, jac_scratch_bytes;
+  size_t mean, shift;               // centred variant: column means (n), shift vector (l)
   size_t total;
 };
 
@@ -90,6 +146,9 @@ static Layout make_layout(const rsvd_ctx *ctx, rsvd_dtype dtype, int64_t m, int6
   if ((t = gemm_partial_bytes(ctx, kind, 1, n, l, m)) > pb) pb = t;
   if ((t = gemm_partial_bytes(ctx, gram, 1, l, l, m)) > pb) pb = t;
   if ((t = gemm_partial_bytes(ctx, gram, 1, l, l, n)) > pb) pb = t;
+  if ((t = colsum_partial_bytes(m, n)) > pb) pb = t;      // column means of the centred variant
+  if ((t = colsum_partial_bytes(m, l)) > pb) pb = t;      // and its shift vectors
+  if ((t = colsum_partial_bytes(n, l)) > pb) pb = t;
   L.partial_bytes = pb;
   L.partial = take(pb);
   L.G = take((size_t)l * l * 8);
@@ -105,6 +164,8 @@ static Layout make_layout(const rsvd_ctx *ctx, rsvd_dtype dtype, int64_t m, int6
   L.Xj = take((size_t)l * l * es);
   L.jac_scratch_bytes = jacobi_scratch_bytes(ctx, dtype, l);
   L.jac_scratch = take(L.jac_scratch_bytes);
+  L.mean = take((size_t)n * es);
+  L.shift = take((size_t)l * es);
   L.total = off;
   return L;
 }
@@ -184,9 +245,11 @@ static int orthonormalize(rsvd_ctx *ctx, hipStream_t s, rsvd_dtype dtype, const 
 
 static int product(rsvd_ctx *ctx, hipStream_t s, rsvd_dtype dtype, const Ws &w, int trans_a, int64_t M, int64_t N,
                    int64_t K, const void *A, int64_t lda, const void *B, int64_t ldb, void *C, int64_t ldc,
-                   int trans_c, bool allow_split, int prof_kind) {
+                   int trans_c, bool allow_split, int prof_kind, double alpha = 1.0, const void *r1_u = nullptr,
+                   const void *r1_v = nullptr, double r1_alpha = 0.0) {
   GemmDesc d;
   d.prof_kind = prof_kind;
+  d.alpha = alpha; d.r1_u = r1_u; d.r1_v = r1_v; d.r1_alpha = r1_alpha;
   d.trans_a = trans_a; d.trans_c = trans_c; d.M = M; d.N = N; d.K = K;
   d.A = A; d.lda = lda; d.B = B; d.ldb = ldb; d.C = C; d.ldc = ldc;
   if (allow_split) { d.partial = w.at<void>(w.L.partial); d.partial_bytes = w.L.partial_bytes; }
@@ -318,9 +381,13 @@ int rsvd_workspace_bytes(rsvd_ctx *ctx, rsvd_dtype dtype, int64_t m, int64_t n, 
   return 0;
 }
 
-int rsvd_run(rsvd_ctx *ctx, void *stream, rsvd_dtype dtype, rsvd_job job, int64_t m, int64_t n, const void *A,
-             int64_t lda, int k, int p, int q, uint64_t seed, void *S, void *U, int64_t ldu, void *Vt, int64_t ldvt,
-             void *workspace, size_t workspace_bytes, rsvd_info *info) {
+// Algorithm 1 on A, or (center != 0) on A - 1 mu^T with mu the column means of A, without forming that matrix:
+//   (A - 1 mu^T) X = A X - 1 (mu^T X),   (A - 1 mu^T)^T Q = A^T Q - mu (1^T Q),
+// the rank-one terms being added in the epilogue of the same product kernels.
+static int run_impl(rsvd_ctx *ctx, void *stream, rsvd_dtype dtype, rsvd_job job, int64_t m, int64_t n, const void *A,
+                    int64_t lda, int k, int p, int q, uint64_t seed, void *S, void *U, int64_t ldu, void *Vt,
+                    int64_t ldvt, void *workspace, size_t workspace_bytes, rsvd_info *info, int center,
+                    void *mean_out) {
   if (ctx == nullptr) return -1;
   if (!valid_dtype(dtype)) return -3;
   if (job < RSVD_JOB_S || job > RSVD_JOB_SUV) return -4;
@@ -350,6 +417,31 @@ int rsvd_run(rsvd_ctx *ctx, void *stream, rsvd_dtype dtype, rsvd_job job, int64_
   int rc;
 
   RSVD_TRY(zero_ints_launch(s, w.at<int>(L.info), 4), "zero info");
+  void *mean = w.at<void>(L.mean), *shift = w.at<void>(L.shift);
+  void *part = w.at<void>(L.partial);
+  if (center) {
+    // mu = A^T 1 / m
+    ProfScope ps(ctx, s, PK_SMALL);
+    RSVD_TRY(colsum_launch(s, dtype, A, lda, m, n, nullptr, 1.0 / (double)m, mean, part, L.partial_bytes), "means");
+    if (mean_out != nullptr) RSVD_TRY(copy_launch(s, dtype, mean, mean_out, n), "copy mean");
+  }
+  // products with the (optionally centred) matrix; X is n x l for A X, m x l for A^T X
+  auto times_a = [&](const void *X, void *Y) -> int {
+    if (!center) return product(ctx, s, dtype, w, 0, m, l, n, A, lda, X, l, Y, l, 0, true, PK_GEMM_AX);
+    {
+      ProfScope ps(ctx, s, PK_SMALL);                                                                 // X^T mu
+      RSVD_TRY(colsum_launch(s, dtype, X, l, n, l, mean, 1.0, shift, part, L.partial_bytes), "shift");
+    }
+    return product(ctx, s, dtype, w, 0, m, l, n, A, lda, X, l, Y, l, 0, true, PK_GEMM_AX, 1.0, nullptr, shift, -1.0);
+  };
+  auto times_at = [&](const void *X, void *Z) -> int {
+    if (!center) return product(ctx, s, dtype, w, 1, n, l, m, A, lda, X, l, Z, l, 0, true, PK_GEMM_ATX);
+    {
+      ProfScope ps(ctx, s, PK_SMALL);                                                                 // X^T 1
+      RSVD_TRY(colsum_launch(s, dtype, X, l, m, l, nullptr, 1.0, shift, part, L.partial_bytes), "shift");
+    }
+    return product(ctx, s, dtype, w, 1, n, l, m, A, lda, X, l, Z, l, 0, true, PK_GEMM_ATX, 1.0, mean, shift, -1.0);
+  };
   // step 1
   {
     ProfScope ps(ctx, s, PK_SKETCH);
@@ -361,23 +453,23 @@ int rsvd_run(rsvd_ctx *ctx, void *stream, rsvd_dtype dtype, rsvd_job job, int64_
   void *curN = bN0, *othN = bN1, *curM = bM0, *othM = bM1;
   uint32_t refill = 16;
   auto swap = [](void *&a, void *&b) { void *t = a; a = b; b = t; };
-  if ((rc = product(ctx, s, dtype, w, 0, m, l, n, A, lda, curN, l, curM, l, 0, true, PK_GEMM_AX))) return rc;
+  if ((rc = times_a(curN, curM))) return rc;
   if ((rc = orthonormalize(ctx, s, dtype, w, m, l, curM, l, othM, nullptr, seed, refill, q == 0 ? 2 : 1))) return rc;
   if (q > 0) swap(curM, othM);
   refill += 2;
   for (int it = 0; it < q; ++it) {
-    if ((rc = product(ctx, s, dtype, w, 1, n, l, m, A, lda, curM, l, curN, l, 0, true, PK_GEMM_ATX))) return rc;
+    if ((rc = times_at(curM, curN))) return rc;
     if ((rc = orthonormalize(ctx, s, dtype, w, n, l, curN, l, othN, nullptr, seed, refill, 1))) return rc;
     swap(curN, othN);
     refill += 2;
-    if ((rc = product(ctx, s, dtype, w, 0, m, l, n, A, lda, curN, l, curM, l, 0, true, PK_GEMM_AX))) return rc;
+    if ((rc = times_a(curN, curM))) return rc;
     const bool last = it == q - 1;
     if ((rc = orthonormalize(ctx, s, dtype, w, m, l, curM, l, othM, nullptr, seed, refill, last ? 2 : 1))) return rc;
     if (!last) swap(curM, othM);
     refill += 2;
   }
   // step 4: B^T = A^T Q
-  if ((rc = product(ctx, s, dtype, w, 1, n, l, m, A, lda, curM, l, curN, l, 0, true, PK_GEMM_ATX))) return rc;
+  if ((rc = times_at(curM, curN))) return rc;
   // step 5
   if ((rc = small_svd(ctx, s, dtype, w, n, l, curN, l, othN, seed, refill))) return rc;
   RSVD_TRY(copy_launch(s, dtype, w.at<void>(L.sigma), S, k), "copy S");
@@ -390,6 +482,20 @@ int rsvd_run(rsvd_ctx *ctx, void *stream, rsvd_dtype dtype, rsvd_job job, int64_
     if ((rc = product(ctx, s, dtype, w, 0, m, k, l, curM, l, w.at<void>(L.Wj), l, U, ldu, 0, false, PK_LIFT))) return rc;
   }
   return finish_info(ctx, s, w, info);
+}
+
+int rsvd_run(rsvd_ctx *ctx, void *stream, rsvd_dtype dtype, rsvd_job job, int64_t m, int64_t n, const void *A,
+             int64_t lda, int k, int p, int q, uint64_t seed, void *S, void *U, int64_t ldu, void *Vt, int64_t ldvt,
+             void *workspace, size_t workspace_bytes, rsvd_info *info) {
+  return run_impl(ctx, stream, dtype, job, m, n, A, lda, k, p, q, seed, S, U, ldu, Vt, ldvt, workspace,
+                  workspace_bytes, info, 0, nullptr);
+}
+
+int rsvd_run_centered(rsvd_ctx *ctx, void *stream, rsvd_dtype dtype, rsvd_job job, int64_t m, int64_t n,
+                      const void *A, int64_t lda, int k, int p, int q, uint64_t seed, void *S, void *U, int64_t ldu,
+                      void *Vt, int64_t ldvt, void *workspace, size_t workspace_bytes, rsvd_info *info, void *mean) {
+  return run_impl(ctx, stream, dtype, job, m, n, A, lda, k, p, q, seed, S, U, ldu, Vt, ldvt, workspace,
+                  workspace_bytes, info, 1, mean);
 }
 
 int rsvd_stage_sketch(rsvd_ctx *ctx, void *stream, rsvd_dtype dtype, uint64_t seed, uint32_t stream_id, int64_t rows,

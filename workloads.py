@@ -65,7 +65,7 @@ CONFIGS = {
 # The three spectra of the paper's performance comparison (Experiments section), 1-based there, 0-based index i here.
 PAPER_SPECTRA = {
     "fast": lambda i: 1.0 / (1.0 + i) ** 2,                                   # sigma_ii = 1 / i^2
-    "sharp": lambda i, beta=20.0: 1e-4 + 1.0 / (1.0 + np.exp(i + 2.0 - beta)),  # 0.0001 + 1/(1 + exp(i + 1 - beta))
+    "sharp": lambda i, beta=20.0: 1e-4 + 1.0 / (1.0 + np.exp(np.minimum(i + 2.0 - beta, 700.0))),  # 1e-4 + 1/(1+exp(i+1-beta))
     "slow": lambda i: 1.0 / (1.0 + i) ** 0.1,                                 # sigma_ii = 1 / i^0.1
 }
 
