@@ -44,7 +44,7 @@ __global__ void copy_kernel(const T *__restrict__ src, T *__restrict__ dst, int6
 // out[j] = alpha * sum_i w[i] * X[i][j] (w == NULL: all ones), accumulated in fp64 in two
 // deterministic stages: row chunks of kColsumRows, then the chunks in order.  Serves the
 // column means and the shift vectors of the centred variant.
-constexpr int kColsumRows = 512;
+constexpr int kColsumRows = 128;
 
 template <typename T>
 __global__ __launch_bounds__(256) void colsum_partial_kernel(const T *__restrict__ X, int64_t ldx, int64_t rows,
@@ -54,12 +54,21 @@ __global__ __launch_bounds__(256) void colsum_partial_kernel(const T *__restrict
   const int64_t r0 = (int64_t)blockIdx.y * kColsumRows;
   const int64_t r1 = (r0 + kColsumRows < rows) ? r0 + kColsumRows : rows;
   if (j >= cols) return;
-  double acc = 0.0;
-  for (int64_t i = r0; i < r1; ++i) {
-    const double x = (double)X[i * ldx + j];
-    acc += (w != nullptr) ? (double)w[i] * x : x;
+  // eight independent partial sums keep eight loads in flight
+  double acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+  int64_t i = r0;
+  for (; i + 8 <= r1; i += 8) {
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const double x = (double)X[(i + u) * ldx + j];
+      acc[u] += (w != nullptr) ? (double)w[i + u] * x : x;
+    }
   }
-  partial[(int64_t)blockIdx.y * cols + j] = acc;
+  for (; i < r1; ++i) {
+    const double x = (double)X[i * ldx + j];
+    acc[0] += (w != nullptr) ? (double)w[i] * x : x;
+  }
+  partial[(int64_t)blockIdx.y * cols + j] = ((acc[0] + acc[1]) + (acc[2] + acc[3])) + ((acc[4] + acc[5]) + (acc[6] + acc[7]));
 }
 
 template <typename T>
@@ -67,9 +76,14 @@ __global__ __launch_bounds__(256) void colsum_final_kernel(const double *__restr
                                                            double alpha, T *__restrict__ out) {
   const int64_t j = (int64_t)blockIdx.x * 256 + threadIdx.x;
   if (j >= cols) return;
-  double acc = 0.0;
-  for (int c = 0; c < chunks; ++c) acc += partial[(int64_t)c * cols + j];
-  out[j] = (T)(alpha * acc);
+  double acc[4] = {0, 0, 0, 0};
+  int c = 0;
+  for (; c + 4 <= chunks; c += 4) {
+#pragma unroll
+    for (int u = 0; u < 4; ++u) acc[u] += partial[(int64_t)(c + u) * cols + j];
+  }
+  for (; c < chunks; ++c) acc[0] += partial[(int64_t)c * cols + j];
+  out[j] = (T)(alpha * ((acc[0] + acc[1]) + (acc[2] + acc[3])));
 }
 
 static size_t colsum_partial_bytes(int64_t rows, int64_t cols) {
