@@ -72,6 +72,8 @@ struct TileStage {
   TIn regs[ITERS][VEC];
 
   // rows_left / cols_left: extent of valid data from the tile origin (may exceed the tile).
+  // (Predicated loads behind a branch measured faster than unconditional loads from a clamped
+  // address followed by a select.)
   __device__ __forceinline__ void load(const TIn *__restrict__ origin, int64_t ld, int64_t rows_left,
                                        int64_t cols_left, int tid) {
 #pragma unroll
@@ -105,7 +107,11 @@ struct TileStage {
   }
 };
 
-template <typename TIn, typename TAcc, typename TOut, bool TA, int BM, int BN, int WGM, int WGN, int VEC>
+// GENERAL = false: the kernel can only store its tile as it is (or as a split-K partial);
+// GENERAL = true: the full epilogue (scaling, accumulation, rank-one term, transposed store,
+// replacement columns).  Two instantiations, because the general epilogue inlines the Philox
+// and Box-Muller code once per accumulator element and the products with A never need it.
+template <typename TIn, typename TAcc, typename TOut, bool TA, int BM, int BN, int WGM, int WGN, int VEC, bool GENERAL>
 __global__ __launch_bounds__(256) void gemm_kernel(const GemmParams P) {
   constexpr int BK = 32;
   static_assert(WGM * WGN == 4, "four wavefronts per workgroup");
@@ -186,22 +192,36 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmParams P) {
   }
 
   // epilogue
+  if (!GENERAL || P.splits > 1) {
+    TOut *Cp = (TOut *)P.C;
+    TAcc *Pp = (TAcc *)P.partial + (int64_t)split * P.M * P.N;
 #pragma unroll
-  for (int i = 0; i < TM; ++i)
+    for (int i = 0; i < TM; ++i)
 #pragma unroll
-    for (int j = 0; j < TN; ++j)
+      for (int j = 0; j < TN; ++j)
 #pragma unroll
-      for (int v = 0; v < 4; ++v) {
-        const int64_t row = m0 + wm0 + i * 16 + Mfma<TAcc>::row(lane, v);
-        const int64_t col = n0 + wn0 + j * 16 + r16;
-        if (row < P.M && col < P.N) {
-          if (P.splits > 1) {
-            ((TAcc *)P.partial)[((int64_t)split * P.M + row) * P.N + col] = acc[i][j][v];
-          } else {
-            store_result<TOut, TAcc, sizeof(TIn) == 4>(P, row, col, acc[i][j][v]);
+        for (int v = 0; v < 4; ++v) {
+          const int64_t row = m0 + wm0 + i * 16 + Mfma<TAcc>::row(lane, v);
+          const int64_t col = n0 + wn0 + j * 16 + r16;
+          if (row < P.M && col < P.N) {
+            if (P.splits > 1) Pp[row * P.N + col] = acc[i][j][v];
+            else Cp[row * P.ldc + col] = (TOut)acc[i][j][v];
           }
         }
-      }
+    return;
+  }
+  if (GENERAL) {
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+          const int64_t row = m0 + wm0 + i * 16 + Mfma<TAcc>::row(lane, v);
+          const int64_t col = n0 + wn0 + j * 16 + r16;
+          if (row < P.M && col < P.N) store_result<TOut, TAcc, sizeof(TIn) == 4>(P, row, col, acc[i][j][v]);
+        }
+  }
 }
 
 template <typename TIn, typename TAcc, typename TOut>
@@ -290,10 +310,14 @@ struct GemmDispatch {
     Q.tiles_m = (int)ceil_div(P.M, BM);
     dim3 grid((unsigned)((int64_t)Q.tiles_n * Q.tiles_m * P.splits));
     constexpr int V = 16 / sizeof(TIn);
-    if (vec) {
-      hipLaunchKernelGGL((gemm_kernel<TIn, TAcc, TOut, TA, BM, BN, WGM, WGN, V>), grid, dim3(256), 0, s, Q);
+    const bool general = P.splits == 1 && (P.alpha != 1.0 || P.beta != 0.0 || P.r1_v != nullptr ||
+                                           P.dead != nullptr || P.trans_c != 0);
+    if (general) {
+      if (vec) hipLaunchKernelGGL((gemm_kernel<TIn, TAcc, TOut, TA, BM, BN, WGM, WGN, V, true>), grid, dim3(256), 0, s, Q);
+      else hipLaunchKernelGGL((gemm_kernel<TIn, TAcc, TOut, TA, BM, BN, WGM, WGN, 1, true>), grid, dim3(256), 0, s, Q);
     } else {
-      hipLaunchKernelGGL((gemm_kernel<TIn, TAcc, TOut, TA, BM, BN, WGM, WGN, 1>), grid, dim3(256), 0, s, Q);
+      if (vec) hipLaunchKernelGGL((gemm_kernel<TIn, TAcc, TOut, TA, BM, BN, WGM, WGN, V, false>), grid, dim3(256), 0, s, Q);
+      else hipLaunchKernelGGL((gemm_kernel<TIn, TAcc, TOut, TA, BM, BN, WGM, WGN, 1, false>), grid, dim3(256), 0, s, Q);
     }
     return hipGetLastError();
   }
