@@ -253,7 +253,7 @@ struct TileChoice {
 };
 
 // Tile shapes instantiated below (see the dispatch switch).
-inline TileChoice choose_tile(int64_t M, int64_t N, size_t acc_size) {
+inline TileChoice choose_tile(int64_t M, int64_t N, int64_t K, size_t acc_size, bool trans_a) {
   TileChoice t;
   if (N <= 128) {
     t.bm = 64;
@@ -265,12 +265,17 @@ inline TileChoice choose_tile(int64_t M, int64_t N, size_t acc_size) {
     const int64_t pad64 = ceil_div(N, 64) * 64 - N, pad128 = ceil_div(N, 128) * 128 - N;
     t.bn = (pad128 < pad64) ? 128 : 64;
   } else {
-    // wide outputs: 128-row tiles, column tile with the least padding
+    // wide outputs: 128-row tiles, column tile with the least padding.  For op(A) = A and
+    // enough tiles to fill the chip twice the 192-wide tile wins on a tie (fewer LDS fragment
+    // reads per matrix instruction); it measured slower for op(A) = A^T, for small grids and for
+    // the short-K triangular applies.
     t.bm = 128;
     const int64_t pad96 = ceil_div(N, 96) * 96 - N, pad128 = ceil_div(N, 128) * 128 - N;
+    const int64_t pad192 = ceil_div(N, 192) * 192 - N;
     t.bn = (pad96 < pad128) ? 96 : 128;
+    if (!trans_a && K >= 2048 && pad192 <= pad96 && pad192 <= pad128 && ceil_div(M, 128) * ceil_div(N, 192) >= 512)
+      t.bn = 192;
   }
-  (void)M;
   return t;
 }
 
@@ -338,19 +343,20 @@ struct GemmDispatch {
     } else {
       if (t.bn == 96)  return run<TA, 128, 96, 2, 2>(s, P, vec);
       if (t.bn == 128) return run<TA, 128, 128, 2, 2>(s, P, vec);
+      if (t.bn == 192 && sizeof(TAcc) == 4) return run<TA, 128, 192, 2, 2>(s, P, vec);
     }
     return hipErrorInvalidValue;
   }
 
-  static size_t partial_bytes(const rsvd_ctx *ctx, int64_t M, int64_t N, int64_t K) {
-    const TileChoice t = choose_tile(M, N, sizeof(TAcc));
+  static size_t partial_bytes(const rsvd_ctx *ctx, int64_t M, int64_t N, int64_t K, bool trans_a) {
+    const TileChoice t = choose_tile(M, N, K, sizeof(TAcc), trans_a);
     const SplitChoice c = choose_split(ctx, t, M, N, K, 0);
     return c.splits > 1 ? (size_t)c.splits * (size_t)M * (size_t)N * sizeof(TAcc) : 0;
   }
 
   static hipError_t launch(rsvd_ctx *ctx, hipStream_t s, const GemmDesc &d) {
     if (d.M <= 0 || d.N <= 0) return hipSuccess;
-    const TileChoice t = choose_tile(d.M, d.N, sizeof(TAcc));
+    const TileChoice t = choose_tile(d.M, d.N, d.K, sizeof(TAcc), d.trans_a != 0);
     SplitChoice c = choose_split(ctx, t, d.M, d.N, d.K, d.force_splits);
     if (c.splits > 1) {
       const size_t need = (size_t)c.splits * (size_t)d.M * (size_t)d.N * sizeof(TAcc);

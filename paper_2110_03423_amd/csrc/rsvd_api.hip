@@ -11,19 +11,18 @@
 
 namespace rsvd {
 
-size_t gemm_partial_bytes_f32(const rsvd_ctx *, int64_t, int64_t, int64_t);
-size_t gemm_partial_bytes_f64(const rsvd_ctx *, int64_t, int64_t, int64_t);
-size_t gemm_partial_bytes_f32acc64(const rsvd_ctx *, int64_t, int64_t, int64_t);
+size_t gemm_partial_bytes_f32(const rsvd_ctx *, int64_t, int64_t, int64_t, int);
+size_t gemm_partial_bytes_f64(const rsvd_ctx *, int64_t, int64_t, int64_t, int);
+size_t gemm_partial_bytes_f32acc64(const rsvd_ctx *, int64_t, int64_t, int64_t, int);
 hipError_t gemm_launch_f32(rsvd_ctx *, hipStream_t, const GemmDesc &);
 hipError_t gemm_launch_f64(rsvd_ctx *, hipStream_t, const GemmDesc &);
 hipError_t gemm_launch_f32acc64(rsvd_ctx *, hipStream_t, const GemmDesc &);
 
 size_t gemm_partial_bytes(const rsvd_ctx *ctx, GemmKind kind, int trans_a, int64_t M, int64_t N, int64_t K) {
-  (void)trans_a;
   switch (kind) {
-    case GEMM_F32: return gemm_partial_bytes_f32(ctx, M, N, K);
-    case GEMM_F64: return gemm_partial_bytes_f64(ctx, M, N, K);
-    default:       return gemm_partial_bytes_f32acc64(ctx, M, N, K);
+    case GEMM_F32: return gemm_partial_bytes_f32(ctx, M, N, K, trans_a);
+    case GEMM_F64: return gemm_partial_bytes_f64(ctx, M, N, K, trans_a);
+    default:       return gemm_partial_bytes_f32acc64(ctx, M, N, K, trans_a);
   }
 }
 
