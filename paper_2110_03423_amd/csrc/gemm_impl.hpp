@@ -260,10 +260,14 @@ inline TileChoice choose_tile(int64_t M, int64_t N, int64_t K, size_t acc_size, 
     t.bn = (int)(ceil_div(N, 16) * 16);
   } else if (acc_size == 8) {
     // fp64 accumulators: the 64-row tile with one wavefront per 16 rows keeps the register
-    // count low enough for two workgroups per CU, which measured faster than 128-row tiles
+    // count low enough for two workgroups per CU
     t.bm = 64;
-    const int64_t pad64 = ceil_div(N, 64) * 64 - N, pad128 = ceil_div(N, 128) * 128 - N;
-    t.bn = (pad128 < pad64) ? 128 : 64;
+    const int64_t pad64 = ceil_div(N, 64) * 64 - N, pad96 = ceil_div(N, 96) * 96 - N;
+    const int64_t pad128 = ceil_div(N, 128) * 128 - N;
+    t.bn = 64;
+    if (pad96 <= pad64) t.bn = 96;
+    if (pad128 < pad64 && pad128 < pad96) t.bn = 128;
+    if (trans_a && t.bn == 96) t.bm = 128;      // measured: 128 x 96 is faster for A^T X, 64 x 96 for A X
   } else {
     // wide outputs: 128-row tiles, column tile with the least padding.  For op(A) = A and
     // enough tiles to fill the chip twice the 192-wide tile wins on a tie (fewer LDS fragment
