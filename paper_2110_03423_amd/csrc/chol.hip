@@ -9,6 +9,7 @@
 // Q by a fresh Gaussian direction), so a rank-deficient Y still gives a full
 // orthonormal basis that contains range(Y).
 #include "common.hpp"
+#include "mfma.hpp"
 
 namespace rsvd {
 
@@ -23,178 +24,243 @@ __device__ __forceinline__ double fast_rsqrt(double d) {
   return y;
 }
 
-// One workgroup of TG x TG threads factors an nb x nb block (nb <= TG * NR) that
-// it holds in registers: thread (ty, tx) owns the elements (ty + TG a, tx + TG b)
-// of the symmetric matrix S and of Z = R^-T.  The block is the sum of n_parts
-// matrices spaced part_stride elements apart (split-K partial Gram matrices are
-// added here, in a fixed order).
-// Right-looking elimination, one step per column j: the owners of row j publish
-// it through double-buffered LDS lines (one barrier per step); every thread then
-// applies the update to its elements of S (blocks on or above the block diagonal,
-// whole 16 x 16 blocks so the inner loop carries no masks) and of Z.  Row j of R and column j of R^-1 are final at
-// step j and go straight to global memory.
+// 64-bit lane read (the lane index is a compile-time constant where this is used).
+__device__ __forceinline__ double readlane_f64(double v, int lane) {
+  const int lo = __builtin_amdgcn_readlane(__double2loint(v), lane);
+  const int hi = __builtin_amdgcn_readlane(__double2hiint(v), lane);
+  return __hiloint2double(hi, lo);
+}
+
+// One workgroup of NB wavefronts factors an nb x nb block (nb <= 16 NB) and inverts the
+// factor.  The block is the sum of n_parts matrices spaced part_stride elements apart
+// (split-K partial Gram matrices are added here, in a fixed order).
+//
+// Elimination on [S | I] by 16 x 16 blocks.  Wavefront r owns block row r for the whole
+// run and keeps it in registers in the accumulator layout of the fp64 matrix-core
+// instruction: slot J >= r is the S block (r, J), slot J < r the block (r, J) of
+// Z = R^-T.  Step kb:
+//   * wavefront kb factors its diagonal block (see diag_factor), multiplies the rest of
+//     its row by T^T, T = R_kk^-1, on the matrix cores (the accumulator layout is also
+//     the B-operand layout, so the row never leaves the registers) and publishes the
+//     finished row (R to the right of the diagonal, Z to the left) and T in LDS;
+//   * one barrier;
+//   * every wavefront r > kb takes  block(r, J) -= R[kb][r]^T block(kb, J)  for its slots.
+// The rows collected in LDS are written out at the end (R^-1 as the transpose of Z).
 //   g0    : original squared column norms for the pivot test, or NULL to use the diagonal
 //   Rinv  : nb x nb block of R^-1 (ld ldri, type TOut, zeros below the diagonal)
 //   R     : same for R in fp64 (ld ldr), or NULL
 //   dead  : nb flags (1 = pivot <= tau * original squared norm)
-template <typename TOut, int TG, int NR>
-__global__ __launch_bounds__(TG * TG) void chol_block_kernel(const double *__restrict__ G, int64_t ldg,
-                                                              int n_parts, int64_t part_stride, int nb,
-                                                              const double *__restrict__ g0, double tau,
-                                                              TOut *__restrict__ Rinv, int64_t ldri,
-                                                              double *__restrict__ R, int64_t ldr,
-                                                              int *__restrict__ dead, DevInfo *info) {
-  constexpr int LMAX = TG * NR;
-  __shared__ double bufS[2][LMAX], bufS1[2][LMAX];    // rows j and j+1 of S, double buffered
-  __shared__ double bufZ[2][LMAX], bufZ1[2][LMAX];    // the same rows of Z
-  __shared__ double d0[LMAX];
-  __shared__ double zdiag[LMAX];
-  __shared__ int n_dead, n_dead2, bad;
-  extern __shared__ double outm[];       // nb x (LMAX + 1): finished rows of R and Z
-  constexpr int ost = LMAX + 1;
-  const int tid = threadIdx.x;
-  const int tx = tid % TG, ty = tid / TG;
-  double S[NR][NR], Z[NR][NR];
+template <int NB> struct CholLds {
+  static constexpr int LP = 16 * NB, LD = LP + 1, TLD = 17;
+  static constexpr size_t bytes = ((size_t)LP * LD + (size_t)NB * 16 * TLD + LP) * sizeof(double);
+};
 
-  if (tid == 0) { n_dead = 0; n_dead2 = 0; bad = 0; }
+// Factor and invert one 16 x 16 symmetric block held in the accumulator layout
+// (register v of lane L: row 4 v + L / 16, column L % 16).  One wavefront runs this
+// alone and a lone wavefront issues about one instruction every five cycles, so the cost
+// is the number of instructions per column; everything is arranged to keep that small.
+// Square-root-free elimination: column j is eliminated by ONE matrix-core instruction per
+// block, a rank-one update whose operands are row j itself (it already sits in the lanes
+// that feed k-slot j % 4), once for the block and once for the identity next to it.  The
+// update is not masked: rows that are already finished are copied out first (sd, sz) and
+// what the update leaves in their place is never read.  Rows are scaled by 1 / sqrt(d_j)
+// at the end.
+//   dblk : in  S_kk, out R_kk (valid on and above the diagonal)
+//   z    : out Z_kk = R_kk^-T (lower triangular)
+//   thr  : lane c holds tau * (reference squared norm of column c); pos: bit c set when that norm is > 0
+//   piv  : 16 doubles of LDS scratch
+//   returns the 16-bit mask of flagged (dependent) columns
+__device__ __forceinline__ unsigned diag_factor(f64x4 &dblk, f64x4 &z, double thr, unsigned pos, int lane,
+                                                double *piv) {
+  const int lr = lane >> 4, lc = lane & 15;
+  double mrow[4];
 #pragma unroll
-  for (int a = 0; a < NR; ++a)
+  for (int q = 0; q < 4; ++q) mrow[q] = (lr == q) ? 1.0 : 0.0;
 #pragma unroll
-    for (int b = 0; b < NR; ++b) { S[a][b] = 0.0; Z[a][b] = 0.0; }
-  // all loads of a batch of parts are issued before they are added, so the memory
-  // latency is paid once per batch and not once per element
-  constexpr int UB = NR > 4 ? 1 : (NR > 2 ? 2 : 4);
-  for (int s0 = 0; s0 < n_parts; s0 += UB) {
-    double v[UB][NR][NR];
+  for (int v = 0; v < 4; ++v) z[v] = (4 * v + lr == lc) ? 1.0 : 0.0;
+  f64x4 sd = {0.0, 0.0, 0.0, 0.0}, sz = {0.0, 0.0, 0.0, 0.0};
+  unsigned dmask = 0;
 #pragma unroll
-    for (int u = 0; u < UB; ++u)
-#pragma unroll
-      for (int a = 0; a < NR; ++a)
-#pragma unroll
-        for (int b = 0; b < NR; ++b) {
-          const int i = ty + TG * a, c = tx + TG * b;
-          v[u][a][b] = (s0 + u < n_parts && i < nb && c < nb)
-                           ? G[(int64_t)(s0 + u) * part_stride + (int64_t)i * ldg + c] : 0.0;
-        }
-#pragma unroll
-    for (int u = 0; u < UB; ++u)
-#pragma unroll
-      for (int a = 0; a < NR; ++a)
-#pragma unroll
-        for (int b = 0; b < NR; ++b) S[a][b] += v[u][a][b];
-  }
-  __syncthreads();                       // n_dead / bad initialised
-#pragma unroll
-  for (int a = 0; a < NR; ++a)
-#pragma unroll
-    for (int b = 0; b < NR; ++b) {
-      const int i = ty + TG * a, c = tx + TG * b;
-      if (i == c && i < nb) {
-        const double d = (g0 != nullptr) ? g0[i] : S[a][b];
-        d0[i] = d;
-        if (!(fabs(d) <= 1.79e308)) bad = 1;      // NaN or Inf
-      }
-      if (i == c && i == nb) { S[a][b] = 1.0; d0[i] = 1.0; }      // padding column of an odd order
+  for (int j = 0; j < 16; ++j) {
+    const int q = j & 3, v4 = j >> 2;
+    const double rowv = dblk[v4];
+    const double d = readlane_f64(rowv, 16 * q + j);            // pivot S[j][j]
+    const unsigned gt = (unsigned)__ballot(d > thr);            // bit c: d exceeds the threshold of column c
+    double y = __builtin_amdgcn_rcp(d);
+    y = fma(fma(-d, y, 1.0), y, y);        // the hardware estimate is good to ~1e-8: one step squares that
+    if (!(((gt & pos) >> j) & 1u)) {                            // dependent column (rare): no elimination
+      dmask |= 1u << j;
+      y = 0.0;
     }
+    const double b_d = rowv * mrow[q];
+    const double b_z = z[v4] * mrow[q];
+    const double a_op = b_d * -y;
+    sd[v4] += b_d;
+    sz[v4] += b_z;
+    dblk = Mfma<double>::run(a_op, b_d, dblk);
+    z = Mfma<double>::run(a_op, b_z, z);
+  }
+  // pivot of row i = diagonal element of the saved row: pass it along the lane row through LDS
+#pragma unroll
+  for (int v = 0; v < 4; ++v)
+    if (lc == 4 * v + lr) piv[lc] = sd[v];
+  __builtin_amdgcn_wave_barrier();
+#pragma unroll
+  for (int v = 0; v < 4; ++v) {
+    const double x = piv[4 * v + lr];
+    double rv = __builtin_amdgcn_rsq(x);
+    rv = rv * (1.5 - 0.5 * x * rv * rv);
+    rv = rv * (1.5 - 0.5 * x * rv * rv);
+    if ((dmask >> (4 * v + lr)) & 1u) rv = 0.0;
+    dblk[v] = sd[v] * rv;
+    z[v] = sz[v] * rv;
+  }
+  return dmask;
+}
 
-  // Two columns per step (a 2 x 2 pivot block): half as many barriers and LDS round
-  // trips as column-by-column elimination, same arithmetic.  The loop is unrolled over
-  // the 16-wide row blocks (A0 is a compile-time constant inside), so the registers that
-  // hold rows j, j+1 are addressed statically and blocks that can no longer change are
-  // dropped at compile time: branches inside a step cost more than the arithmetic they
-  // would save.  An odd order is padded with a unit diagonal entry.
+template <typename TOut, int NB>
+__global__ __launch_bounds__(NB * 64) void chol_mfma_kernel(const double *__restrict__ G, int64_t ldg,
+                                                            int n_parts, int64_t part_stride, int nb,
+                                                            const double *__restrict__ g0, double tau,
+                                                            TOut *__restrict__ Rinv, int64_t ldri,
+                                                            double *__restrict__ R, int64_t ldr,
+                                                            int *__restrict__ dead, DevInfo *info) {
+  typedef CholLds<NB> L;
+  constexpr int LP = L::LP, LD = L::LD, TLD = L::TLD, NT = NB * 64;
+  extern __shared__ double smem[];
+  double *Sm = smem;                       // LP x LD: finished rows of [R | Z]
+  double *Td = Sm + LP * LD;               // NB x 16 x TLD: R_kk^-1
+  double *d0 = Td + NB * 16 * TLD;         // LP: reference squared norms for the pivot test
+  __shared__ double piv[16];
+  __shared__ int n_dead, bad;
+  const int tid = threadIdx.x, lane = tid & 63, wr = tid >> 6;      // wr: block row of this wavefront
+  const int lr = lane >> 4, lc = lane & 15;
+  // register slot t of wavefront wr holds column block (wr + t) mod NB: slot 0 is the
+  // diagonal block, slots 1 .. NB-1-wr the S blocks to its right, the rest the Z blocks
+  auto col_block = [&](int t) { const int J = wr + t; return J >= NB ? J - NB : J; };
+
+  if (tid == 0) { n_dead = 0; bad = 0; }
+  // ---- load block row wr: sum of the parts for the S slots, zero for the Z slots, identity padding
+  f64x4 acc[NB];
 #pragma unroll
-  for (int A0 = 0; A0 < NR; ++A0) {
-    for (int jj = 0; jj < TG; jj += 2) {
-      const int j = A0 * TG + jj;
-      if (j >= nb) break;
-      const int par = (j >> 1) & 1;
-      double *bs0 = bufS[par], *bz0 = bufZ[par], *bs1 = bufS1[par], *bz1 = bufZ1[par];
-      if (ty == jj) {
+  for (int t = 0; t < NB; ++t) acc[t] = f64x4{0.0, 0.0, 0.0, 0.0};
+  {
+    const double *Gr = G + (int64_t)(16 * wr + lr) * ldg + 16 * wr + lc;
+    for (int p = 0; p < n_parts; ++p) {
+      f64x4 cur[NB];
 #pragma unroll
-        for (int b = 0; b < NR; ++b) { bs0[tx + TG * b] = S[A0][b]; bz0[tx + TG * b] = Z[A0][b]; }
-      }
-      if (ty == jj + 1) {
+      for (int t = 0; t < NB; ++t)
 #pragma unroll
-        for (int b = 0; b < NR; ++b) { bs1[tx + TG * b] = S[A0][b]; bz1[tx + TG * b] = Z[A0][b]; }
-      }
-      __syncthreads();
-      const double d00 = bs0[j], d01 = bs0[j + 1], d11 = bs1[j + 1];
-      const double dj0 = d0[j], dj1 = d0[j + 1];
-      const bool dead0 = !(d00 > tau * dj0) || !(dj0 > 0.0);
-      const double rinv0 = dead0 ? 0.0 : fast_rsqrt(d00);
-      const double r01 = d01 * rinv0;
-      const double d11p = d11 - r01 * r01;
-      const bool dead1 = !(d11p > tau * dj1) || !(dj1 > 0.0);
-      const double rinv1 = dead1 ? 0.0 : fast_rsqrt(d11p);
-      double s0[NR], s1[NR], z0[NR], z1[NR], l0[NR], l1[NR];
-#pragma unroll
-      for (int b = 0; b < NR; ++b) {
-        const int c = tx + TG * b;
-        const double t0 = (b >= A0) ? bs0[c] * rinv0 : 0.0;                    // R[j][c] for c > j
-        s0[b] = (c > j) ? t0 : 0.0;
-        s1[b] = (b >= A0 && c > j + 1) ? (bs1[c] - r01 * t0) * rinv1 : 0.0;    // R[j+1][c]
-        const double u0 = (b <= A0) ? ((c < j) ? bz0[c] * rinv0 : ((c == j) ? rinv0 : 0.0)) : 0.0;   // Z[j][c]
-        z0[b] = u0;
-        z1[b] = (b <= A0) ? ((c <= j) ? (bz1[c] - r01 * u0) * rinv1 : ((c == j + 1) ? rinv1 : 0.0)) : 0.0;
-      }
-#pragma unroll
-      for (int a = 0; a < NR; ++a) {
-        const int i = ty + TG * a;
-        const bool below = (a >= A0) && (i > j + 1);
-        const double t0 = below ? bs0[i] * rinv0 : 0.0;                        // R[j][i]
-        l0[a] = t0;
-        l1[a] = below ? (bs1[i] - r01 * t0) * rinv1 : 0.0;                     // R[j+1][i]
-      }
-#pragma unroll
-      for (int a = A0; a < NR; ++a)
-#pragma unroll
-        for (int b = 0; b < NR; ++b) {
-          if (b >= a) S[a][b] = fma(-l1[a], s1[b], fma(-l0[a], s0[b], S[a][b]));   // upper block triangle only
-          if (b <= A0) Z[a][b] = fma(-l1[a], z1[b], fma(-l0[a], z0[b], Z[a][b]));
+        for (int v = 0; v < 4; ++v) {
+          const int row = 16 * wr + 4 * v + lr, col = 16 * (wr + t) + lc;
+          cur[t][v] = (row < nb && col < nb) ? Gr[(int64_t)p * part_stride + (int64_t)(4 * v) * ldg + 16 * t] : 0.0;
         }
-      // rows j, j+1 of R and of Z (= columns of R^-1) are final: park them in LDS
-      if (ty == jj) {
-        const double r00 = dead0 ? 0.0 : d00 * rinv0;
 #pragma unroll
-        for (int b = 0; b < NR; ++b) {
-          const int c = tx + TG * b;
-          outm[j * ost + c] = (c > j) ? s0[b] : ((c == j) ? r00 : z0[b]);
-        }
-        if (tx == jj) {
-          zdiag[j] = rinv0;
-          dead[j] = dead0 ? 1 : 0;
-          if (dead0) n_dead += 1;                                  // single writer
-        }
-      }
-      if (ty == jj + 1) {
-        const double r11 = dead1 ? 0.0 : d11p * rinv1;
+      for (int t = 0; t < NB; ++t) acc[t] += cur[t];
+    }
+    // reference norms of this row's 16 columns; unit diagonal in the padding
 #pragma unroll
-        for (int b = 0; b < NR; ++b) {
-          const int c = tx + TG * b;
-          outm[(j + 1) * ost + c] = (c > j + 1) ? s1[b] : ((c == j + 1) ? r11 : z1[b]);
-        }
-        if (tx == jj + 1 && j + 1 < nb) {
-          zdiag[j + 1] = rinv1;
-          dead[j + 1] = dead1 ? 1 : 0;
-          if (dead1) n_dead2 += 1;                                 // single writer
-        }
-      }
+    for (int v = 0; v < 4; ++v) {
+      const int row = 16 * wr + 4 * v + lr;
+      if (4 * v + lr != lc) continue;          // the lane that holds the diagonal element of this row
+      double dv = 1.0;
+      if (row < nb) dv = (g0 != nullptr) ? g0[row] : acc[0][v];
+      else acc[0][v] = 1.0;
+      d0[row] = dv;
+      if (!(fabs(dv) <= 1.79e308)) bad = 1;      // NaN or Inf
     }
   }
   __syncthreads();
-  // outm: upper triangle = R, strict lower triangle = Z (row i holds Z[i][:i]), zdiag = diagonal of Z
-  for (int idx = tid; idx < nb * nb; idx += TG * TG) {
-    const int r = idx / nb, c = idx - r * nb;
-    double rr = 0.0, ri = 0.0;
-    if (r < c)       { rr = outm[r * ost + c]; ri = outm[c * ost + r]; }
-    else if (r == c) { rr = outm[r * ost + r]; ri = zdiag[r]; }
-    if (R != nullptr) R[(int64_t)r * ldr + c] = rr;
-    Rinv[(int64_t)r * ldri + c] = (TOut)ri;
+
+#pragma unroll 1
+  for (int kb = 0; kb < NB; ++kb) {
+    const int k0 = kb * 16;
+    if (wr == kb) {
+      // ---- pivot row: factor the diagonal block, scale the row, publish it
+      const double d0c = d0[k0 + lc];
+      const unsigned pos = (unsigned)__ballot(d0c > 0.0) & 0xffffu;
+      f64x4 z;
+      const unsigned dmask = diag_factor(acc[0], z, tau * d0c, pos, lane, piv);
+#pragma unroll
+      for (int v = 0; v < 4; ++v) {
+        const int row = 4 * v + lr;
+        Sm[(k0 + row) * LD + k0 + lc] = (lc >= row) ? acc[0][v] : 0.0;        // R_kk
+        Td[(k0 + lc) * TLD + row] = z[v];                                      // T[c][row] = Z[row][c]
+      }
+      if (lane < 16 && k0 + lane < nb) dead[k0 + lane] = (int)((dmask >> lane) & 1u);
+      if (lane == 0) {
+        const int valid = min(16, nb - k0);
+        n_dead += __popc(dmask & ((1u << valid) - 1u));     // one writer at a time (steps are separated by barriers)
+      }
+      __builtin_amdgcn_wave_barrier();
+      double ta[4];
+#pragma unroll
+      for (int s = 0; s < 4; ++s) ta[s] = Td[(k0 + 4 * s + lr) * TLD + lc];
+      // (slot loop innermost: consecutive matrix-core instructions are independent)
+      f64x4 o[NB];
+#pragma unroll
+      for (int t = 1; t < NB; ++t) o[t] = f64x4{0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+      for (int s = 0; s < 4; ++s)
+#pragma unroll
+        for (int t = 1; t < NB; ++t) o[t] = Mfma<double>::run(ta[s], acc[t][s], o[t]);
+#pragma unroll
+      for (int t = 1; t < NB; ++t) {
+        double *dst = Sm + (k0 + lr) * LD + 16 * col_block(t) + lc;
+#pragma unroll
+        for (int v = 0; v < 4; ++v) dst[4 * v * LD] = o[t][v];
+      }
+    }
+    __syncthreads();
+    if (wr > kb) {
+      // ---- trailing rows: block(wr, J) -= R[kb][wr]^T block(kb, J)
+      double na[4];
+#pragma unroll
+      for (int s = 0; s < 4; ++s) na[s] = -Sm[(k0 + 4 * s + lr) * LD + 16 * wr + lc];
+      double b[NB][4];
+#pragma unroll
+      for (int t = 0; t < NB; ++t) {
+        const int J = col_block(t);
+        const bool on = !(J > kb && J < wr);       // an S slot (J >= wr) or a touched Z slot (J <= kb)
+        const double *src = (J == kb) ? Td + (k0 + lc) * TLD + lr                   // Z_kk = T_kk^T
+                                      : Sm + (k0 + lr) * LD + 16 * J + lc;
+        const int step = (J == kb) ? 4 : 4 * LD;
+#pragma unroll
+        for (int s = 0; s < 4; ++s) b[t][s] = on ? src[s * step] : 0.0;      // untouched slots take a zero update
+      }
+      // (slot loop innermost: consecutive matrix-core instructions are independent)
+#pragma unroll
+      for (int s = 0; s < 4; ++s)
+#pragma unroll
+        for (int t = 0; t < NB; ++t) acc[t] = Mfma<double>::run(na[s], b[t][s], acc[t]);
+    } else {
+      // ---- the wavefronts that are done write out block row kb of R and block column kb of R^-1
+      // (R^-1 = Z^T: column k0 + c of R^-1 is row k0 + c of Z), off the critical path
+      const int parts = kb + 1;
+      const int ldr_i = (int)ldr, ldri_i = (int)ldri;      // orders here are at most a few hundred
+      if (R != nullptr) {
+        const int rows = min(16, nb - k0);
+        for (int c = lane; c < nb; c += 64) {
+#pragma unroll 4
+          for (int i = wr; i < rows; i += parts) {
+            const int r = k0 + i;
+            R[r * ldr_i + c] = (c >= r) ? Sm[r * LD + c] : 0.0;
+          }
+        }
+      }
+      const int c = k0 + lc;
+      if (c < nb) {
+#pragma unroll 4
+        for (int r = lr + 4 * wr; r < nb; r += 4 * parts) {
+          double v = 0.0;
+          if (r <= c) v = (r >= k0) ? Td[r * TLD + lc] : Sm[c * LD + r];
+          Rinv[r * ldri_i + c] = (TOut)v;
+        }
+      }
+    }
   }
-  __syncthreads();
   if (tid == 0 && info != nullptr) {
-    if (n_dead + n_dead2 > 0) atomicAdd(&info->refilled, n_dead + n_dead2);
+    if (n_dead > 0) atomicAdd(&info->refilled, n_dead);
     if (bad) atomicMax(&info->status, (int)RSVD_ERR_NONFINITE);
   }
 }
@@ -233,7 +299,7 @@ __global__ void zero_ints_kernel(int *p, int n) {
 
 int chol_max_block(const rsvd_ctx *ctx) {
   (void)ctx;
-  return 128;      // 16 x 16 threads, up to 8 x 8 elements each
+  return 128;      // 8 x 8 blocks of 16 x 16 in 147 KB of LDS
 }
 
 size_t chol_scratch_elems(const rsvd_ctx *ctx, int64_t l) {
@@ -246,30 +312,29 @@ template <typename TOut>
 static hipError_t launch_block(hipStream_t s, const double *G, int64_t ldg, int n_parts, int64_t part_stride, int nb,
                                const double *g0, double tau, TOut *Rinv, int64_t ldri, double *R, int64_t ldr,
                                int *dead, DevInfo *info) {
-  // 256 threads (one wavefront per SIMD) keep the per-step barrier cheap; each thread
-  // holds NR x NR elements of S and of Z, NR = ceil(nb / 16); above 96 the register
-  // budget asks for 1024 threads with 4 x 4 elements.
-  const size_t lds = (size_t)(nb + 1) * ((size_t)((nb + 15) / 16 > 6 ? 128 : ((nb + 15) / 16) * 16) + 1) * sizeof(double);
-#define RSVD_CHOL_CASE(TGV, NRV)                                                                                    \
+  // one workgroup, one wavefront per 16-row block
+#define RSVD_CHOL_CASE(NBV)                                                                                         \
   do {                                                                                                              \
     static bool attr_set = false;                                                                                   \
     if (!attr_set) {                                                                                                \
-      (void)hipFuncSetAttribute(reinterpret_cast<const void *>(&chol_block_kernel<TOut, TGV, NRV>),                 \
-                                hipFuncAttributeMaxDynamicSharedMemorySize, 150 * 1024);                            \
+      (void)hipFuncSetAttribute(reinterpret_cast<const void *>(&chol_mfma_kernel<TOut, NBV>),                       \
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)CholLds<NBV>::bytes);              \
       (void)hipGetLastError();                                                                                      \
       attr_set = true;                                                                                              \
     }                                                                                                               \
-    hipLaunchKernelGGL((chol_block_kernel<TOut, TGV, NRV>), dim3(1), dim3(TGV * TGV), lds, s, G, ldg, n_parts,      \
-                       part_stride, nb, g0, tau, Rinv, ldri, R, ldr, dead, info);                                   \
+    hipLaunchKernelGGL((chol_mfma_kernel<TOut, NBV>), dim3(1), dim3(NBV * 64), CholLds<NBV>::bytes, s, G, ldg,      \
+                       n_parts, part_stride, nb, g0, tau, Rinv, ldri, R, ldr, dead, info);                          \
   } while (0)
   switch ((nb + 15) / 16) {
-    case 1: RSVD_CHOL_CASE(16, 1); break;
-    case 2: RSVD_CHOL_CASE(16, 2); break;
-    case 3: RSVD_CHOL_CASE(16, 3); break;
-    case 4: RSVD_CHOL_CASE(16, 4); break;
-    case 5: RSVD_CHOL_CASE(16, 5); break;
-    case 6: RSVD_CHOL_CASE(16, 6); break;
-    default: RSVD_CHOL_CASE(32, 4); break;
+    case 1: RSVD_CHOL_CASE(1); break;
+    case 2: RSVD_CHOL_CASE(2); break;
+    case 3: RSVD_CHOL_CASE(3); break;
+    case 4: RSVD_CHOL_CASE(4); break;
+    case 5: RSVD_CHOL_CASE(5); break;
+    case 6: RSVD_CHOL_CASE(6); break;
+    case 7: RSVD_CHOL_CASE(7); break;
+    case 8: RSVD_CHOL_CASE(8); break;
+    default: return hipErrorInvalidValue;
   }
 #undef RSVD_CHOL_CASE
   return hipGetLastError();
