@@ -392,6 +392,7 @@ hipError_t chol_inverse_launch(rsvd_ctx *ctx, hipStream_t s, rsvd_dtype out_dtyp
       t.B = Rf + j0 * l + j0 + b; t.ldb = l;
       t.C = G + (j0 + b) * ldg + j0 + b; t.ldc = ldg;
       t.alpha = -1.0; t.beta = 1.0; t.force_splits = 1;
+      t.upper_only = 1;                 // nothing below reads the lower triangle of G
       if ((e = gemm_launch_f64(ctx, s, t)) != hipSuccess) return e;
     }
     if (j0 > 0) {

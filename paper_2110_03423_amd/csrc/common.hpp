@@ -81,6 +81,10 @@ struct GemmDesc {
   // r1_v != NULL: C[i][j] += r1_alpha * u[i] * v[j] with u = r1_u (length M) or all ones when
   // r1_u == NULL, v = r1_v (length N), both in the output type; applied once, after any split-K sum.
   const void *r1_u = nullptr; const void *r1_v = nullptr; double r1_alpha = 0.0;
+  // upper_only != 0: the result is symmetric (M == N) and only its tiles on or above the diagonal
+  // are computed; what lies in the tiles strictly below (and their split-K partials) is undefined.
+  // Every 16 x 16 block on the diagonal is complete.
+  int upper_only = 0;
   const int *dead = nullptr;
   uint64_t seed = 0; uint32_t refill_stream = 0; double refill_scale = 1.0; int64_t refill_ld = 0;
   void *partial = nullptr; size_t partial_bytes = 0;   // split-K scratch

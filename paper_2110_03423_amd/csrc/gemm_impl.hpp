@@ -31,6 +31,7 @@ struct GemmParams {
   int64_t k_per_split;
   int splits;
   int tiles_n, tiles_m;     // grid shape in tiles; the launch is one-dimensional
+  int upper_bm, upper_bn;   // > 0: symmetric result, tiles (of this size) strictly below the diagonal are skipped
   int trans_c;
   double alpha, beta;
   const void *r1_u; const void *r1_v; double r1_alpha;
@@ -145,6 +146,7 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmParams P) {
   const int split = tile / (P.tiles_n * P.tiles_m);
   const int64_t m0 = (int64_t)tile_m * BM;
   const int64_t n0 = (int64_t)tile_n * BN;
+  if (P.upper_bm > 0 && n0 + BN <= m0) return;       // symmetric result: this tile mirrors one that is computed
   const int64_t k_begin = (int64_t)split * P.k_per_split;
   const int64_t k_end = (k_begin + P.k_per_split < P.K) ? (k_begin + P.k_per_split) : P.K;
 
@@ -229,6 +231,9 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const GemmParams P) 
   const int64_t total = P.M * P.N;
   for (int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; e < total;
        e += (int64_t)gridDim.x * blockDim.x) {
+    const int64_t row = e / P.N;
+    const int64_t col = e - row * P.N;
+    if (P.upper_bm > 0 && (col / P.upper_bn + 1) * P.upper_bn <= (row / P.upper_bm) * P.upper_bm) continue;
     const TAcc *p = (const TAcc *)P.partial + e;
     TAcc sum = (TAcc)0;
     // eight loads in flight per step; the additions keep their fixed order
@@ -241,8 +246,7 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const GemmParams P) 
       for (int u = 0; u < 8; ++u) sum += v[u];
     }
     for (; s < P.splits; ++s) sum += p[(int64_t)s * total];
-    const int64_t row = e / P.N;
-    store_result<TOut, TAcc, sizeof(TIn) == 4>(P, row, e - row * P.N, sum);
+    store_result<TOut, TAcc, sizeof(TIn) == 4>(P, row, col, sum);
   }
 }
 
@@ -289,8 +293,14 @@ struct SplitChoice {
 };
 
 inline SplitChoice choose_split(const rsvd_ctx *ctx, const TileChoice &t, int64_t M, int64_t N, int64_t K,
-                                int force) {
-  const int64_t tiles = ceil_div(M, t.bm) * ceil_div(N, t.bn);
+                                int force, bool upper = false) {
+  int64_t tiles = ceil_div(M, t.bm) * ceil_div(N, t.bn);
+  if (upper) {                     // only tiles that reach the diagonal or lie above it do work
+    tiles = 0;
+    for (int64_t tm = 0; tm < ceil_div(M, t.bm); ++tm)
+      for (int64_t tn = 0; tn < ceil_div(N, t.bn); ++tn)
+        if ((tn + 1) * t.bn > tm * t.bm) ++tiles;
+  }
   const int64_t ktiles = ceil_div(K, 32);
   int64_t s = 1;
   if (force > 0) {
@@ -354,14 +364,18 @@ struct GemmDispatch {
 
   static size_t partial_bytes(const rsvd_ctx *ctx, int64_t M, int64_t N, int64_t K, bool trans_a) {
     const TileChoice t = choose_tile(M, N, K, sizeof(TAcc), trans_a);
-    const SplitChoice c = choose_split(ctx, t, M, N, K, 0);
+    SplitChoice c = choose_split(ctx, t, M, N, K, 0);
+    if (M == N) {                  // a symmetric (upper-only) product of this shape may split further
+      const SplitChoice cu = choose_split(ctx, t, M, N, K, 0, true);
+      if (cu.splits > c.splits) c = cu;
+    }
     return c.splits > 1 ? (size_t)c.splits * (size_t)M * (size_t)N * sizeof(TAcc) : 0;
   }
 
   static hipError_t launch(rsvd_ctx *ctx, hipStream_t s, const GemmDesc &d) {
     if (d.M <= 0 || d.N <= 0) return hipSuccess;
     const TileChoice t = choose_tile(d.M, d.N, d.K, sizeof(TAcc), d.trans_a != 0);
-    SplitChoice c = choose_split(ctx, t, d.M, d.N, d.K, d.force_splits);
+    SplitChoice c = choose_split(ctx, t, d.M, d.N, d.K, d.force_splits, d.upper_only != 0);
     if (c.splits > 1) {
       const size_t need = (size_t)c.splits * (size_t)d.M * (size_t)d.N * sizeof(TAcc);
       if (d.partial == nullptr || d.partial_bytes < need) return hipErrorInvalidValue;
@@ -372,6 +386,7 @@ struct GemmDispatch {
     P.A = d.A; P.lda = d.lda; P.B = d.B; P.ldb = d.ldb; P.C = d.C; P.ldc = d.ldc;
     P.partial = d.partial; P.k_per_split = c.k_per_split; P.splits = c.splits;
     P.trans_c = d.trans_c; P.alpha = d.alpha; P.beta = d.beta;
+    P.upper_bm = d.upper_only ? t.bm : 0; P.upper_bn = d.upper_only ? t.bn : 0;
     P.r1_u = d.r1_u; P.r1_v = d.r1_v; P.r1_alpha = d.r1_alpha;
     P.dead = d.dead; P.seed = d.seed; P.refill_stream = d.refill_stream;
     P.refill_scale = d.refill_scale; P.refill_ld = d.refill_ld;

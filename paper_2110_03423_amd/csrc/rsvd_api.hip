@@ -225,6 +225,7 @@ static int orthonormalize(rsvd_ctx *ctx, hipStream_t s, rsvd_dtype dtype, const 
     g.C = w.at<double>(L.G); g.ldc = l;
     g.partial = w.at<void>(L.partial); g.partial_bytes = L.partial_bytes;
     g.prof_kind = PK_GRAM;
+    g.upper_only = (l > chol_max_block(ctx)) ? 1 : 0;   // the blocked factorisation reads the upper triangle only
     // small orders: the Cholesky kernel adds the split-K partials itself
     int splits = 1;
     g.skip_reduce = (l <= chol_max_block(ctx)) ? 1 : 0;
