@@ -111,6 +111,55 @@ def cpu_baseline(cfg, A_host, budget_s=20.0):
                 sample=f"{runs} full call(s) of the numpy fp64 oracle on the whole {cfg.m}x{cfg.n} workload")
 
 
+def sweep(args):
+    """Small-l runs at the shapes of configurations 3 and 5: one JSON line per (shape, k, p, q) with the
+    achieved HBM rate of the two kernels that stream A (algorithmic bytes / HIP-event time per launch)."""
+    import dataclasses
+    import torch
+    import workloads
+    from paper_2110_03423_amd import Rsvd, F32, F64
+
+    ctx = Rsvd(0)
+    dev = "cuda:0"
+    for cid in (3, 5):
+        base = workloads.CONFIGS[cid]
+        A = workloads.build(base, device=dev)
+        dt = F32 if base.dtype == "f32" else F64
+        for (k, p, q) in ((8, 8, 1), (24, 8, 1)):
+            cfg = dataclasses.replace(base, k=k, p=p, q=q)
+            ws = ctx.workspace(dt, cfg.m, cfg.n, k, p)
+            out = (torch.empty(k, dtype=A.dtype, device=dev), torch.empty((cfg.m, k), dtype=A.dtype, device=dev),
+                   torch.empty((k, cfg.n), dtype=A.dtype, device=dev))
+
+            def step():
+                ctx.rsvd_run(A, k, p, q, seed=cfg.seed, workspace=ws, want_info=False, out=out)
+
+            for _ in range(args.warmup):
+                step()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(args.steps):
+                step()
+            torch.cuda.synchronize()
+            ms = (time.perf_counter() - t0) * 1e3 / args.steps
+            ctx.rsvd_profile_enable(True)
+            for _ in range(args.steps):
+                step()
+            torch.cuda.synchronize()
+            prof = ctx.rsvd_profile_read()
+            ctx.rsvd_profile_enable(False)
+            line = {"sweep": cfg.name, "dtype": cfg.dtype, "m": cfg.m, "n": cfg.n, "k": k, "p": p, "q": q,
+                    "ms_per_call": round(ms, 4)}
+            for name in ("gemm_ax", "gemm_atx"):
+                tot, cnt = prof[name]
+                r = roofline_for(name, tot / cnt, cfg)
+                line[name] = dict(avg_us=round(tot / cnt * 1e3, 2), bound=r["bound"], achieved=round(r["achieved"], 1),
+                                  unit=r["unit"], frac=round(r["frac"], 4))
+            print(json.dumps(line), flush=True)
+        del A
+        torch.cuda.empty_cache()
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -120,6 +169,9 @@ def main():
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
     ap.add_argument("--centered", action="store_true",
                     help="time rsvd_run_centered (PCA front end: implicit column centring) instead of rsvd_run")
+    ap.add_argument("--sweep", action="store_true",
+                    help="supplementary sweep instead of the benchmark: the shapes of configurations 3 and 5 with "
+                         "(k, p, q) = (8, 8, 1) and (24, 8, 1), where the products with A are HBM bound")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device-to-device copy (reference dispatch for HBM counters)")
     args = ap.parse_args()
@@ -133,6 +185,9 @@ def main():
     import workloads
     from paper_2110_03423_amd import Rsvd, F32, F64
 
+    if args.sweep:
+        sweep(args)
+        return
     cfg = workloads.CONFIGS[args.config]
     dev = "cuda:0"
     A = workloads.build(cfg, device=dev)

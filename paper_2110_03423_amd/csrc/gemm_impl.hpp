@@ -112,9 +112,9 @@ struct TileStage {
 // GENERAL = true: the full epilogue (scaling, accumulation, rank-one term, transposed store,
 // replacement columns).  Two instantiations, because the general epilogue inlines the Philox
 // and Box-Muller code once per accumulator element and the products with A never need it.
-template <typename TIn, typename TAcc, typename TOut, bool TA, int BM, int BN, int WGM, int WGN, int VEC, bool GENERAL>
+template <typename TIn, typename TAcc, typename TOut, bool TA, int BM, int BN, int WGM, int WGN, int VEC, bool GENERAL,
+          int BK = 32>
 __global__ __launch_bounds__(256) void gemm_kernel(const GemmParams P) {
-  constexpr int BK = 32;
   static_assert(WGM * WGN == 4, "four wavefronts per workgroup");
   constexpr int WM = BM / WGM, WN = BN / WGN;
   static_assert(WM % 16 == 0 && WN % 16 == 0, "wave tile must be made of 16x16 blocks");
@@ -306,7 +306,9 @@ inline SplitChoice choose_split(const rsvd_ctx *ctx, const TileChoice &t, int64_
   if (force > 0) {
     s = force;
   } else {
-    const int64_t want = 2 * (int64_t)ctx->cu_count;
+    // narrow outputs stream A with little work per byte: four workgroups per CU keep enough loads in
+    // flight (measured: 5.0 -> 5.8 TB/s for A^T X at 65536 x 16384, l = 16); two are enough otherwise
+    const int64_t want = (t.bn <= 32 ? 4 : 2) * (int64_t)ctx->cu_count;
     if (tiles < want) s = ceil_div(want, tiles);
     const int64_t max_by_k = ktiles / 4 > 0 ? ktiles / 4 : 1;   // at least 4 k-tiles per split
     if (s > max_by_k) s = max_by_k;
@@ -322,7 +324,7 @@ inline SplitChoice choose_split(const rsvd_ctx *ctx, const TileChoice &t, int64_
 
 template <typename TIn, typename TAcc, typename TOut>
 struct GemmDispatch {
-  template <bool TA, int BM, int BN, int WGM, int WGN>
+  template <bool TA, int BM, int BN, int WGM, int WGN, int BK = 32>
   static hipError_t run(hipStream_t s, const GemmParams &P, bool vec) {
     GemmParams Q = P;
     Q.tiles_n = (int)ceil_div(P.N, BN);
@@ -332,11 +334,11 @@ struct GemmDispatch {
     const bool general = P.splits == 1 && (P.alpha != 1.0 || P.beta != 0.0 || P.r1_v != nullptr ||
                                            P.dead != nullptr || P.trans_c != 0);
     if (general) {
-      if (vec) hipLaunchKernelGGL((gemm_kernel<TIn, TAcc, TOut, TA, BM, BN, WGM, WGN, V, true>), grid, dim3(256), 0, s, Q);
-      else hipLaunchKernelGGL((gemm_kernel<TIn, TAcc, TOut, TA, BM, BN, WGM, WGN, 1, true>), grid, dim3(256), 0, s, Q);
+      if (vec) hipLaunchKernelGGL((gemm_kernel<TIn, TAcc, TOut, TA, BM, BN, WGM, WGN, V, true, BK>), grid, dim3(256), 0, s, Q);
+      else hipLaunchKernelGGL((gemm_kernel<TIn, TAcc, TOut, TA, BM, BN, WGM, WGN, 1, true, BK>), grid, dim3(256), 0, s, Q);
     } else {
-      if (vec) hipLaunchKernelGGL((gemm_kernel<TIn, TAcc, TOut, TA, BM, BN, WGM, WGN, V, false>), grid, dim3(256), 0, s, Q);
-      else hipLaunchKernelGGL((gemm_kernel<TIn, TAcc, TOut, TA, BM, BN, WGM, WGN, 1, false>), grid, dim3(256), 0, s, Q);
+      if (vec) hipLaunchKernelGGL((gemm_kernel<TIn, TAcc, TOut, TA, BM, BN, WGM, WGN, V, false, BK>), grid, dim3(256), 0, s, Q);
+      else hipLaunchKernelGGL((gemm_kernel<TIn, TAcc, TOut, TA, BM, BN, WGM, WGN, 1, false, BK>), grid, dim3(256), 0, s, Q);
     }
     return hipGetLastError();
   }
@@ -345,6 +347,7 @@ struct GemmDispatch {
   static hipError_t by_tile(hipStream_t s, const GemmParams &P, const TileChoice &t, bool vec) {
     if (t.bm == 64) {
       switch (t.bn) {
+        // (64-deep k-tiles for these HBM-bound shapes measured no better than 32)
         case 16:  return run<TA, 64, 16, 4, 1>(s, P, vec);
         case 32:  return run<TA, 64, 32, 4, 1>(s, P, vec);
         case 48:  return run<TA, 64, 48, 4, 1>(s, P, vec);
