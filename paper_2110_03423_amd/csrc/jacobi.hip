@@ -50,6 +50,14 @@ template <typename T> __device__ __forceinline__ T half_row_sum(T v) {
   return v;
 }
 
+// Sum over the G = 4 or 8 lanes that share a column pair.
+template <int G, typename T> __device__ __forceinline__ T group_sum(T v) {
+  v += dpp_mov<0xB1>(v);
+  v += dpp_mov<0x4E>(v);
+  if (G == 8) v += dpp_mov<0x141>(v);
+  return v;
+}
+
 // Reciprocal, square root and reciprocal square root from the hardware estimates
 // (1 ulp in fp32; refined by Newton steps in fp64).  The rotation parameters sit
 // on the serial path of every pair, so their instruction count matters.
@@ -100,22 +108,52 @@ __device__ __forceinline__ void tournament_pair(int n2, int r, int i, int &a, in
   }
 }
 
-// Rotate columns p, q of M (and of J), stored column-major with stride ldm and
-// zero-padded to 8 * RPL rows.  LDS is accessed in 8-byte units (two floats or one
-// double): lane lg of the group's 8 lanes owns units lg, lg + 8, lg + 16, ... of a
-// column (the 8 lanes read one contiguous 64-byte run, free of bank conflicts) and
-// keeps them in registers between the inner products and the update.  Returns
-// true when a rotation was applied.
-template <typename T, int RPL>
-__device__ __forceinline__ bool rotate_pair(T *Mc, T *Jc, int ldm, int p, int q, int lg, T tol, T floor2) {
+// Pair order of the LDS-resident kernel: a recursive halving of the column set.  A set
+// of columns splits into a front half A (floor) and a back half B (ceil); for |B| rounds
+// column A_i meets B_{(i + r) mod |B|}, which covers every pair between A and B with all
+// columns of A busy in every round; then A and B are treated the same way, side by side.
+// All sets of one level have sizes that differ by at most one, so a level of sets of size
+// <= ms takes ceil(ms / 2) rounds and a sweep ceil(l/2) + ceil(l/4) + ... ~ l rounds, like the
+// circle method.  The point of this order: each lane group keeps its column of A in
+// registers for the whole level and only the column of B travels through LDS, which halves
+// the LDS traffic of a round (the LDS port, shared by the four SIMDs, is what bounds it).
+struct JacLevel {
+  unsigned char stat;      // column this group keeps for the level (255: none)
+  unsigned char bstart;    // first column of B
+  unsigned char bsize;     // |B|
+  unsigned char idx;       // i: position of `stat` in A
+};
+constexpr int kJacLevels = 8, kJacGroups = 64;    // orders up to 128
+
+template <typename T> using jac_unit = T __attribute__((ext_vector_type(8 / sizeof(T))));
+
+// Columns are stored column-major with stride ldm and zero-padded to G * RPL rows.  LDS is
+// accessed in 8-byte units (two floats or one double): lane lg of the group's G lanes owns
+// units lg, lg + G, lg + 2 G, ... of a column (the G lanes touch one contiguous run).
+template <typename T, int RPL, int G>
+__device__ __forceinline__ void load_column(const T *col, int lg, jac_unit<T> (&x)[RPL / (8 / (int)sizeof(T))]) {
+  const jac_unit<T> *p = reinterpret_cast<const jac_unit<T> *>(col) + lg;
+#pragma unroll
+  for (int r = 0; r < RPL / (8 / (int)sizeof(T)); ++r) x[r] = p[G * r];
+}
+template <typename T, int RPL, int G>
+__device__ __forceinline__ void store_column(T *col, int lg, const jac_unit<T> (&x)[RPL / (8 / (int)sizeof(T))]) {
+  jac_unit<T> *p = reinterpret_cast<jac_unit<T> *>(col) + lg;
+#pragma unroll
+  for (int r = 0; r < RPL / (8 / (int)sizeof(T)); ++r) p[G * r] = x[r];
+}
+
+// Rotate the pair (kept column x of M with its column u of J, in registers; column q in
+// LDS).  Returns the relative size |x.y| / (|x| |y|) of the inner product it rotated away,
+// 0 when it left the pair alone.
+template <typename T, int RPL, int G>
+__device__ __forceinline__ float rotate_moving(jac_unit<T> (&x)[RPL / (8 / (int)sizeof(T))],
+                                               jac_unit<T> (&u)[RPL / (8 / (int)sizeof(T))], T *Mc, T *Jc, int ldm,
+                                               int q, int lg, T tol, T floor2) {
   constexpr int V = 8 / sizeof(T);          // elements per LDS access
   constexpr int NV = RPL / V;               // accesses per column per lane
-  typedef T unit __attribute__((ext_vector_type(V)));
-  unit *mp = reinterpret_cast<unit *>(Mc + p * ldm) + lg;
-  unit *mq = reinterpret_cast<unit *>(Mc + q * ldm) + lg;
-  unit x[NV], y[NV];
-#pragma unroll
-  for (int r = 0; r < NV; ++r) { x[r] = mp[8 * r]; y[r] = mq[8 * r]; }
+  jac_unit<T> y[NV];
+  load_column<T, RPL, G>(Mc + q * ldm, lg, y);
   T alpha = 0, beta = 0, gamma = 0;
 #pragma unroll
   for (int r = 0; r < NV; ++r)
@@ -125,50 +163,75 @@ __device__ __forceinline__ bool rotate_pair(T *Mc, T *Jc, int ldm, int p, int q,
       beta += y[r][e] * y[r][e];
       gamma += x[r][e] * y[r][e];
     }
-  alpha = half_row_sum(alpha);
-  beta = half_row_sum(beta);
-  gamma = half_row_sum(gamma);
+  alpha = group_sum<G>(alpha);
+  beta = group_sum<G>(beta);
+  gamma = group_sum<G>(gamma);
   if (alpha <= floor2 || beta <= floor2) return 0.f;
   const T limit = tol * fast_sqrt(alpha * beta);
   if (!(fabs(gamma) > limit)) return 0.f;
   const float ratio = (float)(fabs(gamma) * fast_rsq(alpha * beta));
-  unit *jp = reinterpret_cast<unit *>(Jc + p * ldm) + lg;
-  unit *jq = reinterpret_cast<unit *>(Jc + q * ldm) + lg;
-  unit u[NV], v[NV];
-#pragma unroll
-  for (int r = 0; r < NV; ++r) { u[r] = jp[8 * r]; v[r] = jq[8 * r]; }
+  jac_unit<T> v[NV];
+  load_column<T, RPL, G>(Jc + q * ldm, lg, v);
   T c, s;
   rotation_params(alpha, beta, gamma, c, s);
 #pragma unroll
   for (int r = 0; r < NV; ++r) {
-    mp[8 * r] = c * x[r] - s * y[r];
-    mq[8 * r] = s * x[r] + c * y[r];
+    const jac_unit<T> xo = x[r];
+    x[r] = c * xo - s * y[r];
+    y[r] = s * xo + c * y[r];
   }
+  store_column<T, RPL, G>(Mc + q * ldm, lg, y);
 #pragma unroll
   for (int r = 0; r < NV; ++r) {
-    jp[8 * r] = c * u[r] - s * v[r];
-    jq[8 * r] = s * u[r] + c * v[r];
+    const jac_unit<T> uo = u[r];
+    u[r] = c * uo - s * v[r];
+    v[r] = s * uo + c * v[r];
   }
+  store_column<T, RPL, G>(Jc + q * ldm, lg, v);
   return ratio;
 }
 
-// Padded row count and column stride of the LDS layout for order l.
+// The stride is chosen so that the columns a half wavefront touches in one access (8 pairs of 4
+// lanes, or 4 pairs of 8) start 8 (16) banks apart: padded rows + 32 bytes for G = 4.
 __host__ __device__ inline int jacobi_rows_padded(int l) { return ((l + 15) / 16) * 16; }
-__host__ __device__ inline int jacobi_ldm(int l) { return jacobi_rows_padded(l) + 2; }
+__host__ __device__ inline int jacobi_ldm(int l, int G, int elem_size) {
+  return jacobi_rows_padded(l) + (G == 4 ? 32 / elem_size : 2);
+}
 
-template <typename T, typename TIn, int RPL>
-__global__ __launch_bounds__(512) void jacobi_lds_kernel(const TIn *__restrict__ M, int l, T *__restrict__ sigma,
+template <typename T, typename TIn, int RPL, int G>
+__global__ __launch_bounds__(64 * G) void jacobi_lds_kernel(const TIn *__restrict__ M, int l, T *__restrict__ sigma,
                                                          T *__restrict__ X, T *__restrict__ W, DevInfo *info) {
   extern __shared__ __attribute__((aligned(16))) double lds_raw[];
-  const int ldm = jacobi_ldm(l);
+  const int ldm = jacobi_ldm(l, G, (int)sizeof(T));
   T *Mc = reinterpret_cast<T *>(lds_raw);
   T *Jc = Mc + (size_t)l * ldm;
   T *nrm = Jc + (size_t)l * ldm;
   int *rnk = reinterpret_cast<int *>(nrm + l);
   __shared__ int rotations;
   __shared__ T wave_sum[8];
+  __shared__ JacLevel lev[kJacLevels][kJacGroups];
 
   const int tid = threadIdx.x, nt = blockDim.x;
+  // pair order: every column finds, level by level, the set it belongs to; the columns of
+  // a front half claim lane group (start of the set) / 2 + (position in the half)
+  for (int e = tid; e < kJacLevels * kJacGroups; e += nt) (&lev[0][0])[e].stat = 255;
+  __syncthreads();
+  if (tid < l) {
+    int start = 0, size = l;
+    for (int d = 0; d < kJacLevels && size > 1; ++d) {
+      const int h = size >> 1;
+      if (tid < start + h) {
+        JacLevel e;
+        e.stat = (unsigned char)tid; e.bstart = (unsigned char)(start + h); e.bsize = (unsigned char)(size - h);
+        e.idx = (unsigned char)(tid - start);
+        lev[d][(start >> 1) + (tid - start)] = e;
+        size = h;
+      } else {
+        start += h;
+        size -= h;
+      }
+    }
+  }
   T fro2 = 0;
   for (int idx = tid; idx < l * ldm; idx += nt) {
     const int c = idx / ldm, r = idx - c * ldm;
@@ -187,25 +250,38 @@ __global__ __launch_bounds__(512) void jacobi_lds_kernel(const TIn *__restrict__
   for (int w = 0; w < (nt >> 6); ++w) fro2 += wave_sum[w];
   const T floor2 = Eps<T>::value * Eps<T>::value * fro2;
 
-  constexpr int G = 8;           // lanes per column pair
-  const int n2 = l + (l & 1), npairs = n2 / 2;
-  const int group = tid / G, lg = tid % G, ngroups = nt / G;
+  const int group = tid / G, lg = tid % G;       // G lanes per column pair
   const T tol = Eps<T>::value * sqrt((T)l);
   int sweeps = 0;
   bool converged = (l < 2);
-  // nt >= 8 * npairs: every pair of a round has its own lane group
-  const bool has_pair = group < npairs;
-  (void)ngroups;
   const float rho_last = 0.25f * sqrtf((float)tol);
+  constexpr int NV = RPL / (8 / (int)sizeof(T));
   while (!converged && sweeps < kJacobiMaxSweeps) {
     ++sweeps;
     float rho = 0.f;
-    for (int r = 0; r < n2 - 1; ++r) {
-      int a, b;
-      tournament_pair(n2, r, has_pair ? group : 0, a, b);
-      if (has_pair && a < l && b < l) {
-        const int p = a < b ? a : b, q = a < b ? b : a;
-        rho = fmaxf(rho, rotate_pair<T, RPL>(Mc, Jc, ldm, p, q, lg, tol, floor2));
+    int d = 0;
+    for (int ms = l; ms > 1; ms = (ms + 1) >> 1, ++d) {      // ms: largest set of this level
+      JacLevel e;
+      e.stat = 255; e.bstart = 0; e.bsize = 0; e.idx = 0;
+      if (group < kJacGroups) e = lev[d][group];
+      const bool act = e.stat != 255;
+      jac_unit<T> x[NV], u[NV];
+      if (act) {
+        load_column<T, RPL, G>(Mc + e.stat * ldm, lg, x);
+        load_column<T, RPL, G>(Jc + e.stat * ldm, lg, u);
+      }
+      const int nr = ms - (ms >> 1);
+      for (int r = 0; r < nr; ++r) {
+        if (act && r < e.bsize) {
+          int j = e.idx + r;
+          if (j >= e.bsize) j -= e.bsize;
+          rho = fmaxf(rho, rotate_moving<T, RPL, G>(x, u, Mc, Jc, ldm, e.bstart + j, lg, tol, floor2));
+        }
+        __syncthreads();
+      }
+      if (act) {
+        store_column<T, RPL, G>(Mc + e.stat * ldm, lg, x);
+        store_column<T, RPL, G>(Jc + e.stat * ldm, lg, u);
       }
       __syncthreads();
     }
@@ -523,15 +599,21 @@ __global__ __launch_bounds__(256) void jb_scatter_kernel(const T *__restrict__ M
 
 constexpr int kJbMaxSweeps = 24;
 
+// Lanes per column pair of the LDS-resident kernel.
+static int jacobi_group(rsvd_dtype dtype, int64_t l) {
+  (void)dtype; (void)l;
+  return 8;        // 4 lanes per pair measured slower at every order
+}
+
 static size_t jacobi_lds_bytes(rsvd_dtype dtype, int64_t l) {
   const size_t es = dtype_size(dtype);
-  const size_t ldm = (size_t)jacobi_ldm((int)l);
+  const size_t ldm = (size_t)jacobi_ldm((int)l, jacobi_group(dtype, l), (int)es);
   return align_up(2 * (size_t)l * ldm * es + (size_t)l * (es + sizeof(int)), 16);
 }
 
 int jacobi_max_lds_order(const rsvd_ctx *ctx, rsvd_dtype dtype) {
   int l = 2;
-  while (l < 128 && jacobi_lds_bytes(dtype, l + 1) + 512 <= ctx->lds_per_block) ++l;
+  while (l < 128 && jacobi_lds_bytes(dtype, l + 1) + 4096 <= ctx->lds_per_block) ++l;
   return l;      // 128 = 8 lanes per pair x 16 rows each lane keeps in registers
 }
 
@@ -591,7 +673,7 @@ static hipError_t jacobi_block_launch(rsvd_ctx *ctx, hipStream_t s, rsvd_dtype d
     static bool attr_set = false;                                                                                \
     if (!attr_set) {                                                                                             \
       (void)hipFuncSetAttribute(reinterpret_cast<const void *>(&jb_panel_kernel<T, NVV>),                        \
-                                hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 512);                   \
+                                hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 4096);                   \
       (void)hipGetLastError();                                                                                   \
       attr_set = true;                                                                                           \
     }                                                                                                            \
@@ -617,34 +699,46 @@ static hipError_t jacobi_block_launch(rsvd_ctx *ctx, hipStream_t s, rsvd_dtype d
   return hipGetLastError();
 }
 
-template <typename T, typename TIn, int RPL>
+template <typename T, typename TIn, int RPL, int G>
 static hipError_t launch_lds(hipStream_t s, int nt, size_t lds, const void *M, int l, void *sigma, void *X, void *W,
                              DevInfo *info) {
   static bool attr_set = false;
   if (!attr_set) {
-    (void)hipFuncSetAttribute(reinterpret_cast<const void *>(&jacobi_lds_kernel<T, TIn, RPL>),
-                              hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 512);
+    (void)hipFuncSetAttribute(reinterpret_cast<const void *>(&jacobi_lds_kernel<T, TIn, RPL, G>),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 4096);
     (void)hipGetLastError();
     attr_set = true;
   }
-  hipLaunchKernelGGL((jacobi_lds_kernel<T, TIn, RPL>), dim3(1), dim3(nt), lds, s, (const TIn *)M, l, (T *)sigma,
+  hipLaunchKernelGGL((jacobi_lds_kernel<T, TIn, RPL, G>), dim3(1), dim3(nt), lds, s, (const TIn *)M, l, (T *)sigma,
                      (T *)X, (T *)W, info);
   return hipGetLastError();
 }
 
-// rows per lane = padded rows / 8: 2, 4, ..., 16
+// rows per lane = padded rows / G
 template <typename T, typename TIn>
-static hipError_t launch_lds_g(hipStream_t s, int nt, int rpl, size_t lds, const void *M, int l, void *sigma, void *X,
-                               void *W, DevInfo *info) {
+static hipError_t launch_lds_g(hipStream_t s, int nt, int G, int rpl, size_t lds, const void *M, int l, void *sigma,
+                               void *X, void *W, DevInfo *info) {
+  if (G == 8) {
+    switch (rpl) {
+      case 2: return launch_lds<T, TIn, 2, 8>(s, nt, lds, M, l, sigma, X, W, info);
+      case 4: return launch_lds<T, TIn, 4, 8>(s, nt, lds, M, l, sigma, X, W, info);
+      case 6: return launch_lds<T, TIn, 6, 8>(s, nt, lds, M, l, sigma, X, W, info);
+      case 8: return launch_lds<T, TIn, 8, 8>(s, nt, lds, M, l, sigma, X, W, info);
+      case 10: return launch_lds<T, TIn, 10, 8>(s, nt, lds, M, l, sigma, X, W, info);
+      case 12: return launch_lds<T, TIn, 12, 8>(s, nt, lds, M, l, sigma, X, W, info);
+      case 14: return launch_lds<T, TIn, 14, 8>(s, nt, lds, M, l, sigma, X, W, info);
+      default: return launch_lds<T, TIn, 16, 8>(s, nt, lds, M, l, sigma, X, W, info);
+    }
+  }
   switch (rpl) {
-    case 2: return launch_lds<T, TIn, 2>(s, nt, lds, M, l, sigma, X, W, info);
-    case 4: return launch_lds<T, TIn, 4>(s, nt, lds, M, l, sigma, X, W, info);
-    case 6: return launch_lds<T, TIn, 6>(s, nt, lds, M, l, sigma, X, W, info);
-    case 8: return launch_lds<T, TIn, 8>(s, nt, lds, M, l, sigma, X, W, info);
-    case 10: return launch_lds<T, TIn, 10>(s, nt, lds, M, l, sigma, X, W, info);
-    case 12: return launch_lds<T, TIn, 12>(s, nt, lds, M, l, sigma, X, W, info);
-    case 14: return launch_lds<T, TIn, 14>(s, nt, lds, M, l, sigma, X, W, info);
-    default: return launch_lds<T, TIn, 16>(s, nt, lds, M, l, sigma, X, W, info);
+    case 4: return launch_lds<T, TIn, 4, 4>(s, nt, lds, M, l, sigma, X, W, info);
+    case 8: return launch_lds<T, TIn, 8, 4>(s, nt, lds, M, l, sigma, X, W, info);
+    case 12: return launch_lds<T, TIn, 12, 4>(s, nt, lds, M, l, sigma, X, W, info);
+    case 16: return launch_lds<T, TIn, 16, 4>(s, nt, lds, M, l, sigma, X, W, info);
+    case 20: return launch_lds<T, TIn, 20, 4>(s, nt, lds, M, l, sigma, X, W, info);
+    case 24: return launch_lds<T, TIn, 24, 4>(s, nt, lds, M, l, sigma, X, W, info);
+    case 28: return launch_lds<T, TIn, 28, 4>(s, nt, lds, M, l, sigma, X, W, info);
+    default: return launch_lds<T, TIn, 32, 4>(s, nt, lds, M, l, sigma, X, W, info);
   }
 }
 
@@ -661,18 +755,19 @@ hipError_t jacobi_launch(rsvd_ctx *ctx, hipStream_t s, rsvd_dtype dtype, int64_t
     return jacobi_block_launch<double>(ctx, s, dtype, (int)l, (const double *)M, (double *)sigma, (double *)X,
                                        (double *)W, info, (char *)scratch);
   }
-  // one 8-lane group per column pair of a round, all pairs of a round at once
+  // one G-lane group per column pair of a round, all pairs of a round at once
   const int npairs = (int)((l + 1) / 2);
-  int nt = (int)align_up((size_t)npairs * 8, 64);
-  if (nt > 512) nt = 512;
-  const int g = jacobi_rows_padded((int)l) / 8;          // rows per lane
+  const int G = jacobi_group(dtype, l);
+  int nt = (int)align_up((size_t)npairs * G, 64);
+  if (nt > 64 * G) nt = 64 * G;
+  const int g = jacobi_rows_padded((int)l) / G;          // rows per lane
   const size_t lds = jacobi_lds_bytes(dtype, l);
   ProfScope ps(ctx, s, PK_JACOBI);
   if (dtype == RSVD_F32) {
-    if (m_is_f64) return launch_lds_g<float, double>(s, nt, g, lds, M, (int)l, sigma, X, W, info);
-    return launch_lds_g<float, float>(s, nt, g, lds, M, (int)l, sigma, X, W, info);
+    if (m_is_f64) return launch_lds_g<float, double>(s, nt, G, g, lds, M, (int)l, sigma, X, W, info);
+    return launch_lds_g<float, float>(s, nt, G, g, lds, M, (int)l, sigma, X, W, info);
   }
-  return launch_lds_g<double, double>(s, nt, g, lds, M, (int)l, sigma, X, W, info);
+  return launch_lds_g<double, double>(s, nt, G, g, lds, M, (int)l, sigma, X, W, info);
 }
 
 }  // namespace rsvd
