@@ -28,8 +28,8 @@ PEAK_VALU = {"f32": 157.3e12, "f64": 78.6e12}    # vector FLOP/s (256 CUs, 2.4 G
 
 # HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this script at configuration 2,
 # scaled by the same counters on a plain 1 GiB copy (figures and commands: profiles/rsvd_run_cfg2_hbm_counters.md).
-MEASURED_TRAFFIC = {2: {"cholesky": 0.26e6, "jacobi": 0.12e6, "gemm_atx": 136.8e6, "gemm_ax": 101.2e6,
-                        "gram": 10.1e6}}
+MEASURED_TRAFFIC = {2: {"cholesky": 0.13e6, "jacobi": 0.11e6, "gemm_atx": 93.6e6, "gemm_ax": 97.2e6,
+                        "gram": 6.6e6, "apply_rinv": 7.1e6}}
 
 
 def kernel_models(cfg):
@@ -82,9 +82,11 @@ def roofline_for(name, avg_ms, cfg, sweeps=None):
                     frac=flops / t / peak, traffic=None, kernel=name, avg_us=avg_ms * 1e3)
     if "alu" in mod and flops:
         # single-workgroup kernels on the serial path: priced against the vector peak
+        # (one workgroup can use one of the 256 CUs: frac_one_cu prices it against that share)
         peak = PEAK_VALU[mod["alu"]]
         return dict(bound="alu", achieved=flops / t / 1e12, peak=peak / 1e12, unit="TFLOP/s",
-                    frac=flops / t / peak, traffic=None, kernel=name, avg_us=avg_ms * 1e3)
+                    frac=flops / t / peak, frac_one_cu=flops / t / (peak / 256.0), traffic=None, kernel=name,
+                    avg_us=avg_ms * 1e3)
     return dict(bound="hbm", achieved=mod["bytes"] / t / 1e9, peak=PEAK_HBM / 1e9, unit="GB/s",
                 frac=mod["bytes"] / t / PEAK_HBM, traffic=None, kernel=name, avg_us=avg_ms * 1e3)
 
