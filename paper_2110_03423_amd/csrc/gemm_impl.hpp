@@ -292,6 +292,7 @@ struct SplitChoice {
   int64_t k_per_split;
 };
 
+// Split-K factor.
 inline SplitChoice choose_split(const rsvd_ctx *ctx, const TileChoice &t, int64_t M, int64_t N, int64_t K,
                                 int force, bool upper = false) {
   int64_t tiles = ceil_div(M, t.bm) * ceil_div(N, t.bn);
@@ -306,13 +307,17 @@ inline SplitChoice choose_split(const rsvd_ctx *ctx, const TileChoice &t, int64_
   if (force > 0) {
     s = force;
   } else {
-    // narrow outputs stream A with little work per byte: four workgroups per CU keep enough loads in
-    // flight (measured: 5.0 -> 5.8 TB/s for A^T X at 65536 x 16384, l = 16); two are enough otherwise
-    const int64_t want = (t.bn <= 32 ? 4 : 2) * (int64_t)ctx->cu_count;
-    if (tiles < want) s = ceil_div(want, tiles);
-    const int64_t max_by_k = ktiles / 4 > 0 ? ktiles / 4 : 1;   // at least 4 k-tiles per split
+    // Aim at four workgroups per CU (measured better than two from l = 16, where the kernels are HBM
+    // bound and need the loads in flight, to l = 576), rounded to the nearest factor so that a grid
+    // that nearly fills the chip is left alone.  Every split pays a prologue and a tile-sized
+    // partial store: at least 4 k-tiles per split for the 64-row tiles, 8 for the larger ones.
+    const int64_t want = 4 * (int64_t)ctx->cu_count;
+    if (tiles < want) s = (want + tiles / 2) / tiles;
+    const int64_t min_k = (t.bm * t.bn > 64 * 128) ? 8 : 4;
+    const int64_t max_by_k = ktiles / min_k > 0 ? ktiles / min_k : 1;
     if (s > max_by_k) s = max_by_k;
     if (s > 256) s = 256;
+    if (s < 1) s = 1;
   }
   if (s > ktiles) s = ktiles > 0 ? ktiles : 1;
   SplitChoice c;
