@@ -394,6 +394,60 @@ __device__ __forceinline__ float rotate_pair_panel(T *Pc, T *Tc, int ldp, int ld
   return ratio;
 }
 
+// Cross-phase version: the column of the first block (x, NV units per lane) and its
+// column of T (tx: entries lg and lg + 32) stay in registers for all rounds of the launch;
+// only the column q of the second block and its column of T go through LDS.
+template <typename T, int NV>
+__device__ __forceinline__ float rotate_moving_panel(jac_unit<T> (&x)[NV], T (&tx)[2], T *Pc, T *Tc, int ldp, int ldt,
+                                                    int rows_t, int q, int lg, T tol, T floor2) {
+  constexpr int V = 8 / sizeof(T);
+  jac_unit<T> *mq = reinterpret_cast<jac_unit<T> *>(Pc + q * ldp) + lg;
+  jac_unit<T> y[NV];
+#pragma unroll
+  for (int r = 0; r < NV; ++r) y[r] = mq[32 * r];
+  T alpha = 0, beta = 0, gamma = 0;
+#pragma unroll
+  for (int r = 0; r < NV; ++r)
+#pragma unroll
+    for (int e = 0; e < V; ++e) {
+      alpha += x[r][e] * x[r][e];
+      beta += y[r][e] * y[r][e];
+      gamma += x[r][e] * y[r][e];
+    }
+  alpha = group32_sum(alpha);
+  beta = group32_sum(beta);
+  gamma = group32_sum(gamma);
+  if (alpha <= floor2 || beta <= floor2) return 0.f;
+  const T limit = tol * fast_sqrt(alpha * beta);
+  if (!(fabs(gamma) > limit)) return 0.f;
+  const float ratio = (float)(fabs(gamma) * fast_rsq(alpha * beta));
+  T c, s;
+  rotation_params(alpha, beta, gamma, c, s);
+#pragma unroll
+  for (int r = 0; r < NV; ++r) {
+    const jac_unit<T> xo = x[r];
+    x[r] = c * xo - s * y[r];
+    mq[32 * r] = s * xo + c * y[r];
+  }
+  T *tq = Tc + q * ldt;
+#pragma unroll
+  for (int j = 0; j < 2; ++j) {
+    const int i = lg + 32 * j;
+    if (i < rows_t) {
+      const T a = tx[j], bq = tq[i];
+      tx[j] = c * a - s * bq;
+      tq[i] = s * a + c * bq;
+    }
+  }
+  return ratio;
+}
+
+// Workgroup barrier that orders LDS accesses only (a full __syncthreads also waits for the
+// wavefront's outstanding global stores).
+__device__ __forceinline__ void lds_barrier() {
+  asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
 // scratch header shared by the block-Jacobi kernels
 struct JbHeader {
   double fro2;            // ||M||_F^2
@@ -468,10 +522,47 @@ __global__ __launch_bounds__(1024) void jb_panel_kernel(T *__restrict__ Mt, T *_
 
   const int tid = threadIdx.x, nt = blockDim.x;
   auto gcol = [&](int c) { return c < cols_i ? bi * b + c : bj * b + (c - cols_i); };
-  for (int c = tid / 64; c < 2 * b; c += nt / 64) {
-    const T *src = Mt + (int64_t)gcol(c < ncols ? c : 0) * l;
-    for (int r = tid & 63; r < ldp; r += 64) Pc[c * ldp + r] = (c < ncols && r < l) ? src[r] : (T)0;
-  }
+  // panel in: a wavefront takes whole columns, two at a time, and issues every load of both
+  // before the first LDS store (the loads are the latency to hide)
+  constexpr int LPW = (ldp + 63) / 64;      // elements per lane per column
+  const int lane64 = tid & 63, wave = tid >> 6, nwave = nt >> 6;
+  auto panel_in = [&](const T *__restrict__ G) {
+    for (int c0 = wave; c0 < 2 * b; c0 += 2 * nwave) {
+      T v[2][LPW];
+#pragma unroll
+      for (int u = 0; u < 2; ++u) {
+        const int c = c0 + u * nwave;
+        const T *src = G + (int64_t)gcol(c < ncols ? c : 0) * l;
+#pragma unroll
+        for (int j = 0; j < LPW; ++j) {
+          const int r = lane64 + 64 * j;
+          v[u][j] = (c < ncols && r < l) ? src[r] : (T)0;
+        }
+      }
+#pragma unroll
+      for (int u = 0; u < 2; ++u) {
+        const int c = c0 + u * nwave;
+        if (c < 2 * b) {
+#pragma unroll
+          for (int j = 0; j < LPW; ++j) {
+            const int r = lane64 + 64 * j;
+            if (r < ldp) Pc[c * ldp + r] = v[u][j];
+          }
+        }
+      }
+    }
+  };
+  auto panel_out = [&](T *__restrict__ G) {
+    for (int c = wave; c < ncols; c += nwave) {
+      T *dst = G + (int64_t)gcol(c) * l;
+#pragma unroll
+      for (int j = 0; j < LPW; ++j) {
+        const int r = lane64 + 64 * j;
+        if (r < l) dst[r] = Pc[c * ldp + r];
+      }
+    }
+  };
+  panel_in(Mt);
   for (int idx = tid; idx < 2 * b * ldt; idx += nt) {
     const int c = idx / ldt, r = idx - c * ldt;
     Tc[idx] = (r == c && c < ncols) ? (T)1 : (T)0;
@@ -496,49 +587,67 @@ __global__ __launch_bounds__(1024) void jb_panel_kernel(T *__restrict__ Mt, T *_
       __syncthreads();
     }
   } else {
+    // lane group g keeps column g of the first block (and its column of T) for all b rounds
+    const bool act = group < cols_i;
+    jac_unit<T> x[NV];
+    T tx[2] = {(T)0, (T)0};
+    if (act) {
+      const jac_unit<T> *mp = reinterpret_cast<const jac_unit<T> *>(Pc + group * ldp) + lg;
+#pragma unroll
+      for (int r = 0; r < NV; ++r) x[r] = mp[32 * r];
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+        if (lg + 32 * j < ncols) tx[j] = Tc[group * ldt + lg + 32 * j];
+    }
     for (int r = 0; r < b; ++r) {
       int qi = group + r;
       if (qi >= b) qi -= b;
-      if (group < cols_i && qi < cols_j)
-        rho = fmaxf(rho, rotate_pair_panel<T, NV>(Pc, Tc, ldp, ldt, ncols, group, cols_i + qi, lg, tol, floor2));
+      if (act && qi < cols_j)
+        rho = fmaxf(rho, rotate_moving_panel<T, NV>(x, tx, Pc, Tc, ldp, ldt, ncols, cols_i + qi, lg, tol, floor2));
       __syncthreads();
     }
+    if (act) {
+      jac_unit<T> *mp = reinterpret_cast<jac_unit<T> *>(Pc + group * ldp) + lg;
+#pragma unroll
+      for (int r = 0; r < NV; ++r) mp[32 * r] = x[r];
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+        if (lg + 32 * j < ncols) Tc[group * ldt + lg + 32 * j] = tx[j];
+    }
+    __syncthreads();
   }
   if (rho > 0.f) atomicMax(&rotations, __float_as_int(rho));
   __syncthreads();
   const int rho_bits = rotations;
   if (rho_bits == 0) return;                                  // nothing changed: leave M and J alone
 
-  for (int c = tid / 64; c < ncols; c += nt / 64) {
-    T *dst = Mt + (int64_t)gcol(c) * l;
-    for (int r = tid & 63; r < l; r += 64) dst[r] = Pc[c * ldp + r];
-  }
-  __syncthreads();
+  panel_out(Mt);
+  // (only LDS is shared between the phases here: wait for this wavefront's LDS traffic, not for
+  // its global stores, before the barrier)
+  lds_barrier();
   // J[:, panel] <- J[:, panel] T on the matrix cores, the old columns staged through the
   // LDS space of the panel: an (l x 2b) by (2b x 2b) product in 16 x 16 blocks, K = 2b.
-  for (int c = tid / 64; c < ncols; c += nt / 64) {
-    const T *src = Jt + (int64_t)gcol(c) * l;
-    for (int r = tid & 63; r < l; r += 64) Pc[c * ldp + r] = src[r];
-  }
+  panel_in(Jt);
   __syncthreads();
   {
     typedef typename Mfma<T>::vec acc_t;
-    const int lane = tid & 63, wave = tid >> 6, nwave = nt >> 6;
-    const int r16 = lane & 15, kq = lane >> 4;
+    const int r16 = lane64 & 15, kq = lane64 >> 4;
     const int row_blocks = (l + 15) / 16, col_blocks = (2 * b) / 16;
     for (int blk = wave; blk < row_blocks * col_blocks; blk += nwave) {
       const int rb = blk / col_blocks, cb = blk - rb * col_blocks;
       acc_t acc = (acc_t)(T)0;
-      for (int k0 = 0; k0 < 2 * b; k0 += 4) {
-        const T av = Pc[(k0 + kq) * ldp + rb * 16 + r16];           // Jold[row][k]
-        const T bv = Tc[(cb * 16 + r16) * ldt + k0 + kq];            // T[k][col]
-        acc = Mfma<T>::run(av, bv, acc);
-      }
+      const T *ap = Pc + kq * ldp + rb * 16 + r16;                  // Jold[row][k]
+      const T *bp = Tc + (cb * 16 + r16) * ldt + kq;                // T[k][col]
+#pragma unroll 4
+      for (int k0 = 0; k0 < 2 * b; k0 += 4) acc = Mfma<T>::run(ap[k0 * ldp], bp[k0], acc);
       const int cn = cb * 16 + r16;
+      if (cn < ncols) {
+        T *dst = Jt + (int64_t)gcol(cn) * l;
 #pragma unroll
-      for (int v = 0; v < 4; ++v) {
-        const int r = rb * 16 + Mfma<T>::row(lane, v);
-        if (r < l && cn < ncols) Jt[(int64_t)gcol(cn) * l + r] = acc[v];
+        for (int v = 0; v < 4; ++v) {
+          const int r = rb * 16 + Mfma<T>::row(lane64, v);
+          if (r < l) dst[r] = acc[v];
+        }
       }
     }
   }
@@ -633,7 +742,7 @@ static int jb_block_width(const rsvd_ctx *ctx, rsvd_dtype dtype, int64_t l) {
   const int nv = jb_units_per_lane(dtype, l);
   if (nv == 0) return 0;
   const size_t ldp = (size_t)32 * nv * (8 / es) + 2;
-  for (int b = 32; b >= 8; b -= 8) {
+  for (int b = 32; b >= 8; b -= 8) {      // (16 and 24 measured alike at l = 288 and 576, 8 slower)
     const size_t need = ((size_t)(2 * b) * ldp + (size_t)(2 * b) * (2 * b + 2)) * es + 1024;
     if (need <= ctx->lds_per_block) return b;
   }
