@@ -108,11 +108,15 @@ struct TileStage {
   }
 };
 
-// GENERAL = false: the kernel can only store its tile as it is (or as a split-K partial);
-// GENERAL = true: the full epilogue (scaling, accumulation, rank-one term, transposed store,
-// replacement columns).  Two instantiations, because the general epilogue inlines the Philox
-// and Box-Muller code once per accumulator element and the products with A never need it.
-template <typename TIn, typename TAcc, typename TOut, bool TA, int BM, int BN, int WGM, int WGN, int VEC, bool GENERAL,
+// Epilogues (EPI):
+//   0  the kernel can only store its tile as it is (or as a split-K partial);
+//   1  the full epilogue (scaling, accumulation, rank-one term, transposed store, replacement columns);
+//   2  C = alpha * acc + beta * C only, with all of a thread's old values of C loaded before the
+//      first store (element by element the loads would queue behind the stores, one memory
+//      round trip each).
+// Separate instantiations, because the full epilogue inlines the Philox and Box-Muller code once per
+// accumulator element and the products with A never need it.
+template <typename TIn, typename TAcc, typename TOut, bool TA, int BM, int BN, int WGM, int WGN, int VEC, int EPI,
           int BK = 32>
 __global__ __launch_bounds__(256) void gemm_kernel(const GemmParams P) {
   static_assert(WGM * WGN == 4, "four wavefronts per workgroup");
@@ -194,7 +198,7 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmParams P) {
   }
 
   // epilogue
-  if (!GENERAL || P.splits > 1) {
+  if (EPI == 0 || P.splits > 1) {
     TOut *Cp = (TOut *)P.C;
     TAcc *Pp = (TAcc *)P.partial + (int64_t)split * P.M * P.N;
 #pragma unroll
@@ -212,7 +216,7 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmParams P) {
         }
     return;
   }
-  if (GENERAL) {
+  if (EPI == 1) {
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -222,6 +226,38 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmParams P) {
           const int64_t row = m0 + wm0 + i * 16 + Mfma<TAcc>::row(lane, v);
           const int64_t col = n0 + wn0 + j * 16 + r16;
           if (row < P.M && col < P.N) store_result<TOut, TAcc, sizeof(TIn) == 4>(P, row, col, acc[i][j][v]);
+        }
+  }
+  if (EPI == 2) {
+    TOut *Cp = (TOut *)P.C;
+    const TAcc alpha = (TAcc)P.alpha, beta = (TAcc)P.beta;
+    if (beta != (TAcc)0) {
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+          for (int v = 0; v < 4; ++v) {
+            const int64_t row = m0 + wm0 + i * 16 + Mfma<TAcc>::row(lane, v);
+            const int64_t col = n0 + wn0 + j * 16 + r16;
+            const TAcc old = (row < P.M && col < P.N) ? (TAcc)Cp[row * P.ldc + col] : (TAcc)0;
+            acc[i][j][v] = alpha * acc[i][j][v] + beta * old;
+          }
+    } else {
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) acc[i][j] *= alpha;
+    }
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+          const int64_t row = m0 + wm0 + i * 16 + Mfma<TAcc>::row(lane, v);
+          const int64_t col = n0 + wn0 + j * 16 + r16;
+          if (row < P.M && col < P.N) Cp[row * P.ldc + col] = (TOut)acc[i][j][v];
         }
   }
 }
@@ -336,14 +372,17 @@ struct GemmDispatch {
     Q.tiles_m = (int)ceil_div(P.M, BM);
     dim3 grid((unsigned)((int64_t)Q.tiles_n * Q.tiles_m * P.splits));
     constexpr int V = 16 / sizeof(TIn);
-    const bool general = P.splits == 1 && (P.alpha != 1.0 || P.beta != 0.0 || P.r1_v != nullptr ||
-                                           P.dead != nullptr || P.trans_c != 0);
+    const bool general = P.splits == 1 && (P.r1_v != nullptr || P.dead != nullptr || P.trans_c != 0);
+    const bool scaled = P.splits == 1 && !general && (P.alpha != 1.0 || P.beta != 0.0);
     if (general) {
-      if (vec) hipLaunchKernelGGL((gemm_kernel<TIn, TAcc, TOut, TA, BM, BN, WGM, WGN, V, true, BK>), grid, dim3(256), 0, s, Q);
-      else hipLaunchKernelGGL((gemm_kernel<TIn, TAcc, TOut, TA, BM, BN, WGM, WGN, 1, true, BK>), grid, dim3(256), 0, s, Q);
+      if (vec) hipLaunchKernelGGL((gemm_kernel<TIn, TAcc, TOut, TA, BM, BN, WGM, WGN, V, 1, BK>), grid, dim3(256), 0, s, Q);
+      else hipLaunchKernelGGL((gemm_kernel<TIn, TAcc, TOut, TA, BM, BN, WGM, WGN, 1, 1, BK>), grid, dim3(256), 0, s, Q);
+    } else if (scaled) {
+      if (vec) hipLaunchKernelGGL((gemm_kernel<TIn, TAcc, TOut, TA, BM, BN, WGM, WGN, V, 2, BK>), grid, dim3(256), 0, s, Q);
+      else hipLaunchKernelGGL((gemm_kernel<TIn, TAcc, TOut, TA, BM, BN, WGM, WGN, 1, 2, BK>), grid, dim3(256), 0, s, Q);
     } else {
-      if (vec) hipLaunchKernelGGL((gemm_kernel<TIn, TAcc, TOut, TA, BM, BN, WGM, WGN, V, false, BK>), grid, dim3(256), 0, s, Q);
-      else hipLaunchKernelGGL((gemm_kernel<TIn, TAcc, TOut, TA, BM, BN, WGM, WGN, 1, false, BK>), grid, dim3(256), 0, s, Q);
+      if (vec) hipLaunchKernelGGL((gemm_kernel<TIn, TAcc, TOut, TA, BM, BN, WGM, WGN, V, 0, BK>), grid, dim3(256), 0, s, Q);
+      else hipLaunchKernelGGL((gemm_kernel<TIn, TAcc, TOut, TA, BM, BN, WGM, WGN, 1, 0, BK>), grid, dim3(256), 0, s, Q);
     }
     return hipGetLastError();
   }
