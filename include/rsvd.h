@@ -123,6 +123,30 @@ int rsvd_run_centered(rsvd_ctx *ctx, void *stream, rsvd_dtype dtype, rsvd_job jo
                       void *S, void *U, int64_t ldu, void *Vt, int64_t ldvt,
                       void *workspace, size_t workspace_bytes, rsvd_info *info, void *mean);
 
+/*
+ * Many small problems at once (the paper's clustering application calls the
+ * solver on a great number of data blocks): `batch` matrices of one shape,
+ * problem b at A + b * stride_a elements, its results at S + b * stride_s,
+ * U + b * stride_u and Vt + b * stride_vt.  Every kernel launch of Algorithm 1
+ * covers the whole batch, so the single-workgroup steps (Cholesky, Jacobi) of
+ * different problems run side by side.  Problem b draws its sketch with
+ * seed + b; its results equal those of rsvd_run on that matrix with that seed
+ * up to the rounding of a different split of the long sums.
+ *   requires k + p within the single-workgroup kernels (128 for fp32, 96 for
+ *   fp64; RSVD_ERR_UNSUPPORTED otherwise), batch in 1 .. 65535, strides that
+ *   keep the problems apart, and a workspace of rsvd_workspace_bytes_batched().
+ *   info (host, may be NULL) describes the whole batch: the worst status, the
+ *   largest sweep count, the total of replaced columns.
+ */
+int rsvd_workspace_bytes_batched(rsvd_ctx *ctx, rsvd_dtype dtype, int batch, int64_t m, int64_t n,
+                                 int k, int p, int q, rsvd_job job, size_t *bytes);
+int rsvd_run_batched(rsvd_ctx *ctx, void *stream, rsvd_dtype dtype, rsvd_job job, int batch,
+                     int64_t m, int64_t n, const void *A, int64_t lda, int64_t stride_a,
+                     int k, int p, int q, uint64_t seed,
+                     void *S, int64_t stride_s, void *U, int64_t ldu, int64_t stride_u,
+                     void *Vt, int64_t ldvt, int64_t stride_vt,
+                     void *workspace, size_t workspace_bytes, rsvd_info *info);
+
 /* ---- stage entry points: each step of Algorithm 1 on its own, for per-stage
  * parity tests and timing.  They run the same kernels as rsvd_run. ---- */
 

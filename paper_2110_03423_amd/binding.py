@@ -40,6 +40,9 @@ PROTOTYPES = {
                  _VP, _VP, _I64, _VP, _I64, _VP, _SZ, C.POINTER(_Info)],
     "rsvd_run_centered": [_VP, _VP, _INT, _INT, _I64, _I64, _VP, _I64, _INT, _INT, _INT, _U64,
                           _VP, _VP, _I64, _VP, _I64, _VP, _SZ, C.POINTER(_Info), _VP],
+    "rsvd_workspace_bytes_batched": [_VP, _INT, _INT, _I64, _I64, _INT, _INT, _INT, _INT, C.POINTER(_SZ)],
+    "rsvd_run_batched": [_VP, _VP, _INT, _INT, _INT, _I64, _I64, _VP, _I64, _I64, _INT, _INT, _INT, _U64,
+                         _VP, _I64, _VP, _I64, _I64, _VP, _I64, _I64, _VP, _SZ, C.POINTER(_Info)],
     "rsvd_stage_sketch": [_VP, _VP, _INT, _U64, _U32, _I64, _I64, _VP, _I64],
     "rsvd_stage_philox_raw": [_VP, _VP, _U64, _U32, _U64, _I64, _VP],
     "rsvd_stage_gemm_an": [_VP, _VP, _INT, _I64, _I64, _I64, _VP, _I64, _VP, _I64, _VP, _I64, _VP, _SZ],
@@ -175,6 +178,33 @@ class Rsvd:
         else:
             rc = self.lib.rsvd_run_centered(*args, _ptr(_mean))
         self._check(rc)
+        return S, U, Vt, (info if want_info else None)
+
+    def rsvd_run_batched(self, A, k, p, q, seed=0, job=JOB_SUV, workspace=None, want_info=True, out=None):
+        """A: (batch, m, n) device tensor, each matrix row-major.  Returns (S (batch, k), U (batch, m, k),
+        Vt (batch, k, n), info of the whole batch).  Problem b uses seed + b."""
+        assert A.is_cuda and A.dim() == 3 and A.stride(2) == 1
+        batch, m, n = A.shape
+        dt = _dtype_code(A)
+        if workspace is None:
+            need = C.c_size_t()
+            self._check(self.lib.rsvd_workspace_bytes_batched(self.h, dt, batch, m, n, k, p, q, job, C.byref(need)))
+            if self._ws is None or self._ws.numel() < need.value:
+                self._ws = None
+                self._ws = self.torch.empty(need.value, dtype=self.torch.uint8, device=self.device)
+            workspace = self._ws
+        if out is None:
+            S = self._empty((batch, k), A)
+            U = self._empty((batch, m, k), A) if job == JOB_SUV else None
+            Vt = self._empty((batch, k, n), A) if job >= JOB_SV else None
+        else:
+            S, U, Vt = out
+        info = _Info()
+        self._check(self.lib.rsvd_run_batched(
+            self.h, self._stream(), dt, job, batch, m, n, _ptr(A), A.stride(1), A.stride(0), k, p, q, seed,
+            _ptr(S), S.stride(0), _ptr(U), U.stride(1) if U is not None else 0, U.stride(0) if U is not None else 0,
+            _ptr(Vt), Vt.stride(1) if Vt is not None else 0, Vt.stride(0) if Vt is not None else 0,
+            _ptr(workspace), workspace.numel(), C.byref(info) if want_info else None))
         return S, U, Vt, (info if want_info else None)
 
     # ---- stages

@@ -124,8 +124,15 @@ __global__ __launch_bounds__(NB * 64) void chol_mfma_kernel(const double *__rest
                                                             const double *__restrict__ g0, double tau,
                                                             TOut *__restrict__ Rinv, int64_t ldri,
                                                             double *__restrict__ R, int64_t ldr,
-                                                            int *__restrict__ dead, DevInfo *info) {
+                                                            int *__restrict__ dead, DevInfo *info, int64_t stride) {
   typedef CholLds<NB> L;
+  if (blockIdx.x != 0) {              // batched launch: one problem per workgroup, `stride` bytes apart
+    const int64_t off = (int64_t)blockIdx.x * stride;
+    G = reinterpret_cast<const double *>(reinterpret_cast<const char *>(G) + off);
+    Rinv = reinterpret_cast<TOut *>(reinterpret_cast<char *>(Rinv) + off);
+    if (R != nullptr) R = reinterpret_cast<double *>(reinterpret_cast<char *>(R) + off);
+    dead = reinterpret_cast<int *>(reinterpret_cast<char *>(dead) + off);
+  }
   constexpr int LP = L::LP, LD = L::LD, TLD = L::TLD, NT = NB * 64;
   extern __shared__ double smem[];
   double *Sm = smem;                       // LP x LD: finished rows of [R | Z]
@@ -283,7 +290,11 @@ __global__ void fill_zero_f64_kernel(double *__restrict__ p, int64_t n) {
 }
 
 __global__ void triu_product_kernel(int l, const double *__restrict__ R2, const double *__restrict__ R1,
-                                    double *__restrict__ Rb) {
+                                    double *__restrict__ Rb, int64_t stride) {
+  const int64_t off = (int64_t)blockIdx.y * stride;        // batched: bytes between problems
+  R2 = reinterpret_cast<const double *>(reinterpret_cast<const char *>(R2) + off);
+  R1 = reinterpret_cast<const double *>(reinterpret_cast<const char *>(R1) + off);
+  Rb = reinterpret_cast<double *>(reinterpret_cast<char *>(Rb) + off);
   const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (e >= (int64_t)l * l) return;
   const int i = (int)(e / l), j = (int)(e - (int64_t)i * l);
@@ -292,7 +303,8 @@ __global__ void triu_product_kernel(int l, const double *__restrict__ R2, const 
   Rb[e] = acc;
 }
 
-__global__ void zero_ints_kernel(int *p, int n) {
+__global__ void zero_ints_kernel(int *p, int n, int64_t stride) {
+  p = reinterpret_cast<int *>(reinterpret_cast<char *>(p) + (int64_t)blockIdx.y * stride);
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i < n) p[i] = 0;
 }
@@ -311,7 +323,7 @@ size_t chol_scratch_elems(const rsvd_ctx *ctx, int64_t l) {
 template <typename TOut>
 static hipError_t launch_block(hipStream_t s, const double *G, int64_t ldg, int n_parts, int64_t part_stride, int nb,
                                const double *g0, double tau, TOut *Rinv, int64_t ldri, double *R, int64_t ldr,
-                               int *dead, DevInfo *info) {
+                               int *dead, DevInfo *info, int batch = 1, int64_t stride = 0) {
   // one workgroup, one wavefront per 16-row block
 #define RSVD_CHOL_CASE(NBV)                                                                                         \
   do {                                                                                                              \
@@ -322,8 +334,8 @@ static hipError_t launch_block(hipStream_t s, const double *G, int64_t ldg, int 
       (void)hipGetLastError();                                                                                      \
       attr_set = true;                                                                                              \
     }                                                                                                               \
-    hipLaunchKernelGGL((chol_mfma_kernel<TOut, NBV>), dim3(1), dim3(NBV * 64), CholLds<NBV>::bytes, s, G, ldg,      \
-                       n_parts, part_stride, nb, g0, tau, Rinv, ldri, R, ldr, dead, info);                          \
+    hipLaunchKernelGGL((chol_mfma_kernel<TOut, NBV>), dim3(batch), dim3(NBV * 64), CholLds<NBV>::bytes, s, G, ldg,  \
+                       n_parts, part_stride, nb, g0, tau, Rinv, ldri, R, ldr, dead, info, stride);                  \
   } while (0)
   switch ((nb + 15) / 16) {
     case 1: RSVD_CHOL_CASE(1); break;
@@ -342,16 +354,18 @@ static hipError_t launch_block(hipStream_t s, const double *G, int64_t ldg, int 
 
 hipError_t chol_inverse_launch(rsvd_ctx *ctx, hipStream_t s, rsvd_dtype out_dtype, int64_t l, double *G,
                                int64_t ldg, int n_parts, int64_t part_stride, double tau, void *Rinv, double *R,
-                               int *dead, DevInfo *info, double *scratch) {
+                               int *dead, DevInfo *info, double *scratch, int batch, int64_t stride) {
   const int nbmax = chol_max_block(ctx);
+  if (batch < 1 || batch > 65535) return hipErrorInvalidValue;
   if (l <= nbmax) {
     ProfScope ps(ctx, s, PK_CHOL);
     if (out_dtype == RSVD_F32)
       return launch_block<float>(s, G, ldg, n_parts, part_stride, (int)l, nullptr, tau, (float *)Rinv, l, R, l, dead,
-                                 info);
+                                 info, batch, stride);
     return launch_block<double>(s, G, ldg, n_parts, part_stride, (int)l, nullptr, tau, (double *)Rinv, l, R, l, dead,
-                                info);
+                                info, batch, stride);
   }
+  if (batch != 1) return hipErrorNotSupported;       // the blocked path is not batched
   if (n_parts != 1) return hipErrorInvalidValue;     // the blocked path wants the reduced matrix
 
   // Blocked right-looking factorisation; diagonal blocks by the kernel above,
@@ -421,13 +435,16 @@ hipError_t chol_inverse_launch(rsvd_ctx *ctx, hipStream_t s, rsvd_dtype out_dtyp
   return hipGetLastError();
 }
 
-hipError_t triu_product_launch(hipStream_t s, int64_t l, const double *R2, const double *R1, double *Rb) {
-  hipLaunchKernelGGL(triu_product_kernel, dim3((unsigned)ceil_div(l * l, 256)), dim3(256), 0, s, (int)l, R2, R1, Rb);
+hipError_t triu_product_launch(hipStream_t s, int64_t l, const double *R2, const double *R1, double *Rb, int batch,
+                               int64_t stride) {
+  hipLaunchKernelGGL(triu_product_kernel, dim3((unsigned)ceil_div(l * l, 256), (unsigned)batch), dim3(256), 0, s,
+                     (int)l, R2, R1, Rb, stride);
   return hipGetLastError();
 }
 
-hipError_t zero_ints_launch(hipStream_t s, int *p, int n) {
-  hipLaunchKernelGGL(zero_ints_kernel, dim3((unsigned)ceil_div(n, 256)), dim3(256), 0, s, p, n);
+hipError_t zero_ints_launch(hipStream_t s, int *p, int n, int batch, int64_t stride) {
+  hipLaunchKernelGGL(zero_ints_kernel, dim3((unsigned)ceil_div(n, 256), (unsigned)batch), dim3(256), 0, s, p, n,
+                     stride);
   return hipGetLastError();
 }
 

@@ -95,6 +95,11 @@ struct GemmDesc {
   int skip_reduce = 0;
   int skip_reduce_max = 1 << 30;                        // ... only when there are at most this many partials
   int *splits_out = nullptr;
+  // Batched launch: `batch` equal-shaped problems, one per blockIdx.y; the pointers above are
+  // those of problem 0 and problem b adds b times the matching stride (in BYTES; 0 = shared).
+  int batch = 1;
+  int64_t stride_a = 0, stride_b = 0, stride_c = 0, stride_partial = 0, stride_dead = 0, stride_r1u = 0, stride_r1v = 0;
+  uint64_t seed_step = 0;               // problem b draws replacement columns with seed + b * seed_step
 };
 
 enum GemmKind { GEMM_F32 = 0, GEMM_F64 = 1, GEMM_F32_ACC64 = 2 };  // last: fp32 inputs, fp64 MFMA and output
@@ -104,8 +109,9 @@ size_t gemm_partial_bytes(const rsvd_ctx *ctx, GemmKind kind, int trans_a, int64
 hipError_t gemm_launch(rsvd_ctx *ctx, hipStream_t s, GemmKind kind, const GemmDesc &d);
 
 // ---------------------------------------------------------------- sketch
+// batch > 1: problem b (blockIdx.y) writes to out + b * stride_out bytes with seed + b.
 hipError_t sketch_launch(hipStream_t s, rsvd_dtype dtype, uint64_t seed, uint32_t stream_id,
-                         int64_t rows, int64_t cols, void *out, int64_t ld);
+                         int64_t rows, int64_t cols, void *out, int64_t ld, int batch = 1, int64_t stride_out = 0);
 hipError_t philox_raw_launch(hipStream_t s, uint64_t seed, uint32_t stream_id, uint64_t first_group,
                              int64_t n_groups, uint32_t *out);
 
@@ -122,12 +128,16 @@ int chol_max_block(const rsvd_ctx *ctx);
 size_t chol_scratch_elems(const rsvd_ctx *ctx, int64_t l);
 //   G may be given as n_parts matrices part_stride elements apart whose sum is the
 //   Gram matrix (unreduced split-K partials; single-block orders only).
+//   batch > 1 (single-block orders only): problem b = blockIdx.x adds b * stride bytes to G, Rinv, R,
+//   dead and info (stride 0 for info: one shared block).
 hipError_t chol_inverse_launch(rsvd_ctx *ctx, hipStream_t s, rsvd_dtype out_dtype, int64_t l,
                                double *G, int64_t ldg, int n_parts, int64_t part_stride, double tau,
-                               void *Rinv, double *R, int *dead, DevInfo *info, double *scratch);
+                               void *Rinv, double *R, int *dead, DevInfo *info, double *scratch,
+                               int batch = 1, int64_t stride = 0);
 // Rb = R2 * R1 for upper triangular fp64 l x l matrices (ld l).
-hipError_t triu_product_launch(hipStream_t s, int64_t l, const double *R2, const double *R1, double *Rb);
-hipError_t zero_ints_launch(hipStream_t s, int *p, int n);
+hipError_t triu_product_launch(hipStream_t s, int64_t l, const double *R2, const double *R1, double *Rb,
+                               int batch = 1, int64_t stride = 0);
+hipError_t zero_ints_launch(hipStream_t s, int *p, int n, int batch = 1, int64_t stride = 0);
 
 // ---------------------------------------------------------------- Jacobi
 // Largest order the single-workgroup LDS-resident Jacobi kernel handles.
@@ -135,8 +145,9 @@ int jacobi_max_lds_order(const rsvd_ctx *ctx, rsvd_dtype dtype);
 size_t jacobi_scratch_bytes(const rsvd_ctx *ctx, rsvd_dtype dtype, int64_t l);
 // One-sided Jacobi SVD  M = X diag(sigma) W^T  of the l x l row-major matrix M
 // (ld l; fp64 when m_is_f64 else `dtype`).  Outputs in `dtype`, sigma descending.
+// batch > 1 (LDS-resident orders only): problem b = blockIdx.x adds b * stride bytes to M, sigma, X, W.
 hipError_t jacobi_launch(rsvd_ctx *ctx, hipStream_t s, rsvd_dtype dtype, int64_t l,
                          const void *M, int m_is_f64, void *sigma, void *X, void *W,
-                         DevInfo *info, void *scratch, size_t scratch_bytes);
+                         DevInfo *info, void *scratch, size_t scratch_bytes, int batch = 1, int64_t stride = 0);
 
 }  // namespace rsvd

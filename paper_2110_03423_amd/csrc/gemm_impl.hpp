@@ -37,7 +37,27 @@ struct GemmParams {
   const void *r1_u; const void *r1_v; double r1_alpha;
   const int *dead;
   uint64_t seed; uint32_t refill_stream; double refill_scale; int64_t refill_ld;
+  // batched launch (blockIdx.y = problem): byte strides of the pointers above, seed step
+  int64_t stride_a, stride_b, stride_c, stride_partial, stride_dead, stride_r1u, stride_r1v;
+  uint64_t seed_step;
 };
+
+// The parameters of problem blockIdx.y of a batched launch.
+__device__ __forceinline__ GemmParams select_problem(const GemmParams &P0) {
+  GemmParams P = P0;
+  const int64_t b = (int64_t)blockIdx.y;
+  if (b != 0) {
+    P.A = (const char *)P.A + b * P.stride_a;
+    P.B = (const char *)P.B + b * P.stride_b;
+    P.C = (char *)P.C + b * P.stride_c;
+    if (P.partial != nullptr) P.partial = (char *)P.partial + b * P.stride_partial;
+    if (P.dead != nullptr) P.dead = (const int *)((const char *)P.dead + b * P.stride_dead);
+    if (P.r1_u != nullptr) P.r1_u = (const char *)P.r1_u + b * P.stride_r1u;
+    if (P.r1_v != nullptr) P.r1_v = (const char *)P.r1_v + b * P.stride_r1v;
+    P.seed += (uint64_t)b * P.seed_step;
+  }
+  return P;
+}
 
 // Final store of one element of C, shared by the GEMM and the split-K reduction.
 template <typename TOut, typename TAcc, bool F32STREAM>
@@ -118,7 +138,8 @@ struct TileStage {
 // accumulator element and the products with A never need it.
 template <typename TIn, typename TAcc, typename TOut, bool TA, int BM, int BN, int WGM, int WGN, int VEC, int EPI,
           int BK = 32>
-__global__ __launch_bounds__(256) void gemm_kernel(const GemmParams P) {
+__global__ __launch_bounds__(256) void gemm_kernel(const GemmParams P0) {
+  const GemmParams P = select_problem(P0);
   static_assert(WGM * WGN == 4, "four wavefronts per workgroup");
   constexpr int WM = BM / WGM, WN = BN / WGN;
   static_assert(WM % 16 == 0 && WN % 16 == 0, "wave tile must be made of 16x16 blocks");
@@ -263,7 +284,8 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmParams P) {
 }
 
 template <typename TIn, typename TAcc, typename TOut>
-__global__ __launch_bounds__(256) void splitk_reduce_kernel(const GemmParams P) {
+__global__ __launch_bounds__(256) void splitk_reduce_kernel(const GemmParams P0) {
+  const GemmParams P = select_problem(P0);
   const int64_t total = P.M * P.N;
   for (int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; e < total;
        e += (int64_t)gridDim.x * blockDim.x) {
@@ -330,7 +352,7 @@ struct SplitChoice {
 
 // Split-K factor.
 inline SplitChoice choose_split(const rsvd_ctx *ctx, const TileChoice &t, int64_t M, int64_t N, int64_t K,
-                                int force, bool upper = false) {
+                                int force, bool upper = false, int batch = 1) {
   int64_t tiles = ceil_div(M, t.bm) * ceil_div(N, t.bn);
   if (upper) {                     // only tiles that reach the diagonal or lie above it do work
     tiles = 0;
@@ -348,6 +370,7 @@ inline SplitChoice choose_split(const rsvd_ctx *ctx, const TileChoice &t, int64_
     // that nearly fills the chip is left alone.  Every split pays a prologue and a tile-sized
     // partial store: at least 4 k-tiles per split for the 64-row tiles, 8 for the larger ones.
     const int64_t want = 4 * (int64_t)ctx->cu_count;
+    tiles *= batch;                  // a batch fills the chip with fewer splits per problem
     if (tiles < want) s = (want + tiles / 2) / tiles;
     const int64_t min_k = (t.bm * t.bn > 64 * 128) ? 8 : 4;
     const int64_t max_by_k = ktiles / min_k > 0 ? ktiles / min_k : 1;
@@ -366,11 +389,11 @@ inline SplitChoice choose_split(const rsvd_ctx *ctx, const TileChoice &t, int64_
 template <typename TIn, typename TAcc, typename TOut>
 struct GemmDispatch {
   template <bool TA, int BM, int BN, int WGM, int WGN, int BK = 32>
-  static hipError_t run(hipStream_t s, const GemmParams &P, bool vec) {
+  static hipError_t run(hipStream_t s, const GemmParams &P, bool vec, int batch) {
     GemmParams Q = P;
     Q.tiles_n = (int)ceil_div(P.N, BN);
     Q.tiles_m = (int)ceil_div(P.M, BM);
-    dim3 grid((unsigned)((int64_t)Q.tiles_n * Q.tiles_m * P.splits));
+    dim3 grid((unsigned)((int64_t)Q.tiles_n * Q.tiles_m * P.splits), (unsigned)batch);
     constexpr int V = 16 / sizeof(TIn);
     const bool general = P.splits == 1 && (P.r1_v != nullptr || P.dead != nullptr || P.trans_c != 0);
     const bool scaled = P.splits == 1 && !general && (P.alpha != 1.0 || P.beta != 0.0);
@@ -388,23 +411,23 @@ struct GemmDispatch {
   }
 
   template <bool TA>
-  static hipError_t by_tile(hipStream_t s, const GemmParams &P, const TileChoice &t, bool vec) {
+  static hipError_t by_tile(hipStream_t s, const GemmParams &P, const TileChoice &t, bool vec, int batch) {
     if (t.bm == 64) {
       switch (t.bn) {
         // (64-deep k-tiles for these HBM-bound shapes measured no better than 32)
-        case 16:  return run<TA, 64, 16, 4, 1>(s, P, vec);
-        case 32:  return run<TA, 64, 32, 4, 1>(s, P, vec);
-        case 48:  return run<TA, 64, 48, 4, 1>(s, P, vec);
-        case 64:  return run<TA, 64, 64, 4, 1>(s, P, vec);
-        case 80:  return run<TA, 64, 80, 4, 1>(s, P, vec);
-        case 96:  return run<TA, 64, 96, 4, 1>(s, P, vec);
-        case 112: return run<TA, 64, 112, 4, 1>(s, P, vec);
-        case 128: return run<TA, 64, 128, 4, 1>(s, P, vec);
+        case 16:  return run<TA, 64, 16, 4, 1>(s, P, vec, batch);
+        case 32:  return run<TA, 64, 32, 4, 1>(s, P, vec, batch);
+        case 48:  return run<TA, 64, 48, 4, 1>(s, P, vec, batch);
+        case 64:  return run<TA, 64, 64, 4, 1>(s, P, vec, batch);
+        case 80:  return run<TA, 64, 80, 4, 1>(s, P, vec, batch);
+        case 96:  return run<TA, 64, 96, 4, 1>(s, P, vec, batch);
+        case 112: return run<TA, 64, 112, 4, 1>(s, P, vec, batch);
+        case 128: return run<TA, 64, 128, 4, 1>(s, P, vec, batch);
       }
     } else {
-      if (t.bn == 96)  return run<TA, 128, 96, 2, 2>(s, P, vec);
-      if (t.bn == 128) return run<TA, 128, 128, 2, 2>(s, P, vec);
-      if (t.bn == 192 && sizeof(TAcc) == 4) return run<TA, 128, 192, 2, 2>(s, P, vec);
+      if (t.bn == 96)  return run<TA, 128, 96, 2, 2>(s, P, vec, batch);
+      if (t.bn == 128) return run<TA, 128, 128, 2, 2>(s, P, vec, batch);
+      if (t.bn == 192 && sizeof(TAcc) == 4) return run<TA, 128, 192, 2, 2>(s, P, vec, batch);
     }
     return hipErrorInvalidValue;
   }
@@ -422,7 +445,8 @@ struct GemmDispatch {
   static hipError_t launch(rsvd_ctx *ctx, hipStream_t s, const GemmDesc &d) {
     if (d.M <= 0 || d.N <= 0) return hipSuccess;
     const TileChoice t = choose_tile(d.M, d.N, d.K, sizeof(TAcc), d.trans_a != 0);
-    SplitChoice c = choose_split(ctx, t, d.M, d.N, d.K, d.force_splits, d.upper_only != 0);
+    if (d.batch < 1 || d.batch > 65535) return hipErrorInvalidValue;
+    SplitChoice c = choose_split(ctx, t, d.M, d.N, d.K, d.force_splits, d.upper_only != 0, d.batch);
     if (c.splits > 1) {
       const size_t need = (size_t)c.splits * (size_t)d.M * (size_t)d.N * sizeof(TAcc);
       if (d.partial == nullptr || d.partial_bytes < need) return hipErrorInvalidValue;
@@ -437,15 +461,18 @@ struct GemmDispatch {
     P.r1_u = d.r1_u; P.r1_v = d.r1_v; P.r1_alpha = d.r1_alpha;
     P.dead = d.dead; P.seed = d.seed; P.refill_stream = d.refill_stream;
     P.refill_scale = d.refill_scale; P.refill_ld = d.refill_ld;
+    P.stride_a = d.stride_a; P.stride_b = d.stride_b; P.stride_c = d.stride_c; P.stride_partial = d.stride_partial;
+    P.stride_dead = d.stride_dead; P.stride_r1u = d.stride_r1u; P.stride_r1v = d.stride_r1v; P.seed_step = d.seed_step;
     // 16-byte vector loads need aligned bases, leading dimensions and extents.
     constexpr int V = 16 / sizeof(TIn);
     const int64_t a_contig = d.trans_a ? d.M : d.K;
     const bool vec = ((uintptr_t)d.A % 16 == 0) && ((uintptr_t)d.B % 16 == 0) && d.lda % V == 0 &&
-                     d.ldb % V == 0 && a_contig % V == 0 && d.N % V == 0;
+                     d.ldb % V == 0 && a_contig % V == 0 && d.N % V == 0 &&
+                     (d.batch == 1 || (d.stride_a % 16 == 0 && d.stride_b % 16 == 0));
     hipError_t e;
     {
       ProfScope ps(ctx, s, d.prof_kind);
-      e = d.trans_a ? by_tile<true>(s, P, t, vec) : by_tile<false>(s, P, t, vec);
+      e = d.trans_a ? by_tile<true>(s, P, t, vec, d.batch) : by_tile<false>(s, P, t, vec, d.batch);
     }
     if (e != hipSuccess) return e;
     if (d.splits_out != nullptr) *d.splits_out = c.splits;
@@ -453,7 +480,8 @@ struct GemmDispatch {
       ProfScope ps(ctx, s, d.prof_kind + 1);
       int64_t blocks = ceil_div(d.M * d.N, 256);
       if (blocks > 8192) blocks = 8192;
-      hipLaunchKernelGGL((splitk_reduce_kernel<TIn, TAcc, TOut>), dim3((unsigned)blocks), dim3(256), 0, s, P);
+      hipLaunchKernelGGL((splitk_reduce_kernel<TIn, TAcc, TOut>), dim3((unsigned)blocks, (unsigned)d.batch), dim3(256),
+                         0, s, P);
       e = hipGetLastError();
     }
     return e;

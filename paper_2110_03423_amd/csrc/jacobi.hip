@@ -200,8 +200,16 @@ __host__ __device__ inline int jacobi_ldm(int l, int G, int elem_size) {
 
 template <typename T, typename TIn, int RPL, int G>
 __global__ __launch_bounds__(64 * G) void jacobi_lds_kernel(const TIn *__restrict__ M, int l, T *__restrict__ sigma,
-                                                         T *__restrict__ X, T *__restrict__ W, DevInfo *info) {
+                                                         T *__restrict__ X, T *__restrict__ W, DevInfo *info,
+                                                         int64_t stride) {
   extern __shared__ __attribute__((aligned(16))) double lds_raw[];
+  if (blockIdx.x != 0) {              // batched launch: one problem per workgroup, `stride` bytes apart
+    const int64_t off = (int64_t)blockIdx.x * stride;
+    M = reinterpret_cast<const TIn *>(reinterpret_cast<const char *>(M) + off);
+    sigma = reinterpret_cast<T *>(reinterpret_cast<char *>(sigma) + off);
+    X = reinterpret_cast<T *>(reinterpret_cast<char *>(X) + off);
+    W = reinterpret_cast<T *>(reinterpret_cast<char *>(W) + off);
+  }
   const int ldm = jacobi_ldm(l, G, (int)sizeof(T));
   T *Mc = reinterpret_cast<T *>(lds_raw);
   T *Jc = Mc + (size_t)l * ldm;
@@ -810,7 +818,7 @@ static hipError_t jacobi_block_launch(rsvd_ctx *ctx, hipStream_t s, rsvd_dtype d
 
 template <typename T, typename TIn, int RPL, int G>
 static hipError_t launch_lds(hipStream_t s, int nt, size_t lds, const void *M, int l, void *sigma, void *X, void *W,
-                             DevInfo *info) {
+                             DevInfo *info, int batch, int64_t stride) {
   static bool attr_set = false;
   if (!attr_set) {
     (void)hipFuncSetAttribute(reinterpret_cast<const void *>(&jacobi_lds_kernel<T, TIn, RPL, G>),
@@ -818,43 +826,45 @@ static hipError_t launch_lds(hipStream_t s, int nt, size_t lds, const void *M, i
     (void)hipGetLastError();
     attr_set = true;
   }
-  hipLaunchKernelGGL((jacobi_lds_kernel<T, TIn, RPL, G>), dim3(1), dim3(nt), lds, s, (const TIn *)M, l, (T *)sigma,
-                     (T *)X, (T *)W, info);
+  hipLaunchKernelGGL((jacobi_lds_kernel<T, TIn, RPL, G>), dim3(batch), dim3(nt), lds, s, (const TIn *)M, l,
+                     (T *)sigma, (T *)X, (T *)W, info, stride);
   return hipGetLastError();
 }
 
 // rows per lane = padded rows / G
 template <typename T, typename TIn>
 static hipError_t launch_lds_g(hipStream_t s, int nt, int G, int rpl, size_t lds, const void *M, int l, void *sigma,
-                               void *X, void *W, DevInfo *info) {
+                               void *X, void *W, DevInfo *info, int batch, int64_t stride) {
   if (G == 8) {
     switch (rpl) {
-      case 2: return launch_lds<T, TIn, 2, 8>(s, nt, lds, M, l, sigma, X, W, info);
-      case 4: return launch_lds<T, TIn, 4, 8>(s, nt, lds, M, l, sigma, X, W, info);
-      case 6: return launch_lds<T, TIn, 6, 8>(s, nt, lds, M, l, sigma, X, W, info);
-      case 8: return launch_lds<T, TIn, 8, 8>(s, nt, lds, M, l, sigma, X, W, info);
-      case 10: return launch_lds<T, TIn, 10, 8>(s, nt, lds, M, l, sigma, X, W, info);
-      case 12: return launch_lds<T, TIn, 12, 8>(s, nt, lds, M, l, sigma, X, W, info);
-      case 14: return launch_lds<T, TIn, 14, 8>(s, nt, lds, M, l, sigma, X, W, info);
-      default: return launch_lds<T, TIn, 16, 8>(s, nt, lds, M, l, sigma, X, W, info);
+      case 2: return launch_lds<T, TIn, 2, 8>(s, nt, lds, M, l, sigma, X, W, info, batch, stride);
+      case 4: return launch_lds<T, TIn, 4, 8>(s, nt, lds, M, l, sigma, X, W, info, batch, stride);
+      case 6: return launch_lds<T, TIn, 6, 8>(s, nt, lds, M, l, sigma, X, W, info, batch, stride);
+      case 8: return launch_lds<T, TIn, 8, 8>(s, nt, lds, M, l, sigma, X, W, info, batch, stride);
+      case 10: return launch_lds<T, TIn, 10, 8>(s, nt, lds, M, l, sigma, X, W, info, batch, stride);
+      case 12: return launch_lds<T, TIn, 12, 8>(s, nt, lds, M, l, sigma, X, W, info, batch, stride);
+      case 14: return launch_lds<T, TIn, 14, 8>(s, nt, lds, M, l, sigma, X, W, info, batch, stride);
+      default: return launch_lds<T, TIn, 16, 8>(s, nt, lds, M, l, sigma, X, W, info, batch, stride);
     }
   }
   switch (rpl) {
-    case 4: return launch_lds<T, TIn, 4, 4>(s, nt, lds, M, l, sigma, X, W, info);
-    case 8: return launch_lds<T, TIn, 8, 4>(s, nt, lds, M, l, sigma, X, W, info);
-    case 12: return launch_lds<T, TIn, 12, 4>(s, nt, lds, M, l, sigma, X, W, info);
-    case 16: return launch_lds<T, TIn, 16, 4>(s, nt, lds, M, l, sigma, X, W, info);
-    case 20: return launch_lds<T, TIn, 20, 4>(s, nt, lds, M, l, sigma, X, W, info);
-    case 24: return launch_lds<T, TIn, 24, 4>(s, nt, lds, M, l, sigma, X, W, info);
-    case 28: return launch_lds<T, TIn, 28, 4>(s, nt, lds, M, l, sigma, X, W, info);
-    default: return launch_lds<T, TIn, 32, 4>(s, nt, lds, M, l, sigma, X, W, info);
+    case 4: return launch_lds<T, TIn, 4, 4>(s, nt, lds, M, l, sigma, X, W, info, batch, stride);
+    case 8: return launch_lds<T, TIn, 8, 4>(s, nt, lds, M, l, sigma, X, W, info, batch, stride);
+    case 12: return launch_lds<T, TIn, 12, 4>(s, nt, lds, M, l, sigma, X, W, info, batch, stride);
+    case 16: return launch_lds<T, TIn, 16, 4>(s, nt, lds, M, l, sigma, X, W, info, batch, stride);
+    case 20: return launch_lds<T, TIn, 20, 4>(s, nt, lds, M, l, sigma, X, W, info, batch, stride);
+    case 24: return launch_lds<T, TIn, 24, 4>(s, nt, lds, M, l, sigma, X, W, info, batch, stride);
+    case 28: return launch_lds<T, TIn, 28, 4>(s, nt, lds, M, l, sigma, X, W, info, batch, stride);
+    default: return launch_lds<T, TIn, 32, 4>(s, nt, lds, M, l, sigma, X, W, info, batch, stride);
   }
 }
 
 hipError_t jacobi_launch(rsvd_ctx *ctx, hipStream_t s, rsvd_dtype dtype, int64_t l, const void *M,
                          int m_is_f64, void *sigma, void *X, void *W, DevInfo *info, void *scratch,
-                         size_t scratch_bytes) {
+                         size_t scratch_bytes, int batch, int64_t stride) {
+  if (batch < 1 || batch > 65535) return hipErrorInvalidValue;
   if (l > jacobi_max_lds_order(ctx, dtype)) {
+    if (batch != 1) return hipErrorNotSupported;       // the block path is not batched
     // block path: needs the fp64 input (the triangular factor) and its scratch
     const size_t need = jacobi_scratch_bytes(ctx, dtype, l);
     if (need == 0 || scratch == nullptr || scratch_bytes < need || !m_is_f64) return hipErrorNotSupported;
@@ -873,10 +883,10 @@ hipError_t jacobi_launch(rsvd_ctx *ctx, hipStream_t s, rsvd_dtype dtype, int64_t
   const size_t lds = jacobi_lds_bytes(dtype, l);
   ProfScope ps(ctx, s, PK_JACOBI);
   if (dtype == RSVD_F32) {
-    if (m_is_f64) return launch_lds_g<float, double>(s, nt, G, g, lds, M, (int)l, sigma, X, W, info);
-    return launch_lds_g<float, float>(s, nt, G, g, lds, M, (int)l, sigma, X, W, info);
+    if (m_is_f64) return launch_lds_g<float, double>(s, nt, G, g, lds, M, (int)l, sigma, X, W, info, batch, stride);
+    return launch_lds_g<float, float>(s, nt, G, g, lds, M, (int)l, sigma, X, W, info, batch, stride);
   }
-  return launch_lds_g<double, double>(s, nt, G, g, lds, M, (int)l, sigma, X, W, info);
+  return launch_lds_g<double, double>(s, nt, G, g, lds, M, (int)l, sigma, X, W, info, batch, stride);
 }
 
 }  // namespace rsvd

@@ -35,7 +35,10 @@ hipError_t gemm_launch(rsvd_ctx *ctx, hipStream_t s, GemmKind kind, const GemmDe
 }
 
 template <typename T>
-__global__ void copy_kernel(const T *__restrict__ src, T *__restrict__ dst, int64_t n) {
+__global__ void copy_kernel(const T *__restrict__ src, T *__restrict__ dst, int64_t n, int64_t stride_src,
+                            int64_t stride_dst) {
+  src = reinterpret_cast<const T *>(reinterpret_cast<const char *>(src) + (int64_t)blockIdx.y * stride_src);
+  dst = reinterpret_cast<T *>(reinterpret_cast<char *>(dst) + (int64_t)blockIdx.y * stride_dst);
   for (int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; e < n; e += (int64_t)gridDim.x * blockDim.x)
     dst[e] = src[e];
 }
@@ -109,14 +112,19 @@ static hipError_t colsum_launch(hipStream_t s, rsvd_dtype dtype, const void *X, 
   return hipGetLastError();
 }
 
-static hipError_t copy_launch(hipStream_t s, rsvd_dtype dtype, const void *src, void *dst, int64_t n) {
+// batch > 1: problem b copies from src + b * stride_src to dst + b * stride_dst (bytes)
+static hipError_t copy_launch(hipStream_t s, rsvd_dtype dtype, const void *src, void *dst, int64_t n, int batch = 1,
+                              int64_t stride_src = 0, int64_t stride_dst = 0) {
   if (n <= 0) return hipSuccess;
   int64_t blocks = ceil_div(n, 256);
   if (blocks > 4096) blocks = 4096;
+  const dim3 grid((unsigned)blocks, (unsigned)batch);
   if (dtype == RSVD_F32)
-    hipLaunchKernelGGL(copy_kernel<float>, dim3((unsigned)blocks), dim3(256), 0, s, (const float *)src, (float *)dst, n);
+    hipLaunchKernelGGL(copy_kernel<float>, grid, dim3(256), 0, s, (const float *)src, (float *)dst, n, stride_src,
+                       stride_dst);
   else
-    hipLaunchKernelGGL(copy_kernel<double>, dim3((unsigned)blocks), dim3(256), 0, s, (const double *)src, (double *)dst, n);
+    hipLaunchKernelGGL(copy_kernel<double>, grid, dim3(256), 0, s, (const double *)src, (double *)dst, n, stride_src,
+                       stride_dst);
   return hipGetLastError();
 }
 
@@ -186,6 +194,8 @@ static Layout make_layout(const rsvd_ctx *ctx, rsvd_dtype dtype, int64_t m, int6
 struct Ws {
   char *base;
   Layout L;
+  int batch = 1;           // equal-shaped problems handled by every launch
+  int64_t stride = 0;      // bytes between the workspaces of consecutive problems (every buffer of L)
   template <typename P> P *at(size_t off) const { return reinterpret_cast<P *>(base + off); }
 };
 
@@ -225,6 +235,7 @@ static int orthonormalize(rsvd_ctx *ctx, hipStream_t s, rsvd_dtype dtype, const 
     g.C = w.at<double>(L.G); g.ldc = l;
     g.partial = w.at<void>(L.partial); g.partial_bytes = L.partial_bytes;
     g.prof_kind = PK_GRAM;
+    g.batch = w.batch; g.stride_a = g.stride_b = g.stride_c = g.stride_partial = w.stride;
     g.upper_only = (l > chol_max_block(ctx)) ? 1 : 0;   // the blocked factorisation reads the upper triangle only
     // small orders: the Cholesky kernel adds the split-K partials itself
     int splits = 1;
@@ -236,7 +247,7 @@ static int orthonormalize(rsvd_ctx *ctx, hipStream_t s, rsvd_dtype dtype, const 
     const bool parts = g.skip_reduce && splits > 1 && splits <= g.skip_reduce_max;
     RSVD_TRY(chol_inverse_launch(ctx, s, dtype, l, parts ? w.at<double>(L.partial) : w.at<double>(L.G), l,
                                  parts ? splits : 1, l * l, tau, w.at<void>(L.Rinv), R, w.at<int>(L.dead),
-                                 w.at<DevInfo>(L.info), w.at<double>(L.chol_scratch)),
+                                 w.at<DevInfo>(L.info), w.at<double>(L.chol_scratch), w.batch, w.stride),
              "cholesky");
     GemmDesc a;
     a.M = rows; a.N = l; a.K = l;
@@ -245,6 +256,7 @@ static int orthonormalize(rsvd_ctx *ctx, hipStream_t s, rsvd_dtype dtype, const 
     a.dead = w.at<int>(L.dead); a.seed = seed; a.refill_stream = refill_stream + (uint32_t)round;
     a.refill_scale = 1.0 / sqrt((double)rows); a.refill_ld = l;
     a.force_splits = 1;
+    a.batch = w.batch; a.stride_a = a.stride_b = a.stride_c = a.stride_dead = w.stride; a.seed_step = 1;
     a.prof_kind = PK_APPLY;
     RSVD_TRY(gemm_launch(ctx, s, kind, a), "apply R^-1");
     void *tp = src; src = dst; dst = tp;
@@ -252,7 +264,7 @@ static int orthonormalize(rsvd_ctx *ctx, hipStream_t s, rsvd_dtype dtype, const 
   }
   if (Rout) {
     ProfScope ps(ctx, s, PK_SMALL);
-    RSVD_TRY(triu_product_launch(s, l, w.at<double>(L.R2), w.at<double>(L.R1), Rout), "R product");
+    RSVD_TRY(triu_product_launch(s, l, w.at<double>(L.R2), w.at<double>(L.R1), Rout, w.batch, w.stride), "R product");
   }
   return 0;
 }
@@ -260,8 +272,14 @@ static int orthonormalize(rsvd_ctx *ctx, hipStream_t s, rsvd_dtype dtype, const 
 static int product(rsvd_ctx *ctx, hipStream_t s, rsvd_dtype dtype, const Ws &w, int trans_a, int64_t M, int64_t N,
                    int64_t K, const void *A, int64_t lda, const void *B, int64_t ldb, void *C, int64_t ldc,
                    int trans_c, bool allow_split, int prof_kind, double alpha = 1.0, const void *r1_u = nullptr,
-                   const void *r1_v = nullptr, double r1_alpha = 0.0) {
+                   const void *r1_v = nullptr, double r1_alpha = 0.0, int64_t stride_a = -1, int64_t stride_c = -1) {
+  // batched: B is always a workspace buffer; A and C are too unless the caller names their strides (bytes)
   GemmDesc d;
+  d.batch = w.batch;
+  d.stride_a = stride_a >= 0 ? stride_a : w.stride;
+  d.stride_b = w.stride;
+  d.stride_c = stride_c >= 0 ? stride_c : w.stride;
+  d.stride_partial = w.stride;
   d.prof_kind = prof_kind;
   d.alpha = alpha; d.r1_u = r1_u; d.r1_v = r1_v; d.r1_alpha = r1_alpha;
   d.trans_a = trans_a; d.trans_c = trans_c; d.M = M; d.N = N; d.K = K;
@@ -281,7 +299,7 @@ static int small_svd(rsvd_ctx *ctx, hipStream_t s, rsvd_dtype dtype, const Ws &w
   if (rc) return rc;
   hipError_t e = jacobi_launch(ctx, s, dtype, l, w.at<void>(L.Rb), 1, w.at<void>(L.sigma), w.at<void>(L.Xj),
                                w.at<void>(L.Wj), w.at<DevInfo>(L.info), w.at<void>(L.jac_scratch),
-                               L.jac_scratch_bytes);
+                               L.jac_scratch_bytes, w.batch, w.stride);
   if (e == hipErrorNotSupported) return RSVD_ERR_UNSUPPORTED;
   RSVD_TRY(e, "jacobi");
   return 0;
@@ -398,10 +416,15 @@ int rsvd_workspace_bytes(rsvd_ctx *ctx, rsvd_dtype dtype, int64_t m, int64_t n, 
 // Algorithm 1 on A, or (center != 0) on A - 1 mu^T with mu the column means of A, without forming that matrix:
 //   (A - 1 mu^T) X = A X - 1 (mu^T X),   (A - 1 mu^T)^T Q = A^T Q - mu (1^T Q),
 // the rank-one terms being added in the epilogue of the same product kernels.
+// batch > 1: `batch` problems of the same shape, problem b at A + b * stride_a elements (likewise S, U, Vt), sketch
+// seed + b; every kernel launch covers the whole batch.  Needs l within the single-workgroup Cholesky and Jacobi
+// kernels and no centring; the diagnostics are those of the whole batch (worst status, most sweeps, all replaced
+// columns).
 static int run_impl(rsvd_ctx *ctx, void *stream, rsvd_dtype dtype, rsvd_job job, int64_t m, int64_t n, const void *A,
                     int64_t lda, int k, int p, int q, uint64_t seed, void *S, void *U, int64_t ldu, void *Vt,
                     int64_t ldvt, void *workspace, size_t workspace_bytes, rsvd_info *info, int center,
-                    void *mean_out) {
+                    void *mean_out, int batch = 1, int64_t stride_a = 0, int64_t stride_s = 0, int64_t stride_u = 0,
+                    int64_t stride_vt = 0) {
   if (ctx == nullptr) return -1;
   if (!valid_dtype(dtype)) return -3;
   if (job < RSVD_JOB_S || job > RSVD_JOB_SUV) return -4;
@@ -418,12 +441,17 @@ static int run_impl(rsvd_ctx *ctx, void *stream, rsvd_dtype dtype, rsvd_job job,
   if (job >= RSVD_JOB_SV && Vt == nullptr) return -16;
   if (job >= RSVD_JOB_SV && ldvt < n) return -17;
   const int64_t l = (int64_t)k + p;
+  const int64_t es = (int64_t)dtype_size(dtype);
   Ws w;
   w.L = make_layout(ctx, dtype, m, n, l);
   w.base = (char *)workspace;
+  w.batch = batch;
+  w.stride = (int64_t)w.L.total;             // a multiple of 256
   if (workspace == nullptr || ((uintptr_t)workspace & 255) != 0) return -18;
-  if (workspace_bytes < w.L.total) return -19;
+  if (workspace_bytes < w.L.total * (size_t)batch) return -19;
   if (l > jacobi_max_lds_order(ctx, dtype) && jacobi_scratch_bytes(ctx, dtype, l) == 0) return RSVD_ERR_UNSUPPORTED;
+  if (batch > 1 && (l > jacobi_max_lds_order(ctx, dtype) || l > chol_max_block(ctx) || center))
+    return RSVD_ERR_UNSUPPORTED;
   hipStream_t s = (hipStream_t)stream;
   const Layout &L = w.L;
   void *bM0 = w.at<void>(L.bufM[0]), *bM1 = w.at<void>(L.bufM[1]);
@@ -441,7 +469,9 @@ static int run_impl(rsvd_ctx *ctx, void *stream, rsvd_dtype dtype, rsvd_job job,
   }
   // products with the (optionally centred) matrix; X is n x l for A X, m x l for A^T X
   auto times_a = [&](const void *X, void *Y) -> int {
-    if (!center) return product(ctx, s, dtype, w, 0, m, l, n, A, lda, X, l, Y, l, 0, true, PK_GEMM_AX);
+    if (!center)
+      return product(ctx, s, dtype, w, 0, m, l, n, A, lda, X, l, Y, l, 0, true, PK_GEMM_AX, 1.0, nullptr, nullptr, 0.0,
+                     stride_a * es);
     {
       ProfScope ps(ctx, s, PK_SMALL);                                                                 // X^T mu
       RSVD_TRY(colsum_launch(s, dtype, X, l, n, l, mean, 1.0, shift, part, L.partial_bytes), "shift");
@@ -449,7 +479,9 @@ static int run_impl(rsvd_ctx *ctx, void *stream, rsvd_dtype dtype, rsvd_job job,
     return product(ctx, s, dtype, w, 0, m, l, n, A, lda, X, l, Y, l, 0, true, PK_GEMM_AX, 1.0, nullptr, shift, -1.0);
   };
   auto times_at = [&](const void *X, void *Z) -> int {
-    if (!center) return product(ctx, s, dtype, w, 1, n, l, m, A, lda, X, l, Z, l, 0, true, PK_GEMM_ATX);
+    if (!center)
+      return product(ctx, s, dtype, w, 1, n, l, m, A, lda, X, l, Z, l, 0, true, PK_GEMM_ATX, 1.0, nullptr, nullptr, 0.0,
+                     stride_a * es);
     {
       ProfScope ps(ctx, s, PK_SMALL);                                                                 // X^T 1
       RSVD_TRY(colsum_launch(s, dtype, X, l, m, l, nullptr, 1.0, shift, part, L.partial_bytes), "shift");
@@ -459,7 +491,7 @@ static int run_impl(rsvd_ctx *ctx, void *stream, rsvd_dtype dtype, rsvd_job job,
   // step 1
   {
     ProfScope ps(ctx, s, PK_SKETCH);
-    RSVD_TRY(sketch_launch(s, dtype, seed, 0u, n, l, bN0, l), "sketch");
+    RSVD_TRY(sketch_launch(s, dtype, seed, 0u, n, l, bN0, l, batch, w.stride), "sketch");
   }
   // step 2: Y = A Omega, then q rounds of Z = A^T Q, Y = A Z.  Every product is
   // re-orthonormalised; all but the last with a single CholeskyQR round (result in
@@ -486,14 +518,18 @@ static int run_impl(rsvd_ctx *ctx, void *stream, rsvd_dtype dtype, rsvd_job job,
   if ((rc = times_at(curM, curN))) return rc;
   // step 5
   if ((rc = small_svd(ctx, s, dtype, w, n, l, curN, l, othN, seed, refill))) return rc;
-  RSVD_TRY(copy_launch(s, dtype, w.at<void>(L.sigma), S, k), "copy S");
+  RSVD_TRY(copy_launch(s, dtype, w.at<void>(L.sigma), S, k, batch, w.stride, stride_s * es), "copy S");
   if (job >= RSVD_JOB_SV) {
     // V^T = (Qb X[:, :k])^T
-    if ((rc = product(ctx, s, dtype, w, 0, n, k, l, curN, l, w.at<void>(L.Xj), l, Vt, ldvt, 1, false, PK_LIFT))) return rc;
+    if ((rc = product(ctx, s, dtype, w, 0, n, k, l, curN, l, w.at<void>(L.Xj), l, Vt, ldvt, 1, false, PK_LIFT, 1.0,
+                      nullptr, nullptr, 0.0, -1, stride_vt * es)))
+      return rc;
   }
   if (job == RSVD_JOB_SUV) {
     // step 6: U = Q Ub[:, :k]
-    if ((rc = product(ctx, s, dtype, w, 0, m, k, l, curM, l, w.at<void>(L.Wj), l, U, ldu, 0, false, PK_LIFT))) return rc;
+    if ((rc = product(ctx, s, dtype, w, 0, m, k, l, curM, l, w.at<void>(L.Wj), l, U, ldu, 0, false, PK_LIFT, 1.0,
+                      nullptr, nullptr, 0.0, -1, stride_u * es)))
+      return rc;
   }
   return finish_info(ctx, s, w, info);
 }
@@ -510,6 +546,35 @@ int rsvd_run_centered(rsvd_ctx *ctx, void *stream, rsvd_dtype dtype, rsvd_job jo
                       void *Vt, int64_t ldvt, void *workspace, size_t workspace_bytes, rsvd_info *info, void *mean) {
   return run_impl(ctx, stream, dtype, job, m, n, A, lda, k, p, q, seed, S, U, ldu, Vt, ldvt, workspace,
                   workspace_bytes, info, 1, mean);
+}
+
+int rsvd_workspace_bytes_batched(rsvd_ctx *ctx, rsvd_dtype dtype, int batch, int64_t m, int64_t n, int k, int p,
+                                 int q, rsvd_job job, size_t *bytes) {
+  if (batch < 1 || batch > 65535) return -3;
+  size_t one = 0;
+  const int rc = rsvd_workspace_bytes(ctx, dtype, m, n, k, p, q, job, &one);
+  if (rc != 0) return rc < -2 ? rc - 1 : rc;          // arguments after `batch` sit one place later here
+  if (bytes == nullptr) return -10;
+  *bytes = one * (size_t)batch;
+  return 0;
+}
+
+int rsvd_run_batched(rsvd_ctx *ctx, void *stream, rsvd_dtype dtype, rsvd_job job, int batch, int64_t m, int64_t n,
+                     const void *A, int64_t lda, int64_t stride_a, int k, int p, int q, uint64_t seed, void *S,
+                     int64_t stride_s, void *U, int64_t ldu, int64_t stride_u, void *Vt, int64_t ldvt,
+                     int64_t stride_vt, void *workspace, size_t workspace_bytes, rsvd_info *info) {
+  if (batch < 1 || batch > 65535) return -5;
+  // positions of the arguments in this prototype (run_impl reports those of rsvd_run)
+  static const int pos[20] = {0, 1, 2, 3, 4, 6, 7, 8, 9, 11, 12, 13, 14, 15, 17, 18, 20, 21, 23, 24};
+  if (batch > 1) {
+    if (stride_a < (m - 1) * lda + n) return -10;
+    if (stride_s < k) return -16;
+    if (job == RSVD_JOB_SUV && stride_u < (m - 1) * ldu + k) return -19;
+    if (job >= RSVD_JOB_SV && stride_vt < (int64_t)(k - 1) * ldvt + n) return -22;
+  }
+  const int rc = run_impl(ctx, stream, dtype, job, m, n, A, lda, k, p, q, seed, S, U, ldu, Vt, ldvt, workspace,
+                          workspace_bytes, info, 0, nullptr, batch, stride_a, stride_s, stride_u, stride_vt);
+  return (rc < 0 && -rc < 20) ? -pos[-rc] : rc;
 }
 
 int rsvd_stage_sketch(rsvd_ctx *ctx, void *stream, rsvd_dtype dtype, uint64_t seed, uint32_t stream_id, int64_t rows,

@@ -5,11 +5,15 @@
 namespace rsvd {
 
 // One thread per Philox group; the group's 4 (fp32) or 2 (fp64) normals go to
-// consecutive row-major elements of the rows x cols matrix.
+// consecutive row-major elements of the rows x cols matrix.  Problem blockIdx.y of a batch
+// uses seed + blockIdx.y and writes stride_out bytes further on.
 template <typename T, bool F32>
 __global__ __launch_bounds__(256) void sketch_kernel(uint64_t seed, uint32_t stream, int64_t cols,
-                                                     int64_t total, T *__restrict__ out, int64_t ld) {
+                                                     int64_t total, T *__restrict__ out, int64_t ld,
+                                                     int64_t stride_out) {
   constexpr int PER = F32 ? 4 : 2;
+  seed += (uint64_t)blockIdx.y;
+  out = reinterpret_cast<T *>(reinterpret_cast<char *>(out) + (int64_t)blockIdx.y * stride_out);
   const int64_t n_groups = (total + PER - 1) / PER;
   for (int64_t g = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; g < n_groups;
        g += (int64_t)gridDim.x * blockDim.x) {
@@ -55,15 +59,16 @@ static int grid_for(int64_t items) {
 }
 
 hipError_t sketch_launch(hipStream_t s, rsvd_dtype dtype, uint64_t seed, uint32_t stream_id,
-                         int64_t rows, int64_t cols, void *out, int64_t ld) {
+                         int64_t rows, int64_t cols, void *out, int64_t ld, int batch, int64_t stride_out) {
   const int64_t total = rows * cols;
   if (total == 0) return hipSuccess;
+  if (batch < 1 || batch > 65535) return hipErrorInvalidValue;
   if (dtype == RSVD_F32) {
-    hipLaunchKernelGGL((sketch_kernel<float, true>), dim3(grid_for((total + 3) / 4)), dim3(256), 0, s,
-                       seed, stream_id, cols, total, (float *)out, ld);
+    hipLaunchKernelGGL((sketch_kernel<float, true>), dim3(grid_for((total + 3) / 4), batch), dim3(256), 0, s,
+                       seed, stream_id, cols, total, (float *)out, ld, stride_out);
   } else {
-    hipLaunchKernelGGL((sketch_kernel<double, false>), dim3(grid_for((total + 1) / 2)), dim3(256), 0, s,
-                       seed, stream_id, cols, total, (double *)out, ld);
+    hipLaunchKernelGGL((sketch_kernel<double, false>), dim3(grid_for((total + 1) / 2), batch), dim3(256), 0, s,
+                       seed, stream_id, cols, total, (double *)out, ld, stride_out);
   }
   return hipGetLastError();
 }
