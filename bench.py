@@ -162,6 +162,57 @@ def sweep(args):
         torch.cuda.empty_cache()
 
 
+def batched(args):
+    """Batches of equal-shaped small problems (the clustering use of the solver): one JSON line per
+    (shape, batch) with the time per problem of rsvd_run_batched and of a loop of rsvd_run calls."""
+    import torch
+    from paper_2110_03423_amd import Rsvd
+
+    ctx = Rsvd(0)
+    dev = "cuda:0"
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(7)
+    cases = [  # m, n, k, p, q, dtype, batches
+        (2000, 500, 16, 16, 1, torch.float32, (1, 16, 256)),
+        (10000, 2000, 64, 16, 2, torch.float32, (1, 4, 16)),
+        (4000, 1000, 32, 16, 2, torch.float64, (1, 16, 64)),
+    ]
+    for (m, n, k, p, q, tdt, batches) in cases:
+        for batch in batches:
+            # low-rank-plus-noise problems, a different one per slot
+            r = 2 * (k + p)
+            A = torch.randn((batch, m, r), dtype=tdt, device=dev, generator=gen) @ \
+                (torch.randn((batch, r, n), dtype=tdt, device=dev, generator=gen) *
+                 (0.9 ** torch.arange(r, dtype=tdt, device=dev))[None, :, None])
+            A += 1e-3 * torch.randn(A.shape, dtype=tdt, device=dev, generator=gen)
+            out_b = None
+
+            def run_batched():
+                nonlocal out_b
+                out_b = ctx.rsvd_run_batched(A, k, p, q, seed=1, want_info=False)
+
+            def run_loop():
+                for b in range(batch):
+                    ctx.rsvd_run(A[b], k, p, q, seed=1 + b, want_info=False)
+
+            res = {}
+            for name, fn in (("batched", run_batched), ("loop", run_loop)):
+                for _ in range(args.warmup):
+                    fn()
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+                for _ in range(args.steps):
+                    fn()
+                torch.cuda.synchronize()
+                res[name] = (time.perf_counter() - t0) * 1e3 / args.steps
+            print(json.dumps({"batched": f"{m}x{n}", "dtype": "f32" if tdt == torch.float32 else "f64", "k": k, "p": p,
+                              "q": q, "batch": batch, "ms_per_problem_batched": round(res["batched"] / batch, 4),
+                              "ms_per_problem_loop": round(res["loop"] / batch, 4),
+                              "speedup": round(res["loop"] / res["batched"], 2)}), flush=True)
+            del A
+            torch.cuda.empty_cache()
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -174,6 +225,8 @@ def main():
     ap.add_argument("--sweep", action="store_true",
                     help="supplementary sweep instead of the benchmark: the shapes of configurations 3 and 5 with "
                          "(k, p, q) = (8, 8, 1) and (24, 8, 1), where the products with A are HBM bound")
+    ap.add_argument("--batched", action="store_true",
+                    help="supplementary: rsvd_run_batched on batches of small problems against a loop of rsvd_run calls")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device-to-device copy (reference dispatch for HBM counters)")
     args = ap.parse_args()
@@ -189,6 +242,9 @@ def main():
 
     if args.sweep:
         sweep(args)
+        return
+    if args.batched:
+        batched(args)
         return
     cfg = workloads.CONFIGS[args.config]
     dev = "cuda:0"
