@@ -28,7 +28,7 @@ PEAK_VALU = {"f32": 157.3e12, "f64": 78.6e12}    # vector FLOP/s (256 CUs, 2.4 G
 
 # HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this script at configuration 2,
 # scaled by the same counters on a plain 1 GiB copy (figures and commands: profiles/rsvd_run_cfg2_hbm_counters.md).
-MEASURED_TRAFFIC = {2: {"cholesky": 0.13e6, "jacobi": 0.11e6, "gemm_atx": 93.6e6, "gemm_ax": 97.2e6,
+MEASURED_TRAFFIC = {2: {"cholesky": 0.14e6, "jacobi": 0.12e6, "gemm_atx": 103.8e6, "gemm_ax": 108.5e6,
                         "gram": 6.6e6, "apply_rinv": 7.1e6}}
 
 
