@@ -4,7 +4,7 @@ Notation follows the paper: A is m x n, k the target rank, p the
 oversampling, q the exponent of the power scheme, s = k + p (called l here
 and in the rest of this repository), S the sketching matrix (Omega here).
 
-Readings where the paper leaves a choice (each also listed in the design doc):
+Readings where the paper leaves a choice:
   * A^* is the transpose (real input).
   * Algorithm 1 step 2 prints Y = (A A^*)^q A S with no intermediate
     factorisation, while the notes on steps 2-3 describe QR and GEMM
