@@ -64,7 +64,8 @@ typedef struct {
   int32_t refilled_columns;/* columns found linearly dependent and replaced by
                               fresh Gaussian directions, summed over all
                               orthonormalisations of the call */
-  int32_t reserved;
+  int32_t skipped_reorth;   /* 1: the condition estimate of the first panel let the power scheme drop one of
+                             * its two re-orthonormalisations per iteration (see rsvd_run); else 0 */
 } rsvd_info;
 
 /* Create / destroy a context bound to HIP device `device`.  Host-side only:
@@ -101,6 +102,13 @@ int rsvd_workspace_bytes(rsvd_ctx *ctx, rsvd_dtype dtype, int64_t m, int64_t n,
  *   info   host pointer or NULL.  Non-NULL: the call synchronises `stream`
  *          before returning and the return value includes device-side status.
  * Requires k >= 1, p >= 0, q >= 0, k + p <= min(m, n).
+ * Re-orthonormalisation inside the power scheme (step 2; the algorithm as
+ * printed has none, it is there for floating point): after every product by
+ * default.  When the triangular factor of the first panel A Omega shows a
+ * small condition number (estimate ||R||_F ||R^-1||_F / sqrt(k + p) at most
+ * 32 in fp32, 128 in fp64), one of the two factorisations of every iteration
+ * is dropped - decided on the device, no synchronisation; info->skipped_reorth
+ * reports it.  The basis of step 3 always gets its full treatment.
  */
 int rsvd_run(rsvd_ctx *ctx, void *stream, rsvd_dtype dtype, rsvd_job job,
              int64_t m, int64_t n, const void *A, int64_t lda,

@@ -124,8 +124,12 @@ __global__ __launch_bounds__(NB * 64) void chol_mfma_kernel(const double *__rest
                                                             const double *__restrict__ g0, double tau,
                                                             TOut *__restrict__ Rinv, int64_t ldri,
                                                             double *__restrict__ R, int64_t ldr,
-                                                            int *__restrict__ dead, DevInfo *info, int64_t stride) {
+                                                            int *__restrict__ dead, DevInfo *info, int64_t stride,
+                                                            const int *skip_flag) {
   typedef CholLds<NB> L;
+  if (skip_flag != nullptr &&
+      *reinterpret_cast<const int *>(reinterpret_cast<const char *>(skip_flag) + (int64_t)blockIdx.x * stride) != 0)
+    return;
   if (blockIdx.x != 0) {              // batched launch: one problem per workgroup, `stride` bytes apart
     const int64_t off = (int64_t)blockIdx.x * stride;
     G = reinterpret_cast<const double *>(reinterpret_cast<const char *>(G) + off);
@@ -323,7 +327,8 @@ size_t chol_scratch_elems(const rsvd_ctx *ctx, int64_t l) {
 template <typename TOut>
 static hipError_t launch_block(hipStream_t s, const double *G, int64_t ldg, int n_parts, int64_t part_stride, int nb,
                                const double *g0, double tau, TOut *Rinv, int64_t ldri, double *R, int64_t ldr,
-                               int *dead, DevInfo *info, int batch = 1, int64_t stride = 0) {
+                               int *dead, DevInfo *info, int batch = 1, int64_t stride = 0,
+                               const int *skip_flag = nullptr) {
   // one workgroup, one wavefront per 16-row block
 #define RSVD_CHOL_CASE(NBV)                                                                                         \
   do {                                                                                                              \
@@ -335,7 +340,7 @@ static hipError_t launch_block(hipStream_t s, const double *G, int64_t ldg, int 
       attr_set = true;                                                                                              \
     }                                                                                                               \
     hipLaunchKernelGGL((chol_mfma_kernel<TOut, NBV>), dim3(batch), dim3(NBV * 64), CholLds<NBV>::bytes, s, G, ldg,  \
-                       n_parts, part_stride, nb, g0, tau, Rinv, ldri, R, ldr, dead, info, stride);                  \
+                       n_parts, part_stride, nb, g0, tau, Rinv, ldri, R, ldr, dead, info, stride, skip_flag);       \
   } while (0)
   switch ((nb + 15) / 16) {
     case 1: RSVD_CHOL_CASE(1); break;
@@ -354,16 +359,17 @@ static hipError_t launch_block(hipStream_t s, const double *G, int64_t ldg, int 
 
 hipError_t chol_inverse_launch(rsvd_ctx *ctx, hipStream_t s, rsvd_dtype out_dtype, int64_t l, double *G,
                                int64_t ldg, int n_parts, int64_t part_stride, double tau, void *Rinv, double *R,
-                               int *dead, DevInfo *info, double *scratch, int batch, int64_t stride) {
+                               int *dead, DevInfo *info, double *scratch, int batch, int64_t stride,
+                               const int *skip_flag) {
   const int nbmax = chol_max_block(ctx);
   if (batch < 1 || batch > 65535) return hipErrorInvalidValue;
   if (l <= nbmax) {
     ProfScope ps(ctx, s, PK_CHOL);
     if (out_dtype == RSVD_F32)
       return launch_block<float>(s, G, ldg, n_parts, part_stride, (int)l, nullptr, tau, (float *)Rinv, l, R, l, dead,
-                                 info, batch, stride);
+                                 info, batch, stride, skip_flag);
     return launch_block<double>(s, G, ldg, n_parts, part_stride, (int)l, nullptr, tau, (double *)Rinv, l, R, l, dead,
-                                info, batch, stride);
+                                info, batch, stride, skip_flag);
   }
   if (batch != 1) return hipErrorNotSupported;       // the blocked path is not batched
   if (n_parts != 1) return hipErrorInvalidValue;     // the blocked path wants the reduced matrix
@@ -387,7 +393,7 @@ hipError_t chol_inverse_launch(rsvd_ctx *ctx, hipStream_t s, rsvd_dtype out_dtyp
     {
       ProfScope ps(ctx, s, PK_CHOL);
       e = launch_block<double>(s, G + j0 * ldg + j0, ldg, 1, 0, (int)b, g0 + j0, tau, Xf + j0 * l + j0, l,
-                               Rf + j0 * l + j0, l, dead + j0, info);
+                               Rf + j0 * l + j0, l, dead + j0, info, 1, 0, skip_flag);
     }
     if (e != hipSuccess) return e;
     if (rest > 0) {
@@ -397,7 +403,7 @@ hipError_t chol_inverse_launch(rsvd_ctx *ctx, hipStream_t s, rsvd_dtype out_dtyp
       p.A = Xf + j0 * l + j0; p.lda = l;
       p.B = G + j0 * ldg + j0 + b; p.ldb = ldg;
       p.C = Rf + j0 * l + j0 + b; p.ldc = l;
-      p.force_splits = 1;
+      p.force_splits = 1; p.skip_flag = skip_flag;
       if ((e = gemm_launch_f64(ctx, s, p)) != hipSuccess) return e;
       // trailing update: G[rest, rest] -= R[j, rest]^T R[j, rest]
       GemmDesc t;
@@ -407,6 +413,7 @@ hipError_t chol_inverse_launch(rsvd_ctx *ctx, hipStream_t s, rsvd_dtype out_dtyp
       t.C = G + (j0 + b) * ldg + j0 + b; t.ldc = ldg;
       t.alpha = -1.0; t.beta = 1.0; t.force_splits = 1;
       t.upper_only = 1;                 // nothing below reads the lower triangle of G
+      t.skip_flag = skip_flag;
       if ((e = gemm_launch_f64(ctx, s, t)) != hipSuccess) return e;
     }
     if (j0 > 0) {
@@ -415,13 +422,13 @@ hipError_t chol_inverse_launch(rsvd_ctx *ctx, hipStream_t s, rsvd_dtype out_dtyp
       a.M = j0; a.N = b; a.K = b;
       a.A = Rf + j0; a.lda = l;
       a.B = Xf + j0 * l + j0; a.ldb = l;
-      a.C = T; a.ldc = b; a.force_splits = 1;
+      a.C = T; a.ldc = b; a.force_splits = 1; a.skip_flag = skip_flag;
       if ((e = gemm_launch_f64(ctx, s, a)) != hipSuccess) return e;
       GemmDesc c;
       c.M = j0; c.N = b; c.K = j0;
       c.A = Xf; c.lda = l;
       c.B = T; c.ldb = b;
-      c.C = Xf + j0; c.ldc = l; c.alpha = -1.0; c.force_splits = 1;
+      c.C = Xf + j0; c.ldc = l; c.alpha = -1.0; c.force_splits = 1; c.skip_flag = skip_flag;
       if ((e = gemm_launch_f64(ctx, s, c)) != hipSuccess) return e;
     }
   }
@@ -432,6 +439,51 @@ hipError_t chol_inverse_launch(rsvd_ctx *ctx, hipStream_t s, rsvd_dtype out_dtyp
   }
   if (R != nullptr)
     hipLaunchKernelGGL((convert_matrix_kernel<double>), dim3(512), dim3(256), 0, s, Rf, l * l, R);
+  return hipGetLastError();
+}
+
+// One workgroup per problem: sums of squares of R and of R^-1, flag = (their product <= limit^2).
+template <typename T>
+__global__ __launch_bounds__(1024) void cond_flag_kernel(int l, const double *__restrict__ R, const T *__restrict__ Rinv,
+                                                         double limit, int *flag, DevInfo *info, int64_t stride) {
+  const int64_t off = (int64_t)blockIdx.x * stride;
+  R = reinterpret_cast<const double *>(reinterpret_cast<const char *>(R) + off);
+  Rinv = reinterpret_cast<const T *>(reinterpret_cast<const char *>(Rinv) + off);
+  flag = reinterpret_cast<int *>(reinterpret_cast<char *>(flag) + off);
+  __shared__ double part[2][16];
+  __shared__ int singular;
+  if (threadIdx.x == 0) singular = 0;
+  __syncthreads();
+  double a = 0.0, b = 0.0;
+  for (int e = threadIdx.x; e < l * l; e += blockDim.x) {
+    const double r = R[e], x = (double)Rinv[e];
+    a += r * r;
+    b += x * x;
+  }
+  for (int j = threadIdx.x; j < l; j += blockDim.x)
+    if (!(fabs((double)Rinv[j * l + j]) > 0.0)) singular = 1;       // a column was flagged dependent (or NaN)
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) { a += __shfl_xor(a, o, 64); b += __shfl_xor(b, o, 64); }
+  if ((threadIdx.x & 63) == 0) { part[0][threadIdx.x >> 6] = a; part[1][threadIdx.x >> 6] = b; }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    a = 0.0; b = 0.0;
+    for (int w = 0; w < (int)(blockDim.x >> 6); ++w) { a += part[0][w]; b += part[1][w]; }
+    const double k2 = a * b;                     // (||R||_F ||R^-1||_F)^2 >= cond_2(R)^2
+    const int f = (!singular && k2 > 0.0 && k2 <= limit * limit) ? 1 : 0;      // NaN and Inf give 0
+    *flag = f;
+    if (f && info != nullptr) atomicMax(&info->skipped_reorth, 1);
+  }
+}
+
+hipError_t cond_flag_launch(hipStream_t s, rsvd_dtype dtype, int64_t l, const double *R, const void *Rinv,
+                            double limit, int *flag, DevInfo *info, int batch, int64_t stride) {
+  if (dtype == RSVD_F32)
+    hipLaunchKernelGGL(cond_flag_kernel<float>, dim3(batch), dim3(1024), 0, s, (int)l, R, (const float *)Rinv, limit,
+                       flag, info, stride);
+  else
+    hipLaunchKernelGGL(cond_flag_kernel<double>, dim3(batch), dim3(1024), 0, s, (int)l, R, (const double *)Rinv, limit,
+                       flag, info, stride);
   return hipGetLastError();
 }
 

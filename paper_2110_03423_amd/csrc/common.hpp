@@ -59,7 +59,7 @@ struct DevInfo {
   int status;
   int jacobi_sweeps;
   int refilled;
-  int reserved;
+  int skipped_reorth;
 };
 
 // ---------------------------------------------------------------- GEMM
@@ -100,6 +100,10 @@ struct GemmDesc {
   int batch = 1;
   int64_t stride_a = 0, stride_b = 0, stride_c = 0, stride_partial = 0, stride_dead = 0, stride_r1u = 0, stride_r1v = 0;
   uint64_t seed_step = 0;               // problem b draws replacement columns with seed + b * seed_step
+  // Device-side switches (ints in device memory, one per problem, stride_flag bytes apart):
+  //   skip_flag != NULL and *skip_flag != 0: the launch (and its split-K reduction) does nothing;
+  //   alt_flag != NULL and *alt_flag != 0: B_alt (same shape, leading dimension and stride as B) replaces B.
+  const int *skip_flag = nullptr; const int *alt_flag = nullptr; const void *B_alt = nullptr; int64_t stride_flag = 0;
 };
 
 enum GemmKind { GEMM_F32 = 0, GEMM_F64 = 1, GEMM_F32_ACC64 = 2 };  // last: fp32 inputs, fp64 MFMA and output
@@ -130,10 +134,16 @@ size_t chol_scratch_elems(const rsvd_ctx *ctx, int64_t l);
 //   Gram matrix (unreduced split-K partials; single-block orders only).
 //   batch > 1 (single-block orders only): problem b = blockIdx.x adds b * stride bytes to G, Rinv, R,
 //   dead and info (stride 0 for info: one shared block).
+//   skip_flag (device, may be NULL; strided like the rest in a batch): non-zero = do nothing.
 hipError_t chol_inverse_launch(rsvd_ctx *ctx, hipStream_t s, rsvd_dtype out_dtype, int64_t l,
                                double *G, int64_t ldg, int n_parts, int64_t part_stride, double tau,
                                void *Rinv, double *R, int *dead, DevInfo *info, double *scratch,
-                               int batch = 1, int64_t stride = 0);
+                               int batch = 1, int64_t stride = 0, const int *skip_flag = nullptr);
+// *flag = 1 when the Frobenius condition number ||R||_F ||R^-1||_F (an upper bound of the 2-norm one) of the
+// l x l factor is at most `limit` and finite, else 0.  R fp64, Rinv in `dtype`, both l x l with ld l.
+// info (may be NULL): skipped_reorth is raised to the flag.
+hipError_t cond_flag_launch(hipStream_t s, rsvd_dtype dtype, int64_t l, const double *R, const void *Rinv,
+                            double limit, int *flag, DevInfo *info, int batch = 1, int64_t stride = 0);
 // Rb = R2 * R1 for upper triangular fp64 l x l matrices (ld l).
 hipError_t triu_product_launch(hipStream_t s, int64_t l, const double *R2, const double *R1, double *Rb,
                                int batch = 1, int64_t stride = 0);

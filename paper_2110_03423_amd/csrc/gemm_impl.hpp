@@ -40,6 +40,10 @@ struct GemmParams {
   // batched launch (blockIdx.y = problem): byte strides of the pointers above, seed step
   int64_t stride_a, stride_b, stride_c, stride_partial, stride_dead, stride_r1u, stride_r1v;
   uint64_t seed_step;
+  // device-side switches (ints in device memory, one per problem, stride_flag bytes apart; may be NULL):
+  //   *skip_flag != 0: the launch does nothing;  *alt_flag != 0: B_alt takes the place of B
+  const int *skip_flag; const int *alt_flag; const void *B_alt; int64_t stride_flag;
+  int skip_now;             // filled in on the device
 };
 
 // The parameters of problem blockIdx.y of a batched launch.
@@ -56,6 +60,10 @@ __device__ __forceinline__ GemmParams select_problem(const GemmParams &P0) {
     if (P.r1_v != nullptr) P.r1_v = (const char *)P.r1_v + b * P.stride_r1v;
     P.seed += (uint64_t)b * P.seed_step;
   }
+  P.skip_now = 0;
+  if (P.skip_flag != nullptr) P.skip_now = *(const int *)((const char *)P.skip_flag + b * P.stride_flag);
+  if (P.alt_flag != nullptr && *(const int *)((const char *)P.alt_flag + b * P.stride_flag) != 0)
+    P.B = (const char *)P.B_alt + b * P.stride_b;
   return P;
 }
 
@@ -140,6 +148,7 @@ template <typename TIn, typename TAcc, typename TOut, bool TA, int BM, int BN, i
           int BK = 32>
 __global__ __launch_bounds__(256) void gemm_kernel(const GemmParams P0) {
   const GemmParams P = select_problem(P0);
+  if (P.skip_now) return;
   static_assert(WGM * WGN == 4, "four wavefronts per workgroup");
   constexpr int WM = BM / WGM, WN = BN / WGN;
   static_assert(WM % 16 == 0 && WN % 16 == 0, "wave tile must be made of 16x16 blocks");
@@ -286,6 +295,7 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmParams P0) {
 template <typename TIn, typename TAcc, typename TOut>
 __global__ __launch_bounds__(256) void splitk_reduce_kernel(const GemmParams P0) {
   const GemmParams P = select_problem(P0);
+  if (P.skip_now) return;
   const int64_t total = P.M * P.N;
   for (int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; e < total;
        e += (int64_t)gridDim.x * blockDim.x) {
@@ -463,12 +473,14 @@ struct GemmDispatch {
     P.refill_scale = d.refill_scale; P.refill_ld = d.refill_ld;
     P.stride_a = d.stride_a; P.stride_b = d.stride_b; P.stride_c = d.stride_c; P.stride_partial = d.stride_partial;
     P.stride_dead = d.stride_dead; P.stride_r1u = d.stride_r1u; P.stride_r1v = d.stride_r1v; P.seed_step = d.seed_step;
+    P.skip_flag = d.skip_flag; P.alt_flag = d.alt_flag; P.B_alt = d.B_alt; P.stride_flag = d.stride_flag; P.skip_now = 0;
     // 16-byte vector loads need aligned bases, leading dimensions and extents.
     constexpr int V = 16 / sizeof(TIn);
     const int64_t a_contig = d.trans_a ? d.M : d.K;
     const bool vec = ((uintptr_t)d.A % 16 == 0) && ((uintptr_t)d.B % 16 == 0) && d.lda % V == 0 &&
                      d.ldb % V == 0 && a_contig % V == 0 && d.N % V == 0 &&
-                     (d.batch == 1 || (d.stride_a % 16 == 0 && d.stride_b % 16 == 0));
+                     (d.batch == 1 || (d.stride_a % 16 == 0 && d.stride_b % 16 == 0)) &&
+                     (d.B_alt == nullptr || (uintptr_t)d.B_alt % 16 == 0);
     hipError_t e;
     {
       ProfScope ps(ctx, s, d.prof_kind);

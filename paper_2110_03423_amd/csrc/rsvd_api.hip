@@ -147,6 +147,7 @@ struct Layout {
   size_t G, chol_scratch;           // fp64 Gram matrix, blocked-Cholesky scratch
   size_t Rinv, R1, R2, Rb;          // R^-1 (dtype), R factors of both rounds and their product (fp64)
   size_t dead, info;                // flags per column, DevInfo
+  size_t flags;                     // device-side switches (ints): [0] = the power scheme may skip one side
   size_t sigma, Wj, Xj;             // all l triplets of step 5: sigma, Ub (= W), X
   size_t jac_scratch, jac_scratch_bytes;
   size_t mean, shift;               // centred variant: column means (n), shift vector (l)
@@ -180,6 +181,7 @@ static Layout make_layout(const rsvd_ctx *ctx, rsvd_dtype dtype, int64_t m, int6
   L.Rb = take((size_t)l * l * 8);
   L.dead = take((size_t)l * sizeof(int));
   L.info = take(sizeof(DevInfo));
+  L.flags = take(16 * sizeof(int));
   L.sigma = take((size_t)l * es);
   L.Wj = take((size_t)l * l * es);
   L.Xj = take((size_t)l * l * es);
@@ -218,9 +220,11 @@ static int fail_hip(rsvd_ctx *ctx, hipError_t e, const char *where) {
 // the same range (orthonormal to about cond(Y) * eps), which is all the power
 // scheme needs between two products.  Rout (fp64, l x l, two rounds only)
 // receives R with Y = Q R, or NULL.
+// skip_flag (device int, or NULL): when it reads non-zero every launch of this call does nothing (the caller then
+// goes on with Y itself).  keep_r: the triangular factor of the first round is also written to the R1 buffer.
 static int orthonormalize(rsvd_ctx *ctx, hipStream_t s, rsvd_dtype dtype, const Ws &w, int64_t rows, int64_t l,
                           void *Y, int64_t ldy, void *tmp, double *Rout, uint64_t seed, uint32_t refill_stream,
-                          int rounds = 2) {
+                          int rounds = 2, const int *skip_flag = nullptr, bool keep_r = false) {
   const GemmKind kind = dtype == RSVD_F32 ? GEMM_F32 : GEMM_F64;
   const GemmKind gram = dtype == RSVD_F32 ? GEMM_F32_ACC64 : GEMM_F64;
   const Layout &L = w.L;
@@ -236,6 +240,7 @@ static int orthonormalize(rsvd_ctx *ctx, hipStream_t s, rsvd_dtype dtype, const 
     g.partial = w.at<void>(L.partial); g.partial_bytes = L.partial_bytes;
     g.prof_kind = PK_GRAM;
     g.batch = w.batch; g.stride_a = g.stride_b = g.stride_c = g.stride_partial = w.stride;
+    g.skip_flag = skip_flag; g.stride_flag = w.stride;
     g.upper_only = (l > chol_max_block(ctx)) ? 1 : 0;   // the blocked factorisation reads the upper triangle only
     // small orders: the Cholesky kernel adds the split-K partials itself
     int splits = 1;
@@ -243,11 +248,11 @@ static int orthonormalize(rsvd_ctx *ctx, hipStream_t s, rsvd_dtype dtype, const 
     g.skip_reduce_max = 4;          // more partials than this are cheaper to add in their own kernel
     g.splits_out = &splits;
     RSVD_TRY(gemm_launch(ctx, s, gram, g), "gram");
-    double *R = Rout ? w.at<double>(round == 0 ? L.R1 : L.R2) : nullptr;
+    double *R = (Rout || (keep_r && round == 0)) ? w.at<double>(round == 0 ? L.R1 : L.R2) : nullptr;
     const bool parts = g.skip_reduce && splits > 1 && splits <= g.skip_reduce_max;
     RSVD_TRY(chol_inverse_launch(ctx, s, dtype, l, parts ? w.at<double>(L.partial) : w.at<double>(L.G), l,
                                  parts ? splits : 1, l * l, tau, w.at<void>(L.Rinv), R, w.at<int>(L.dead),
-                                 w.at<DevInfo>(L.info), w.at<double>(L.chol_scratch), w.batch, w.stride),
+                                 w.at<DevInfo>(L.info), w.at<double>(L.chol_scratch), w.batch, w.stride, skip_flag),
              "cholesky");
     GemmDesc a;
     a.M = rows; a.N = l; a.K = l;
@@ -257,6 +262,7 @@ static int orthonormalize(rsvd_ctx *ctx, hipStream_t s, rsvd_dtype dtype, const 
     a.refill_scale = 1.0 / sqrt((double)rows); a.refill_ld = l;
     a.force_splits = 1;
     a.batch = w.batch; a.stride_a = a.stride_b = a.stride_c = a.stride_dead = w.stride; a.seed_step = 1;
+    a.skip_flag = skip_flag; a.stride_flag = w.stride;
     a.prof_kind = PK_APPLY;
     RSVD_TRY(gemm_launch(ctx, s, kind, a), "apply R^-1");
     void *tp = src; src = dst; dst = tp;
@@ -272,7 +278,8 @@ static int orthonormalize(rsvd_ctx *ctx, hipStream_t s, rsvd_dtype dtype, const 
 static int product(rsvd_ctx *ctx, hipStream_t s, rsvd_dtype dtype, const Ws &w, int trans_a, int64_t M, int64_t N,
                    int64_t K, const void *A, int64_t lda, const void *B, int64_t ldb, void *C, int64_t ldc,
                    int trans_c, bool allow_split, int prof_kind, double alpha = 1.0, const void *r1_u = nullptr,
-                   const void *r1_v = nullptr, double r1_alpha = 0.0, int64_t stride_a = -1, int64_t stride_c = -1) {
+                   const void *r1_v = nullptr, double r1_alpha = 0.0, int64_t stride_a = -1, int64_t stride_c = -1,
+                   const int *alt_flag = nullptr, const void *B_alt = nullptr) {
   // batched: B is always a workspace buffer; A and C are too unless the caller names their strides (bytes)
   GemmDesc d;
   d.batch = w.batch;
@@ -280,6 +287,7 @@ static int product(rsvd_ctx *ctx, hipStream_t s, rsvd_dtype dtype, const Ws &w, 
   d.stride_b = w.stride;
   d.stride_c = stride_c >= 0 ? stride_c : w.stride;
   d.stride_partial = w.stride;
+  d.alt_flag = alt_flag; d.B_alt = B_alt; d.stride_flag = w.stride;      // *alt_flag != 0: B_alt is the operand
   d.prof_kind = prof_kind;
   d.alpha = alpha; d.r1_u = r1_u; d.r1_v = r1_v; d.r1_alpha = r1_alpha;
   d.trans_a = trans_a; d.trans_c = trans_c; d.M = M; d.N = N; d.K = K;
@@ -313,7 +321,7 @@ static int finish_info(rsvd_ctx *ctx, hipStream_t s, const Ws &w, rsvd_info *inf
   info->status = h.status;
   info->jacobi_sweeps = h.jacobi_sweeps;
   info->refilled_columns = h.refilled;
-  info->reserved = 0;
+  info->skipped_reorth = h.skipped_reorth;
   return h.status;
 }
 
@@ -468,20 +476,21 @@ static int run_impl(rsvd_ctx *ctx, void *stream, rsvd_dtype dtype, rsvd_job job,
     if (mean_out != nullptr) RSVD_TRY(copy_launch(s, dtype, mean, mean_out, n), "copy mean");
   }
   // products with the (optionally centred) matrix; X is n x l for A X, m x l for A^T X
-  auto times_a = [&](const void *X, void *Y) -> int {
+  // (alt_flag / X_alt: when the device flag reads non-zero, X_alt is multiplied instead of X)
+  auto times_a = [&](const void *X, void *Y, const int *alt_flag = nullptr, const void *X_alt = nullptr) -> int {
     if (!center)
       return product(ctx, s, dtype, w, 0, m, l, n, A, lda, X, l, Y, l, 0, true, PK_GEMM_AX, 1.0, nullptr, nullptr, 0.0,
-                     stride_a * es);
+                     stride_a * es, -1, alt_flag, X_alt);
     {
       ProfScope ps(ctx, s, PK_SMALL);                                                                 // X^T mu
       RSVD_TRY(colsum_launch(s, dtype, X, l, n, l, mean, 1.0, shift, part, L.partial_bytes), "shift");
     }
     return product(ctx, s, dtype, w, 0, m, l, n, A, lda, X, l, Y, l, 0, true, PK_GEMM_AX, 1.0, nullptr, shift, -1.0);
   };
-  auto times_at = [&](const void *X, void *Z) -> int {
+  auto times_at = [&](const void *X, void *Z, const int *alt_flag = nullptr, const void *X_alt = nullptr) -> int {
     if (!center)
       return product(ctx, s, dtype, w, 1, n, l, m, A, lda, X, l, Z, l, 0, true, PK_GEMM_ATX, 1.0, nullptr, nullptr, 0.0,
-                     stride_a * es);
+                     stride_a * es, -1, alt_flag, X_alt);
     {
       ProfScope ps(ctx, s, PK_SMALL);                                                                 // X^T 1
       RSVD_TRY(colsum_launch(s, dtype, X, l, m, l, nullptr, 1.0, shift, part, L.partial_bytes), "shift");
@@ -496,21 +505,53 @@ static int run_impl(rsvd_ctx *ctx, void *stream, rsvd_dtype dtype, rsvd_job job,
   // step 2: Y = A Omega, then q rounds of Z = A^T Q, Y = A Z.  Every product is
   // re-orthonormalised; all but the last with a single CholeskyQR round (result in
   // the other panel of the pair), the last one (step 3) with two.
+  //
+  // Adaptive schedule (Algorithm 1 as printed has no factorisation inside the power scheme at all; the
+  // re-orthonormalisation is there for floating point): the factor R of the first panel Y = A Omega gives an
+  // upper bound kappa_F = ||R||_F ||R^-1||_F of its condition number, which is that of A on the sketched range.
+  // A panel that is multiplied by A (or A^T) without being orthonormalised first arrives with that number squared,
+  // so when kappa_F is small enough for the precision, one of the two orthonormalisations of every iteration
+  // is switched off ON THE DEVICE (flag in the workspace; the launches are still issued and return at once, the
+  // next product reads the raw panel).  The side that is dropped is the more expensive one; the final basis
+  // (step 3) always gets its two rounds.  The centred variant keeps the full schedule.
   void *curN = bN0, *othN = bN1, *curM = bM0, *othM = bM1;
   uint32_t refill = 16;
   auto swap = [](void *&a, void *&b) { void *t = a; a = b; b = t; };
+  const bool adaptive = q > 0 && !center;
+  const int *skip = adaptive ? w.at<int>(L.flags) : nullptr;
+  const bool drop_m = adaptive && (int64_t)(q - 1) * m > (int64_t)q * n;      // else the n-side ones are dropped
   if ((rc = times_a(curN, curM))) return rc;
-  if ((rc = orthonormalize(ctx, s, dtype, w, m, l, curM, l, othM, nullptr, seed, refill, q == 0 ? 2 : 1))) return rc;
+  if ((rc = orthonormalize(ctx, s, dtype, w, m, l, curM, l, othM, nullptr, seed, refill, q == 0 ? 2 : 1, nullptr,
+                           adaptive)))
+    return rc;
+  if (adaptive) {
+    // kappa_F overestimates the 2-norm condition number by a factor between 1 and l (about sqrt(l) for the
+    // decaying and the noise-floor spectra met here), so kappa_F / sqrt(l) serves as the estimate.  A skipped
+    // factorisation costs about eps * kappa^2 in the weakest sketched direction, and the next Gram matrix has
+    // condition kappa^4, which must stay clear of the dependent-column threshold: estimate <= 32 (fp32), 128 (fp64).
+    ProfScope ps(ctx, s, PK_SMALL);
+    const double limit = (dtype == RSVD_F32 ? 32.0 : 128.0) * sqrt((double)l);
+    RSVD_TRY(cond_flag_launch(s, dtype, l, w.at<double>(L.R1), w.at<void>(L.Rinv), limit, w.at<int>(L.flags),
+                              w.at<DevInfo>(L.info), batch, w.stride),
+             "condition flag");
+  }
   if (q > 0) swap(curM, othM);
   refill += 2;
+  bool m_raw = false;          // the previous m-side factorisation may have been skipped: raw panel in othM
   for (int it = 0; it < q; ++it) {
-    if ((rc = times_at(curM, curN))) return rc;
-    if ((rc = orthonormalize(ctx, s, dtype, w, n, l, curN, l, othN, nullptr, seed, refill, 1))) return rc;
+    if ((rc = times_at(curM, curN, m_raw ? skip : nullptr, m_raw ? othM : nullptr))) return rc;
+    const bool n_skippable = adaptive && !drop_m;
+    if ((rc = orthonormalize(ctx, s, dtype, w, n, l, curN, l, othN, nullptr, seed, refill, 1,
+                             n_skippable ? skip : nullptr)))
+      return rc;
     swap(curN, othN);
     refill += 2;
-    if ((rc = times_a(curN, curM))) return rc;
+    if ((rc = times_a(curN, curM, n_skippable ? skip : nullptr, n_skippable ? othN : nullptr))) return rc;
     const bool last = it == q - 1;
-    if ((rc = orthonormalize(ctx, s, dtype, w, m, l, curM, l, othM, nullptr, seed, refill, last ? 2 : 1))) return rc;
+    m_raw = adaptive && drop_m && !last;
+    if ((rc = orthonormalize(ctx, s, dtype, w, m, l, curM, l, othM, nullptr, seed, refill, last ? 2 : 1,
+                             m_raw ? skip : nullptr)))
+      return rc;
     if (!last) swap(curM, othM);
     refill += 2;
   }

@@ -203,3 +203,33 @@ def test_centered_variant_is_pca(dt, m, n, k, p, q):
     assert err_g <= 1.01 * err_o + 50 * eps * np.linalg.norm(Ac)
     # left vectors of a centred matrix are orthogonal to the ones vector
     assert np.abs(U.sum(axis=0)).max() <= 200 * np.sqrt(m) * eps * max(1.0, np.abs(mu).max() / S[-1] * np.sqrt(n))
+
+
+@pytest.mark.parametrize("m,n,q,expect", [
+    (6000, 300, 3, 1),      # tall, q = 3: the m-side factorisations inside the power scheme are dropped
+    (300, 6000, 2, 1),      # wide: the n-side ones
+    (2000, 500, 1, 1),      # q = 1: only an n-side one exists
+    (2000, 500, 0, 0),      # no power scheme, nothing to drop
+])
+def test_adaptive_reorthonormalisation(m, n, q, expect):
+    """Flat spectrum above a noise floor: the first panel is well conditioned, so one factorisation per
+    iteration is dropped on the device; the result must still meet the oracle (which never drops any)."""
+    import dataclasses
+    cfg = dataclasses.replace(scaled(CONFIGS[3], m, n, rank=20, k=24, p=8),
+                              spectrum=lambda i: 4.0 - i / 10.0)      # 4 .. 2.1 over a noise floor near 1
+    A = workloads.build(cfg)
+    A_dev = to_dev(A)
+    _, _, _, info = ctx().rsvd_run(A_dev, cfg.k, cfg.p, q, seed=cfg.seed)
+    assert info.skipped_reorth == expect
+    run_and_compare(cfg, A_dev, A, q=q, note="adaptive schedule")
+
+
+def test_ill_conditioned_panel_keeps_the_full_schedule():
+    cfg = scaled(CONFIGS[2], 1500, 400, k=40, p=24)       # 0.9^i: condition ~ 850 over the 64 sketched directions
+    A = workloads.build(cfg)
+    _, _, _, info = ctx().rsvd_run(to_dev(A), cfg.k, cfg.p, 2, seed=cfg.seed)
+    assert info.skipped_reorth == 0
+    cfg1 = scaled(CONFIGS[1], 300, 200, rank=9, k=9, p=5)  # rank-deficient sketch: never dropped
+    A1 = workloads.build(cfg1)
+    _, _, _, info = ctx().rsvd_run(to_dev(A1), cfg1.k, cfg1.p, 2, seed=0)
+    assert info.skipped_reorth == 0 and info.refilled_columns > 0
