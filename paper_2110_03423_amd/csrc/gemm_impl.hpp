@@ -154,7 +154,7 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmParams P0) {
   static_assert(WM % 16 == 0 && WN % 16 == 0, "wave tile must be made of 16x16 blocks");
   constexpr int TM = WM / 16, TN = WN / 16;
   // LDS strides (elements)
-  constexpr int SA = TA ? (BM + pad_kmajor(BM)) : (BK + (sizeof(TIn) == 4 ? 4 : 1));
+  constexpr int SA = TA ? (BM + pad_kmajor(BM)) : (BK + (sizeof(TIn) == 4 ? 4 : 2));
   constexpr int SB = BN + pad_kmajor(BN);
   constexpr int A_ROWS = TA ? BK : BM, A_COLS = TA ? BM : BK;
   __shared__ TIn As[A_ROWS * SA];
