@@ -47,6 +47,7 @@ CASES = [
     (scaled(CONFIGS[3], 2000, 250, rank=25, k=40, p=8), 3, 2),   # fp32, l = 48, noisy tail
     (scaled(CONFIGS[4], 500, 400, rank=64, k=64, p=32), 4, 1),   # fp64, l = 96: largest fp64 order of the batched path
     (scaled(CONFIGS[2], 333, 129, k=7, p=6), 9, 0),              # odd everything: scalar load paths, q = 0
+    (scaled(CONFIGS[5], 600, 300, rank=64, k=100, p=28), 3, 1),  # fp32, l = 128: largest order of the batched path
 ]
 
 
@@ -73,6 +74,26 @@ def test_batched_matches_oracle_and_single_calls(base, batch, q):
         tol = 200 * parity.EPS[base.dtype] * np.sqrt(max(base.m, base.n))
         assert (np.abs(S[b] - S1)[sig] <= tol * S1[0]).all(), b
     say("  worst relative singular value error", worst, "sweeps", info.jacobi_sweeps)
+
+
+def test_batch_mixes_schedules():
+    """The adaptive re-orthonormalisation is decided per problem on the device: a batch that holds a
+    well-conditioned matrix (drops a factorisation) next to an ill-conditioned one (keeps all) must get both right."""
+    import torch
+    flat = dataclasses.replace(scaled(CONFIGS[3], 1500, 300, rank=20, k=24, p=8), spectrum=lambda i: 4.0 - i / 10.0)
+    steep = dataclasses.replace(scaled(CONFIGS[2], 1500, 300, k=24, p=8), dtype="f32")
+    A = np.stack([workloads.build(flat), workloads.build(steep), workloads.build(dataclasses.replace(flat, cid=33))])
+    A_dev = torch.from_numpy(A).to("cuda:0")
+    c = ctx()
+    S, U, Vt, info = c.rsvd_run_batched(A_dev, 24, 8, 2, seed=5)
+    torch.cuda.synchronize()
+    assert info.status == 0 and info.skipped_reorth == 1
+    S, U, Vt = (to_np(t).astype(np.float64) for t in (S, U, Vt))
+    for b, cfg in enumerate((flat, steep, flat)):
+        _check_problem(b, cfg, A[b], S[b], U[b], Vt[b], 5 + b, 2)
+    # each problem on its own takes the schedule its own conditioning calls for
+    assert c.rsvd_run(A_dev[0], 24, 8, 2, seed=5)[3].skipped_reorth == 1
+    assert c.rsvd_run(A_dev[1], 24, 8, 2, seed=6)[3].skipped_reorth == 0
 
 
 def test_batched_strides_jobs_and_batch_of_one():
