@@ -302,8 +302,20 @@ __global__ void triu_product_kernel(int l, const double *__restrict__ R2, const 
   const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (e >= (int64_t)l * l) return;
   const int i = (int)(e / l), j = (int)(e - (int64_t)i * l);
+  // eight products per step with all their loads issued first (one at a time, every term would wait
+  // for its own memory round trip)
   double acc = 0.0;
-  for (int t = i; t <= j; ++t) acc += R2[(int64_t)i * l + t] * R1[(int64_t)t * l + j];
+  for (int t0 = i; t0 <= j; t0 += 8) {
+    double a[8], b[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const int t = t0 + u;
+      a[u] = (t <= j) ? R2[(int64_t)i * l + t] : 0.0;
+      b[u] = (t <= j) ? R1[(int64_t)t * l + j] : 0.0;
+    }
+#pragma unroll
+    for (int u = 0; u < 8; ++u) acc = fma(a[u], b[u], acc);
+  }
   Rb[e] = acc;
 }
 
