@@ -124,8 +124,10 @@ int rsvd_run(rsvd_ctx *ctx, void *stream, rsvd_dtype dtype, rsvd_job job,
 /*
  * The paper's PCA application: the same decomposition of the column-centred
  * matrix A - 1 mu^T (mu = column means of A, rows = observations), computed
- * without forming that matrix - every product with A or A^T gets its rank-one
- * correction in the epilogue of the product kernel.  S^2 / (m - 1) are the
+ * without forming that matrix: the product kernels take mu_j (kept in fp64)
+ * away from every element of A while they stage it, so the result is as
+ * accurate as on a matrix centred beforehand, however large the means are
+ * against the spread of the data.  S^2 / (m - 1) are the
  * variances along the principal axes, the rows of Vt the axes, U diag(S) the
  * scores.  Arguments as rsvd_run, positions 1-20 unchanged; `mean` (device,
  * n values, may be NULL) receives mu.

@@ -78,9 +78,11 @@ struct GemmDesc {
   const void *B = nullptr; int64_t ldb = 0;
   void *C = nullptr;       int64_t ldc = 0;
   double alpha = 1.0, beta = 0.0;
-  // r1_v != NULL: C[i][j] += r1_alpha * u[i] * v[j] with u = r1_u (length M) or all ones when
-  // r1_u == NULL, v = r1_v (length N), both in the output type; applied once, after any split-K sum.
-  const void *r1_u = nullptr; const void *r1_v = nullptr; double r1_alpha = 0.0;
+  // a_shift != NULL: the product is taken with A - 1 a_shift^T (one fp64 offset per column of the
+  // stored A, i.e. K of them for trans_a == 0 and M for trans_a != 0), subtracted element by element
+  // in fp64 while the tiles of A are staged.  Plain product only: alpha = 1, beta = 0, no trans_c,
+  // no dead columns, batch = 1.
+  const double *a_shift = nullptr;
   // upper_only != 0: the result is symmetric (M == N) and only its tiles on or above the diagonal
   // are computed; what lies in the tiles strictly below (and their split-K partials) is undefined.
   // Every 16 x 16 block on the diagonal is complete.
@@ -98,7 +100,7 @@ struct GemmDesc {
   // Batched launch: `batch` equal-shaped problems, one per blockIdx.y; the pointers above are
   // those of problem 0 and problem b adds b times the matching stride (in BYTES; 0 = shared).
   int batch = 1;
-  int64_t stride_a = 0, stride_b = 0, stride_c = 0, stride_partial = 0, stride_dead = 0, stride_r1u = 0, stride_r1v = 0;
+  int64_t stride_a = 0, stride_b = 0, stride_c = 0, stride_partial = 0, stride_dead = 0;
   uint64_t seed_step = 0;               // problem b draws replacement columns with seed + b * seed_step
   // Device-side switches (ints in device memory, one per problem, stride_flag bytes apart):
   //   skip_flag != NULL and *skip_flag != 0: the launch (and its split-K reduction) does nothing;

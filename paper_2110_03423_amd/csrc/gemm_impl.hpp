@@ -34,11 +34,11 @@ struct GemmParams {
   int upper_bm, upper_bn;   // > 0: symmetric result, tiles (of this size) strictly below the diagonal are skipped
   int trans_c;
   double alpha, beta;
-  const void *r1_u; const void *r1_v; double r1_alpha;
+  const double *a_shift;    // non-NULL: op(A) is built from A[i][j] - a_shift[j] (one value per column of A)
   const int *dead;
   uint64_t seed; uint32_t refill_stream; double refill_scale; int64_t refill_ld;
   // batched launch (blockIdx.y = problem): byte strides of the pointers above, seed step
-  int64_t stride_a, stride_b, stride_c, stride_partial, stride_dead, stride_r1u, stride_r1v;
+  int64_t stride_a, stride_b, stride_c, stride_partial, stride_dead;
   uint64_t seed_step;
   // device-side switches (ints in device memory, one per problem, stride_flag bytes apart; may be NULL):
   //   *skip_flag != 0: the launch does nothing;  *alt_flag != 0: B_alt takes the place of B
@@ -56,8 +56,6 @@ __device__ __forceinline__ GemmParams select_problem(const GemmParams &P0) {
     P.C = (char *)P.C + b * P.stride_c;
     if (P.partial != nullptr) P.partial = (char *)P.partial + b * P.stride_partial;
     if (P.dead != nullptr) P.dead = (const int *)((const char *)P.dead + b * P.stride_dead);
-    if (P.r1_u != nullptr) P.r1_u = (const char *)P.r1_u + b * P.stride_r1u;
-    if (P.r1_v != nullptr) P.r1_v = (const char *)P.r1_v + b * P.stride_r1v;
     P.seed += (uint64_t)b * P.seed_step;
   }
   P.skip_now = 0;
@@ -72,10 +70,6 @@ template <typename TOut, typename TAcc, bool F32STREAM>
 __device__ __forceinline__ void store_result(const GemmParams &P, int64_t row, int64_t col, TAcc acc) {
   TOut *C = (TOut *)P.C;
   double v = P.alpha * (double)acc;
-  if (P.r1_v != nullptr) {
-    const double u = (P.r1_u != nullptr) ? (double)((const TOut *)P.r1_u)[row] : 1.0;
-    v += P.r1_alpha * u * (double)((const TOut *)P.r1_v)[col];
-  }
   if (P.dead != nullptr && P.dead[col] != 0) {
     v = P.refill_scale *
         philox_normal_at<F32STREAM>((uint64_t)(row * P.refill_ld + col), P.refill_stream, P.seed);
@@ -93,24 +87,42 @@ __device__ __forceinline__ void store_result(const GemmParams &P, int64_t row, i
 // want a row stride that is not a multiple of 32 words.
 __host__ __device__ constexpr int pad_kmajor(int x) { return (x % 32 == 0) ? 16 : 0; }
 
-template <typename TIn, int ROWS, int COLS, int VEC>
+// SHIFT: the tile is a piece of a matrix whose columns carry an offset that is taken away on the way
+// to LDS (in fp64, rounded once): element (r, c) becomes x - shift[c].  The subtraction waits for
+// store(), so that the loads of the next tile stay in flight behind the matrix instructions.
+// (Tried: the offset as a pair of floats, and the subtraction placed behind the matrix instructions
+// of the tile before; neither was faster.)
+template <typename TIn, int ROWS, int COLS, int VEC, bool SHIFT = false>
 struct TileStage {
   static constexpr int SLOTS_PER_ROW = COLS / VEC;
   static constexpr int SLOTS = ROWS * SLOTS_PER_ROW;
   static constexpr int ITERS = (SLOTS + 255) / 256;
+  static_assert(!SHIFT || 256 % SLOTS_PER_ROW == 0, "a thread must stay in one column group");
   TIn regs[ITERS][VEC];
+  double sh[SHIFT ? VEC : 1];
+  unsigned valid;            // SHIFT: bit it = the slot of iteration it holds data (padding stays zero)
 
   // rows_left / cols_left: extent of valid data from the tile origin (may exceed the tile).
+  // shift: the offsets of the tile's columns (SHIFT only); NULL keeps those of the load before.
   // (Predicated loads behind a branch measured faster than unconditional loads from a clamped
   // address followed by a select.)
   __device__ __forceinline__ void load(const TIn *__restrict__ origin, int64_t ld, int64_t rows_left,
-                                       int64_t cols_left, int tid) {
+                                       int64_t cols_left, int tid, const double *__restrict__ shift = nullptr) {
+    if (SHIFT) {
+      valid = 0u;
+      if (shift != nullptr) {
+        const int c = (tid % SLOTS_PER_ROW) * VEC;
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) sh[e] = (c + e < cols_left) ? shift[c + e] : 0.0;
+      }
+    }
 #pragma unroll
     for (int it = 0; it < ITERS; ++it) {
       const int idx = tid + it * 256;
       const int r = idx / SLOTS_PER_ROW;
       const int c = (idx - r * SLOTS_PER_ROW) * VEC;
       const bool ok = (ITERS * 256 == SLOTS || idx < SLOTS) && r < rows_left && c < cols_left;
+      if (SHIFT && ok) valid |= 1u << it;
       if (VEC == 1) {
         regs[it][0] = ok ? origin[(int64_t)r * ld + c] : (TIn)0;
       } else {
@@ -130,7 +142,11 @@ struct TileStage {
         const int r = idx / SLOTS_PER_ROW;
         const int c = (idx - r * SLOTS_PER_ROW) * VEC;
 #pragma unroll
-        for (int e = 0; e < VEC; ++e) lds[r * stride + c + e] = regs[it][e];
+        for (int e = 0; e < VEC; ++e) {
+          TIn x = regs[it][e];
+          if (SHIFT) x = ((valid >> it) & 1u) ? (TIn)((double)x - sh[e]) : (TIn)0;
+          lds[r * stride + c + e] = x;
+        }
       }
     }
   }
@@ -141,7 +157,10 @@ struct TileStage {
 //   1  the full epilogue (scaling, accumulation, rank-one term, transposed store, replacement columns);
 //   2  C = alpha * acc + beta * C only, with all of a thread's old values of C loaded before the
 //      first store (element by element the loads would queue behind the stores, one memory
-//      round trip each).
+//      round trip each);
+//   3  as 0, with the column offsets P.a_shift taken away from A while its tiles are staged
+//      (the centred products: A - 1 mu^T is never formed, and no cancellation happens after
+//      the fact as it would with a rank-one correction of the product).
 // Separate instantiations, because the full epilogue inlines the Philox and Box-Muller code once per
 // accumulator element and the products with A never need it.
 template <typename TIn, typename TAcc, typename TOut, bool TA, int BM, int BN, int WGM, int WGN, int VEC, int EPI,
@@ -194,12 +213,15 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmParams P0) {
 #pragma unroll
     for (int j = 0; j < TN; ++j) acc[i][j] = (acc_t)(TAcc)0;
 
-  TileStage<TIn, A_ROWS, A_COLS, VEC> sa;
+  constexpr bool CENTER = (EPI == 3);
+  TileStage<TIn, A_ROWS, A_COLS, VEC, CENTER> sa;
   TileStage<TIn, BK, BN, VEC> sb;
 
   auto load_tiles = [&](int64_t k0) {
-    if (TA) sa.load(A + k0 * P.lda + m0, P.lda, k_end - k0, P.M - m0, tid);
-    else    sa.load(A + m0 * P.lda + k0, P.lda, P.M - m0, k_end - k0, tid);
+    // columns of A: the rows of op(A) = A^T (the same for every k-tile), the k index otherwise
+    if (TA) sa.load(A + k0 * P.lda + m0, P.lda, k_end - k0, P.M - m0, tid,
+                    (CENTER && k0 == k_begin) ? P.a_shift + m0 : nullptr);
+    else    sa.load(A + m0 * P.lda + k0, P.lda, P.M - m0, k_end - k0, tid, CENTER ? P.a_shift + k0 : nullptr);
     sb.load(B + k0 * P.ldb + n0, P.ldb, k_end - k0, P.N - n0, tid);
   };
 
@@ -228,7 +250,7 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmParams P0) {
   }
 
   // epilogue
-  if (EPI == 0 || P.splits > 1) {
+  if (EPI == 0 || EPI == 3 || P.splits > 1) {
     TOut *Cp = (TOut *)P.C;
     TAcc *Pp = (TAcc *)P.partial + (int64_t)split * P.M * P.N;
 #pragma unroll
@@ -405,9 +427,12 @@ struct GemmDispatch {
     Q.tiles_m = (int)ceil_div(P.M, BM);
     dim3 grid((unsigned)((int64_t)Q.tiles_n * Q.tiles_m * P.splits), (unsigned)batch);
     constexpr int V = 16 / sizeof(TIn);
-    const bool general = P.splits == 1 && (P.r1_v != nullptr || P.dead != nullptr || P.trans_c != 0);
+    const bool general = P.splits == 1 && (P.dead != nullptr || P.trans_c != 0);
     const bool scaled = P.splits == 1 && !general && (P.alpha != 1.0 || P.beta != 0.0);
-    if (general) {
+    if (P.a_shift != nullptr) {
+      if (vec) hipLaunchKernelGGL((gemm_kernel<TIn, TAcc, TOut, TA, BM, BN, WGM, WGN, V, 3, BK>), grid, dim3(256), 0, s, Q);
+      else hipLaunchKernelGGL((gemm_kernel<TIn, TAcc, TOut, TA, BM, BN, WGM, WGN, 1, 3, BK>), grid, dim3(256), 0, s, Q);
+    } else if (general) {
       if (vec) hipLaunchKernelGGL((gemm_kernel<TIn, TAcc, TOut, TA, BM, BN, WGM, WGN, V, 1, BK>), grid, dim3(256), 0, s, Q);
       else hipLaunchKernelGGL((gemm_kernel<TIn, TAcc, TOut, TA, BM, BN, WGM, WGN, 1, 1, BK>), grid, dim3(256), 0, s, Q);
     } else if (scaled) {
@@ -462,17 +487,20 @@ struct GemmDispatch {
       if (d.partial == nullptr || d.partial_bytes < need) return hipErrorInvalidValue;
     }
     if (d.trans_c && d.beta != 0.0) return hipErrorInvalidValue;
+    // the centred product has the lean epilogue only
+    if (d.a_shift != nullptr && (d.dead != nullptr || d.trans_c || d.alpha != 1.0 || d.beta != 0.0 || d.batch != 1))
+      return hipErrorInvalidValue;
     GemmParams P;
     P.M = d.M; P.N = d.N; P.K = d.K;
     P.A = d.A; P.lda = d.lda; P.B = d.B; P.ldb = d.ldb; P.C = d.C; P.ldc = d.ldc;
     P.partial = d.partial; P.k_per_split = c.k_per_split; P.splits = c.splits;
     P.trans_c = d.trans_c; P.alpha = d.alpha; P.beta = d.beta;
     P.upper_bm = d.upper_only ? t.bm : 0; P.upper_bn = d.upper_only ? t.bn : 0;
-    P.r1_u = d.r1_u; P.r1_v = d.r1_v; P.r1_alpha = d.r1_alpha;
+    P.a_shift = d.a_shift;
     P.dead = d.dead; P.seed = d.seed; P.refill_stream = d.refill_stream;
     P.refill_scale = d.refill_scale; P.refill_ld = d.refill_ld;
     P.stride_a = d.stride_a; P.stride_b = d.stride_b; P.stride_c = d.stride_c; P.stride_partial = d.stride_partial;
-    P.stride_dead = d.stride_dead; P.stride_r1u = d.stride_r1u; P.stride_r1v = d.stride_r1v; P.seed_step = d.seed_step;
+    P.stride_dead = d.stride_dead; P.seed_step = d.seed_step;
     P.skip_flag = d.skip_flag; P.alt_flag = d.alt_flag; P.B_alt = d.B_alt; P.stride_flag = d.stride_flag; P.skip_now = 0;
     // 16-byte vector loads need aligned bases, leading dimensions and extents.
     constexpr int V = 16 / sizeof(TIn);

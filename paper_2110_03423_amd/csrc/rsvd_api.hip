@@ -43,15 +43,14 @@ __global__ void copy_kernel(const T *__restrict__ src, T *__restrict__ dst, int6
     dst[e] = src[e];
 }
 
-// out[j] = alpha * sum_i w[i] * X[i][j] (w == NULL: all ones), accumulated in fp64 in two
-// deterministic stages: row chunks of kColsumRows, then the chunks in order.  Serves the
-// column means and the shift vectors of the centred variant.
+// Column means: out64[j] = (1 / rows) * sum_i X[i][j], accumulated in fp64 in two deterministic
+// stages (row chunks of kColsumRows, then the chunks in order); out (may be NULL) receives the
+// same values rounded to the matrix type.
 constexpr int kColsumRows = 128;
 
 template <typename T>
 __global__ __launch_bounds__(256) void colsum_partial_kernel(const T *__restrict__ X, int64_t ldx, int64_t rows,
-                                                             int64_t cols, const T *__restrict__ w,
-                                                             double *__restrict__ partial) {
+                                                             int64_t cols, double *__restrict__ partial) {
   const int64_t j = (int64_t)blockIdx.x * 256 + threadIdx.x;
   const int64_t r0 = (int64_t)blockIdx.y * kColsumRows;
   const int64_t r1 = (r0 + kColsumRows < rows) ? r0 + kColsumRows : rows;
@@ -61,21 +60,16 @@ __global__ __launch_bounds__(256) void colsum_partial_kernel(const T *__restrict
   int64_t i = r0;
   for (; i + 8 <= r1; i += 8) {
 #pragma unroll
-    for (int u = 0; u < 8; ++u) {
-      const double x = (double)X[(i + u) * ldx + j];
-      acc[u] += (w != nullptr) ? (double)w[i + u] * x : x;
-    }
+    for (int u = 0; u < 8; ++u) acc[u] += (double)X[(i + u) * ldx + j];
   }
-  for (; i < r1; ++i) {
-    const double x = (double)X[i * ldx + j];
-    acc[0] += (w != nullptr) ? (double)w[i] * x : x;
-  }
+  for (; i < r1; ++i) acc[0] += (double)X[i * ldx + j];
   partial[(int64_t)blockIdx.y * cols + j] = ((acc[0] + acc[1]) + (acc[2] + acc[3])) + ((acc[4] + acc[5]) + (acc[6] + acc[7]));
 }
 
 template <typename T>
 __global__ __launch_bounds__(256) void colsum_final_kernel(const double *__restrict__ partial, int chunks, int64_t cols,
-                                                           double alpha, T *__restrict__ out) {
+                                                           double alpha, double *__restrict__ out64,
+                                                           T *__restrict__ out) {
   const int64_t j = (int64_t)blockIdx.x * 256 + threadIdx.x;
   if (j >= cols) return;
   double acc[4] = {0, 0, 0, 0};
@@ -85,29 +79,32 @@ __global__ __launch_bounds__(256) void colsum_final_kernel(const double *__restr
     for (int u = 0; u < 4; ++u) acc[u] += partial[(int64_t)(c + u) * cols + j];
   }
   for (; c < chunks; ++c) acc[0] += partial[(int64_t)c * cols + j];
-  out[j] = (T)(alpha * ((acc[0] + acc[1]) + (acc[2] + acc[3])));
+  const double mu = alpha * ((acc[0] + acc[1]) + (acc[2] + acc[3]));
+  out64[j] = mu;
+  if (out != nullptr) out[j] = (T)mu;
 }
 
 static size_t colsum_partial_bytes(int64_t rows, int64_t cols) {
   return (size_t)ceil_div(rows, kColsumRows) * (size_t)cols * sizeof(double);
 }
 
-static hipError_t colsum_launch(hipStream_t s, rsvd_dtype dtype, const void *X, int64_t ldx, int64_t rows, int64_t cols,
-                                const void *w, double alpha, void *out, void *partial, size_t partial_bytes) {
+static hipError_t colmean_launch(hipStream_t s, rsvd_dtype dtype, const void *X, int64_t ldx, int64_t rows,
+                                 int64_t cols, double *out64, void *out, void *partial, size_t partial_bytes) {
   const int chunks = (int)ceil_div(rows, kColsumRows);
   if (partial == nullptr || partial_bytes < colsum_partial_bytes(rows, cols)) return hipErrorInvalidValue;
   dim3 grid((unsigned)ceil_div(cols, 256), (unsigned)chunks);
   dim3 grid2((unsigned)ceil_div(cols, 256));
+  const double alpha = 1.0 / (double)rows;
   if (dtype == RSVD_F32) {
     hipLaunchKernelGGL(colsum_partial_kernel<float>, grid, dim3(256), 0, s, (const float *)X, ldx, rows, cols,
-                       (const float *)w, (double *)partial);
+                       (double *)partial);
     hipLaunchKernelGGL(colsum_final_kernel<float>, grid2, dim3(256), 0, s, (const double *)partial, chunks, cols,
-                       alpha, (float *)out);
+                       alpha, out64, (float *)out);
   } else {
     hipLaunchKernelGGL(colsum_partial_kernel<double>, grid, dim3(256), 0, s, (const double *)X, ldx, rows, cols,
-                       (const double *)w, (double *)partial);
+                       (double *)partial);
     hipLaunchKernelGGL(colsum_final_kernel<double>, grid2, dim3(256), 0, s, (const double *)partial, chunks, cols,
-                       alpha, (double *)out);
+                       alpha, out64, (double *)out);
   }
   return hipGetLastError();
 }
@@ -150,7 +147,7 @@ struct Layout {
   size_t flags;                     // device-side switches (ints): [0] = the power scheme may skip one side
   size_t sigma, Wj, Xj;             // all l triplets of step 5: sigma, Ub (= W), X
   size_t jac_scratch, jac_scratch_bytes;
-  size_t mean, shift;               // centred variant: column means (n), shift vector (l)
+  size_t mean;                      // centred variant: column means (n, fp64)
   size_t total;
 };
 
@@ -169,8 +166,6 @@ static Layout make_layout(const rsvd_ctx *ctx, rsvd_dtype dtype, int64_t m, int6
   if ((t = gemm_partial_bytes(ctx, gram, 1, l, l, m)) > pb) pb = t;
   if ((t = gemm_partial_bytes(ctx, gram, 1, l, l, n)) > pb) pb = t;
   if ((t = colsum_partial_bytes(m, n)) > pb) pb = t;      // column means of the centred variant
-  if ((t = colsum_partial_bytes(m, l)) > pb) pb = t;      // and its shift vectors
-  if ((t = colsum_partial_bytes(n, l)) > pb) pb = t;
   L.partial_bytes = pb;
   L.partial = take(pb);
   L.G = take((size_t)l * l * 8);
@@ -187,8 +182,7 @@ static Layout make_layout(const rsvd_ctx *ctx, rsvd_dtype dtype, int64_t m, int6
   L.Xj = take((size_t)l * l * es);
   L.jac_scratch_bytes = jacobi_scratch_bytes(ctx, dtype, l);
   L.jac_scratch = take(L.jac_scratch_bytes);
-  L.mean = take((size_t)n * es);
-  L.shift = take((size_t)l * es);
+  L.mean = take((size_t)n * 8);
   L.total = off;
   return L;
 }
@@ -277,9 +271,9 @@ static int orthonormalize(rsvd_ctx *ctx, hipStream_t s, rsvd_dtype dtype, const 
 
 static int product(rsvd_ctx *ctx, hipStream_t s, rsvd_dtype dtype, const Ws &w, int trans_a, int64_t M, int64_t N,
                    int64_t K, const void *A, int64_t lda, const void *B, int64_t ldb, void *C, int64_t ldc,
-                   int trans_c, bool allow_split, int prof_kind, double alpha = 1.0, const void *r1_u = nullptr,
-                   const void *r1_v = nullptr, double r1_alpha = 0.0, int64_t stride_a = -1, int64_t stride_c = -1,
-                   const int *alt_flag = nullptr, const void *B_alt = nullptr) {
+                   int trans_c, bool allow_split, int prof_kind, double alpha = 1.0, const double *a_shift = nullptr,
+                   int64_t stride_a = -1, int64_t stride_c = -1, const int *alt_flag = nullptr,
+                   const void *B_alt = nullptr) {
   // batched: B is always a workspace buffer; A and C are too unless the caller names their strides (bytes)
   GemmDesc d;
   d.batch = w.batch;
@@ -289,7 +283,7 @@ static int product(rsvd_ctx *ctx, hipStream_t s, rsvd_dtype dtype, const Ws &w, 
   d.stride_partial = w.stride;
   d.alt_flag = alt_flag; d.B_alt = B_alt; d.stride_flag = w.stride;      // *alt_flag != 0: B_alt is the operand
   d.prof_kind = prof_kind;
-  d.alpha = alpha; d.r1_u = r1_u; d.r1_v = r1_v; d.r1_alpha = r1_alpha;
+  d.alpha = alpha; d.a_shift = a_shift;
   d.trans_a = trans_a; d.trans_c = trans_c; d.M = M; d.N = N; d.K = K;
   d.A = A; d.lda = lda; d.B = B; d.ldb = ldb; d.C = C; d.ldc = ldc;
   if (allow_split) { d.partial = w.at<void>(w.L.partial); d.partial_bytes = w.L.partial_bytes; }
@@ -422,8 +416,8 @@ int rsvd_workspace_bytes(rsvd_ctx *ctx, rsvd_dtype dtype, int64_t m, int64_t n, 
 }
 
 // Algorithm 1 on A, or (center != 0) on A - 1 mu^T with mu the column means of A, without forming that matrix:
-//   (A - 1 mu^T) X = A X - 1 (mu^T X),   (A - 1 mu^T)^T Q = A^T Q - mu (1^T Q),
-// the rank-one terms being added in the epilogue of the same product kernels.
+// the product kernels take mu_j (fp64) away from every element of A on its way into LDS, so the result carries
+// rounding errors of the size of the centred entries, not of the means.
 // batch > 1: `batch` problems of the same shape, problem b at A + b * stride_a elements (likewise S, U, Vt), sketch
 // seed + b; every kernel launch covers the whole batch.  Needs l within the single-workgroup Cholesky and Jacobi
 // kernels and no centring; the diagnostics are those of the whole batch (worst status, most sweeps, all replaced
@@ -467,35 +461,21 @@ static int run_impl(rsvd_ctx *ctx, void *stream, rsvd_dtype dtype, rsvd_job job,
   int rc;
 
   RSVD_TRY(zero_ints_launch(s, w.at<int>(L.info), 4), "zero info");
-  void *mean = w.at<void>(L.mean), *shift = w.at<void>(L.shift);
-  void *part = w.at<void>(L.partial);
+  double *mean = center ? w.at<double>(L.mean) : nullptr;
   if (center) {
-    // mu = A^T 1 / m
+    // mu = A^T 1 / m, kept in fp64 for the products and handed out in the matrix type
     ProfScope ps(ctx, s, PK_SMALL);
-    RSVD_TRY(colsum_launch(s, dtype, A, lda, m, n, nullptr, 1.0 / (double)m, mean, part, L.partial_bytes), "means");
-    if (mean_out != nullptr) RSVD_TRY(copy_launch(s, dtype, mean, mean_out, n), "copy mean");
+    RSVD_TRY(colmean_launch(s, dtype, A, lda, m, n, mean, mean_out, w.at<void>(L.partial), L.partial_bytes), "means");
   }
   // products with the (optionally centred) matrix; X is n x l for A X, m x l for A^T X
   // (alt_flag / X_alt: when the device flag reads non-zero, X_alt is multiplied instead of X)
   auto times_a = [&](const void *X, void *Y, const int *alt_flag = nullptr, const void *X_alt = nullptr) -> int {
-    if (!center)
-      return product(ctx, s, dtype, w, 0, m, l, n, A, lda, X, l, Y, l, 0, true, PK_GEMM_AX, 1.0, nullptr, nullptr, 0.0,
-                     stride_a * es, -1, alt_flag, X_alt);
-    {
-      ProfScope ps(ctx, s, PK_SMALL);                                                                 // X^T mu
-      RSVD_TRY(colsum_launch(s, dtype, X, l, n, l, mean, 1.0, shift, part, L.partial_bytes), "shift");
-    }
-    return product(ctx, s, dtype, w, 0, m, l, n, A, lda, X, l, Y, l, 0, true, PK_GEMM_AX, 1.0, nullptr, shift, -1.0);
+    return product(ctx, s, dtype, w, 0, m, l, n, A, lda, X, l, Y, l, 0, true, PK_GEMM_AX, 1.0, mean, stride_a * es, -1,
+                   alt_flag, X_alt);
   };
   auto times_at = [&](const void *X, void *Z, const int *alt_flag = nullptr, const void *X_alt = nullptr) -> int {
-    if (!center)
-      return product(ctx, s, dtype, w, 1, n, l, m, A, lda, X, l, Z, l, 0, true, PK_GEMM_ATX, 1.0, nullptr, nullptr, 0.0,
-                     stride_a * es, -1, alt_flag, X_alt);
-    {
-      ProfScope ps(ctx, s, PK_SMALL);                                                                 // X^T 1
-      RSVD_TRY(colsum_launch(s, dtype, X, l, m, l, nullptr, 1.0, shift, part, L.partial_bytes), "shift");
-    }
-    return product(ctx, s, dtype, w, 1, n, l, m, A, lda, X, l, Z, l, 0, true, PK_GEMM_ATX, 1.0, mean, shift, -1.0);
+    return product(ctx, s, dtype, w, 1, n, l, m, A, lda, X, l, Z, l, 0, true, PK_GEMM_ATX, 1.0, mean, stride_a * es, -1,
+                   alt_flag, X_alt);
   };
   // step 1
   {
@@ -513,11 +493,11 @@ static int run_impl(rsvd_ctx *ctx, void *stream, rsvd_dtype dtype, rsvd_job job,
   // so when kappa_F is small enough for the precision, one of the two orthonormalisations of every iteration
   // is switched off ON THE DEVICE (flag in the workspace; the launches are still issued and return at once, the
   // next product reads the raw panel).  The side that is dropped is the more expensive one; the final basis
-  // (step 3) always gets its two rounds.  The centred variant keeps the full schedule.
+  // (step 3) always gets its two rounds.
   void *curN = bN0, *othN = bN1, *curM = bM0, *othM = bM1;
   uint32_t refill = 16;
   auto swap = [](void *&a, void *&b) { void *t = a; a = b; b = t; };
-  const bool adaptive = q > 0 && !center;
+  const bool adaptive = q > 0;
   const int *skip = adaptive ? w.at<int>(L.flags) : nullptr;
   const bool drop_m = adaptive && (int64_t)(q - 1) * m > (int64_t)q * n;      // else the n-side ones are dropped
   if ((rc = times_a(curN, curM))) return rc;
@@ -563,13 +543,13 @@ static int run_impl(rsvd_ctx *ctx, void *stream, rsvd_dtype dtype, rsvd_job job,
   if (job >= RSVD_JOB_SV) {
     // V^T = (Qb X[:, :k])^T
     if ((rc = product(ctx, s, dtype, w, 0, n, k, l, curN, l, w.at<void>(L.Xj), l, Vt, ldvt, 1, false, PK_LIFT, 1.0,
-                      nullptr, nullptr, 0.0, -1, stride_vt * es)))
+                      nullptr, -1, stride_vt * es)))
       return rc;
   }
   if (job == RSVD_JOB_SUV) {
     // step 6: U = Q Ub[:, :k]
     if ((rc = product(ctx, s, dtype, w, 0, m, k, l, curM, l, w.at<void>(L.Wj), l, U, ldu, 0, false, PK_LIFT, 1.0,
-                      nullptr, nullptr, 0.0, -1, stride_u * es)))
+                      nullptr, -1, stride_u * es)))
       return rc;
   }
   return finish_info(ctx, s, w, info);

@@ -205,6 +205,32 @@ def test_centered_variant_is_pca(dt, m, n, k, p, q):
     assert np.abs(U.sum(axis=0)).max() <= 200 * np.sqrt(m) * eps * max(1.0, np.abs(mu).max() / S[-1] * np.sqrt(n))
 
 
+@pytest.mark.parametrize("dt,m,n,k,p,q,scale", [("f32", 2479, 1668, 60, 4, 2, 1e3), ("f32", 690, 2360, 23, 14, 0, 3e3),
+                                               ("f64", 1200, 700, 30, 10, 1, 1e6)])
+def test_centered_variant_with_dominant_means(dt, m, n, k, p, q, scale):
+    """Feature means `scale` times larger than the spread of the data: the result must be as good as Algorithm 1
+    on the explicitly centred matrix, i.e. carry rounding errors of the size of the centred entries (a product
+    corrected by a rank-one term after the fact would carry those of the means)."""
+    say("centered, dominant means", dt, m, n, k, p, q, scale)
+    npdt = np.float32 if dt == "f32" else np.float64
+    cfg = scaled(CONFIGS[3], m, n, rank=min(40, n), k=k, p=p)
+    base = workloads.build(cfg).astype(np.float64)
+    offs = workloads.gaussian_matrix(1, n, seed=78)
+    A = (base * 0.05 + scale * 0.05 * offs).astype(npdt)
+    S, U, Vt, info, mean = ctx().rsvd_run_centered(to_dev(A), k, p, q, seed=cfg.seed)
+    S, U, Vt, mean = (to_np(t).astype(np.float64) for t in (S, U, Vt, mean))
+    A64 = A.astype(np.float64)
+    Ac = A64 - A64.mean(axis=0)
+    assert np.linalg.norm(A64) >= 0.2 * scale * np.linalg.norm(Ac)
+    o = orc.rsvd(Ac, k, p, q, cfg.seed, npdt)
+    res = parity.check_triplets(S, U, Vt, o.S, o.U, o.Vt, dt, m, n)
+    eps = parity.EPS[dt]
+    err_g = orc.reconstruction_error(Ac, U, S, Vt)
+    err_o = orc.reconstruction_error(Ac, o.U, o.S, o.Vt)
+    say(f"  sv_rel={res['sv_rel_max']:.2e} sinU={res['sin_u']:.2e} sinV={res['sin_v']:.2e} err ratio {err_g / err_o:.6f}")
+    assert err_g <= 1.01 * err_o + 50 * eps * np.linalg.norm(Ac)
+
+
 @pytest.mark.parametrize("m,n,q,expect", [
     (6000, 300, 3, 1),      # tall, q = 3: the m-side factorisations inside the power scheme are dropped
     (300, 6000, 2, 1),      # wide: the n-side ones
