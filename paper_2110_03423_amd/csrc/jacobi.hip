@@ -450,12 +450,6 @@ __device__ __forceinline__ float rotate_moving_panel(jac_unit<T> (&x)[NV], T (&t
   return ratio;
 }
 
-// Workgroup barrier that orders LDS accesses only (a full __syncthreads also waits for the
-// wavefront's outstanding global stores).
-__device__ __forceinline__ void lds_barrier() {
-  asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
-}
-
 // scratch header shared by the block-Jacobi kernels
 struct JbHeader {
   double fro2;            // ||M||_F^2
@@ -498,30 +492,112 @@ template <typename T, int NV> __host__ __device__ constexpr int jb_ldp() { retur
 //   the other exactly once.
 // One outer sweep = one diagonal launch + (nblk - 1) cross launches = l - 1 rounds
 // in all, the same count as the plain tournament.
-template <typename T, int NV>
-__global__ __launch_bounds__(1024) void jb_panel_kernel(T *__restrict__ Mt, T *__restrict__ Jt, int l, int b,
-                                                        int nblk, int phase, int round, int sweep, JbHeader *hdr) {
-  const T tol = Eps<T>::value * sqrt((T)l);
-  // converged in the previous sweep (see the stopping rule at the top of this file)
-  if (sweep > 0 && __int_as_float(hdr->counters[sweep - 1]) <= 0.25f * sqrtf((float)tol)) return;
-  int bi, bj, cols_i, cols_j;
+//
+// The rotations never read J, and a launch keeps only nblk / 2 of the chip's workgroups busy.
+// So a rotating workgroup only leaves its accumulated T (and a flag that it rotated at all) in a
+// two-slot ring in global memory, and the NEXT launch carries, behind its own rot_wgs rotating
+// workgroups, one workgroup per (block pair of the launch before, chunk of kJbRowChunk rows) that
+// applies that T to the matching columns of J on the matrix cores while the rotations of the
+// current round run.  A last launch with rot_wgs = 0 applies what the final round left.
+
+// Block pair (and column counts) of workgroup g of a launch.
+struct JbPair { int bi, bj, cols_i, cols_j; bool valid; };
+__device__ __forceinline__ JbPair jb_pair(int phase, int round, int g, int l, int b, int nblk) {
+  JbPair p;
+  p.valid = true;
   if (phase == 0) {
-    bi = bj = (int)blockIdx.x;
-    cols_i = (l - bi * b < b) ? (l - bi * b) : b;
-    cols_j = 0;
+    p.bi = p.bj = g;
+    p.cols_i = (l - p.bi * b < b) ? (l - p.bi * b) : b;
+    p.cols_j = 0;
   } else {
     const int nblk2 = nblk + (nblk & 1);
     int ba, bb;
-    tournament_pair(nblk2, round, blockIdx.x, ba, bb);
-    if (ba >= nblk || bb >= nblk) return;                      // bye
-    bi = ba < bb ? ba : bb;
-    bj = ba < bb ? bb : ba;
-    cols_i = (l - bi * b < b) ? (l - bi * b) : b;
-    cols_j = (l - bj * b < b) ? (l - bj * b) : b;
+    tournament_pair(nblk2, round, g, ba, bb);
+    p.valid = ba < nblk && bb < nblk;                          // else a bye
+    p.bi = ba < bb ? ba : bb;
+    p.bj = ba < bb ? bb : ba;
+    p.cols_i = (l - p.bi * b < b) ? (l - p.bi * b) : b;
+    p.cols_j = p.valid ? ((l - p.bj * b < b) ? (l - p.bj * b) : b) : 0;
   }
+  return p;
+}
+
+constexpr int kJbRowChunk = 64;
+
+// J[rows of chunk, panel] <- J[rows of chunk, panel] T for block pair `pr`: the old entries staged
+// through LDS, a (64 x 2b) by (2b x 2b) product in 16 x 16 blocks.
+template <typename T>
+__device__ __forceinline__ void jb_apply_t(T *__restrict__ Jt, const T *__restrict__ Tg, int l, int b, const JbPair &pr,
+                                           int chunk, T *lds) {
+  constexpr int LDJ = kJbRowChunk + 8;
+  const int ldt = 2 * b + 2;
+  T *Pj = lds;                       // [2b][LDJ]: Pj[k][i] = J[i0 + i][panel column k]
+  T *Tl = lds + (size_t)(2 * b) * LDJ;      // [2b][ldt]: Tl[col][k] = T[k][col]
+  const int tid = threadIdx.x, nt = blockDim.x;
+  const int lane64 = tid & 63, wave = tid >> 6, nwave = nt >> 6;
+  const int ncols = pr.cols_i + pr.cols_j;
+  const int i0 = chunk * kJbRowChunk;
+  auto gcol = [&](int c) { return c < pr.cols_i ? pr.bi * b + c : pr.bj * b + (c - pr.cols_i); };
+  for (int c = wave; c < 2 * b; c += nwave) {
+    const int i = i0 + lane64;
+    Pj[c * LDJ + lane64] = (c < ncols && i < l) ? Jt[(int64_t)gcol(c) * l + i] : (T)0;
+  }
+  for (int idx = tid; idx < 4 * b * b; idx += nt) {
+    const int c = idx / (2 * b), k = idx - c * (2 * b);
+    Tl[c * ldt + k] = Tg[idx];
+  }
+  __syncthreads();
+  typedef typename Mfma<T>::vec acc_t;
+  const int r16 = lane64 & 15, kq = lane64 >> 4;
+  const int col_blocks = (2 * b) / 16;
+  for (int blk = wave; blk < (kJbRowChunk / 16) * col_blocks; blk += nwave) {
+    const int rb = blk / col_blocks, cb = blk - rb * col_blocks;
+    acc_t acc = (acc_t)(T)0;
+    const T *ap = Pj + kq * LDJ + rb * 16 + r16;                  // Jold[row][k]
+    const T *bp = Tl + (cb * 16 + r16) * ldt + kq;                // T[k][col]
+#pragma unroll 4
+    for (int k0 = 0; k0 < 2 * b; k0 += 4) acc = Mfma<T>::run(ap[k0 * LDJ], bp[k0], acc);
+    const int cn = cb * 16 + r16;
+    if (cn < ncols) {
+      T *dst = Jt + (int64_t)gcol(cn) * l;
+#pragma unroll
+      for (int v = 0; v < 4; ++v) {
+        const int r = i0 + rb * 16 + Mfma<T>::row(lane64, v);
+        if (r < l) dst[r] = acc[v];
+      }
+    }
+  }
+}
+
+template <typename T, int NV>
+__global__ __launch_bounds__(1024) void jb_panel_kernel(T *__restrict__ Mt, T *__restrict__ Jt, int l, int b,
+                                                        int nblk, int phase, int round, int sweep, int rot_wgs,
+                                                        int prev_phase, int prev_round, int prev_sweep,
+                                                        T *__restrict__ Tring, int *__restrict__ chg, int slot,
+                                                        JbHeader *hdr) {
+  const T tol = Eps<T>::value * sqrt((T)l);
+  const float rho_last = 0.25f * sqrtf((float)tol);            // see the stopping rule at the top of this file
+  extern __shared__ __attribute__((aligned(16))) double lds_raw[];
+  if ((int)blockIdx.x >= rot_wgs) {
+    // J role: the launch before (phase, round, sweep = prev_*) left its T in the other slot
+    const int chunks = (l + kJbRowChunk - 1) / kJbRowChunk;
+    const int j = (int)blockIdx.x - rot_wgs;
+    const int g = j / chunks;
+    if (prev_sweep > 0 && __int_as_float(hdr->counters[prev_sweep - 1]) <= rho_last) return;   // that launch did nothing
+    const JbPair pr = jb_pair(prev_phase, prev_round, g, l, b, nblk);
+    const int pslot = slot ^ 1;
+    if (!pr.valid || chg[pslot * nblk + g] == 0) return;
+    jb_apply_t<T>(Jt, Tring + ((size_t)pslot * nblk + g) * (size_t)(4 * b * b), l, b, pr, j - g * chunks,
+                  reinterpret_cast<T *>(lds_raw));
+    return;
+  }
+  // converged in the previous sweep
+  if (sweep > 0 && __int_as_float(hdr->counters[sweep - 1]) <= rho_last) return;
+  const JbPair pr = jb_pair(phase, round, (int)blockIdx.x, l, b, nblk);
+  if (!pr.valid) return;                                       // bye
+  const int bi = pr.bi, bj = pr.bj, cols_i = pr.cols_i, cols_j = pr.cols_j;
   const int ncols = cols_i + cols_j;
 
-  extern __shared__ __attribute__((aligned(16))) double lds_raw[];
   constexpr int ldp = jb_ldp<T, NV>();
   const int ldt = (2 * b) + 2;
   T *Pc = reinterpret_cast<T *>(lds_raw);
@@ -627,39 +703,20 @@ __global__ __launch_bounds__(1024) void jb_panel_kernel(T *__restrict__ Mt, T *_
   if (rho > 0.f) atomicMax(&rotations, __float_as_int(rho));
   __syncthreads();
   const int rho_bits = rotations;
-  if (rho_bits == 0) return;                                  // nothing changed: leave M and J alone
-
-  panel_out(Mt);
-  // (only LDS is shared between the phases here: wait for this wavefront's LDS traffic, not for
-  // its global stores, before the barrier)
-  lds_barrier();
-  // J[:, panel] <- J[:, panel] T on the matrix cores, the old columns staged through the
-  // LDS space of the panel: an (l x 2b) by (2b x 2b) product in 16 x 16 blocks, K = 2b.
-  panel_in(Jt);
-  __syncthreads();
-  {
-    typedef typename Mfma<T>::vec acc_t;
-    const int r16 = lane64 & 15, kq = lane64 >> 4;
-    const int row_blocks = (l + 15) / 16, col_blocks = (2 * b) / 16;
-    for (int blk = wave; blk < row_blocks * col_blocks; blk += nwave) {
-      const int rb = blk / col_blocks, cb = blk - rb * col_blocks;
-      acc_t acc = (acc_t)(T)0;
-      const T *ap = Pc + kq * ldp + rb * 16 + r16;                  // Jold[row][k]
-      const T *bp = Tc + (cb * 16 + r16) * ldt + kq;                // T[k][col]
-#pragma unroll 4
-      for (int k0 = 0; k0 < 2 * b; k0 += 4) acc = Mfma<T>::run(ap[k0 * ldp], bp[k0], acc);
-      const int cn = cb * 16 + r16;
-      if (cn < ncols) {
-        T *dst = Jt + (int64_t)gcol(cn) * l;
-#pragma unroll
-        for (int v = 0; v < 4; ++v) {
-          const int r = rb * 16 + Mfma<T>::row(lane64, v);
-          if (r < l) dst[r] = acc[v];
-        }
-      }
-    }
+  if (rho_bits == 0) {                                        // nothing changed: leave M alone, no T to apply
+    if (tid == 0) chg[slot * nblk + blockIdx.x] = 0;
+    return;
   }
-  if (tid == 0) atomicMax(&hdr->counters[sweep], rho_bits);
+  panel_out(Mt);
+  T *Tg = Tring + ((size_t)slot * nblk + blockIdx.x) * (size_t)(4 * b * b);
+  for (int idx = tid; idx < 4 * b * b; idx += nt) {
+    const int c = idx / (2 * b), k = idx - c * (2 * b);
+    Tg[idx] = Tc[c * ldt + k];
+  }
+  if (tid == 0) {
+    chg[slot * nblk + blockIdx.x] = 1;
+    atomicMax(&hdr->counters[sweep], rho_bits);
+  }
 }
 
 // Column norms (one wavefront per column), then ranks by counting, then the scatter.
@@ -762,8 +819,10 @@ size_t jacobi_scratch_bytes(const rsvd_ctx *ctx, rsvd_dtype dtype, int64_t l) {
   if (l <= jacobi_max_lds_order(ctx, dtype)) return 0;
   if (jb_block_width(ctx, dtype, l) == 0) return 0;          // unsupported order
   const size_t es = dtype_size(dtype);
+  const size_t b = (size_t)jb_block_width(ctx, dtype, l), nblk = ceil_div((size_t)l, b);
   return align_up(sizeof(JbHeader), 256) + 2 * align_up((size_t)l * l * es, 256) + align_up((size_t)l * es, 256) +
-         align_up((size_t)l * sizeof(int), 256);
+         align_up((size_t)l * sizeof(int), 256) + align_up(2 * nblk * 4 * b * b * es, 256) +
+         align_up(2 * nblk * sizeof(int), 256);
 }
 
 template <typename T>
@@ -777,12 +836,15 @@ static hipError_t jacobi_block_launch(rsvd_ctx *ctx, hipStream_t s, rsvd_dtype d
   T *Mt = reinterpret_cast<T *>(p); p += align_up((size_t)l * l * es, 256);
   T *Jt = reinterpret_cast<T *>(p); p += align_up((size_t)l * l * es, 256);
   T *nrm = reinterpret_cast<T *>(p); p += align_up((size_t)l * es, 256);
-  int *rnk = reinterpret_cast<int *>(p);
+  int *rnk = reinterpret_cast<int *>(p); p += align_up((size_t)l * sizeof(int), 256);
   const int nblk = (l + b - 1) / b;
+  T *Tring = reinterpret_cast<T *>(p); p += align_up((size_t)2 * nblk * 4 * b * b * es, 256);   // [2][nblk][2b][2b]
+  int *chg = reinterpret_cast<int *>(p);                                                        // [2][nblk]
   const int nblk2 = nblk + (nblk & 1);
   const int nv = jb_units_per_lane(dtype, l);
   const size_t ldp = (size_t)32 * nv * (8 / es) + 2;
-  const size_t lds = ((size_t)(2 * b) * ldp + (size_t)(2 * b) * (2 * b + 2)) * es;
+  const size_t lds = ((size_t)(2 * b) * ldp + (size_t)(2 * b) * (2 * b + 2)) * es;   // (covers the J role: 2b x 72)
+  const int chunks = (l + kJbRowChunk - 1) / kJbRowChunk;
   ProfScope ps(ctx, s, PK_JACOBI);
   hipLaunchKernelGGL((jb_init_kernel<T>), dim3(1), dim3(1024), 0, s, M, l, Mt, Jt, hdr);
 #define RSVD_JB_CASE(NVV)                                                                                        \
@@ -794,13 +856,17 @@ static hipError_t jacobi_block_launch(rsvd_ctx *ctx, hipStream_t s, rsvd_dtype d
       (void)hipGetLastError();                                                                                   \
       attr_set = true;                                                                                           \
     }                                                                                                            \
+    int slot = 0, pp = -1, pr = 0, psw = 0, pwgs = 0;          /* the launch before: phase, round, sweep, pairs */ \
+    auto go = [&](int phase, int round, int sweep, int wgs) {                                                    \
+      hipLaunchKernelGGL((jb_panel_kernel<T, NVV>), dim3(wgs + pwgs * chunks), dim3(1024), lds, s, Mt, Jt, l, b, \
+                         nblk, phase, round, sweep, wgs, pp, pr, psw, Tring, chg, slot, hdr);                    \
+      pp = phase; pr = round; psw = sweep; pwgs = wgs; slot ^= 1;                                                \
+    };                                                                                                           \
     for (int sweep = 0; sweep < kJbMaxSweeps; ++sweep) {                                                         \
-      hipLaunchKernelGGL((jb_panel_kernel<T, NVV>), dim3(nblk), dim3(1024), lds, s, Mt, Jt, l, b, nblk, 0, 0,    \
-                         sweep, hdr);                                                                            \
-      for (int round = 0; round < nblk2 - 1; ++round)                                                            \
-        hipLaunchKernelGGL((jb_panel_kernel<T, NVV>), dim3(nblk2 / 2), dim3(1024), lds, s, Mt, Jt, l, b, nblk,   \
-                           1, round, sweep, hdr);                                                                \
+      go(0, 0, sweep, nblk);                                                                                     \
+      for (int round = 0; round < nblk2 - 1; ++round) go(1, round, sweep, nblk2 / 2);                            \
     }                                                                                                            \
+    go(0, 0, kJbMaxSweeps, 0);                                 /* applies the T of the last round */            \
   } break
   switch (nv) {
     RSVD_JB_CASE(2); RSVD_JB_CASE(3); RSVD_JB_CASE(4); RSVD_JB_CASE(5); RSVD_JB_CASE(6); RSVD_JB_CASE(7);
