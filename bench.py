@@ -284,6 +284,23 @@ def main():
     torch.cuda.synchronize()
     per_call = np.array([a.elapsed_time(b) for a, b in evs])
 
+    # supplementary: the same call recorded once as a HIP graph and replayed (what a serving loop would do;
+    # the call allocates nothing and never synchronises when it gets its workspace and no diagnostics)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        step()
+    torch.cuda.synchronize()
+    graph.replay()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        graph.replay()
+    torch.cuda.synchronize()
+    graph_ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    del graph
+
     # second pass over the same steps with HIP events around every kernel launch
     ctx.rsvd_profile_enable(True)
     for _ in range(args.steps):
@@ -317,6 +334,7 @@ def main():
         "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 4),
         "ms_per_step_mean_std_10": [round(float(per_call.mean()), 4), round(float(per_call.std()), 4)],
+        "ms_per_step_graph_replay": round(graph_ms, 4),
         "higher_is_better": False,
         "scaling": "weak",
         "vs_baseline": None,

@@ -106,6 +106,10 @@ int rsvd_workspace_bytes(rsvd_ctx *ctx, rsvd_dtype dtype, int64_t m, int64_t n,
  *   Vt     k x n, leading dimension ldvt >= n  (RSVD_JOB_SV / SUV, else may be NULL)
  *   info   host pointer or NULL.  Non-NULL: the call synchronises `stream`
  *          before returning and the return value includes device-side status.
+ *          NULL: the call only enqueues kernels on `stream` - no allocation,
+ *          no synchronisation, no memset nodes, nothing read from the
+ *          workspace before it is written - so it may be recorded into a HIP
+ *          graph (after one ordinary call of the same shape) and replayed.
  * Requires k >= 1, p >= 0, q >= 0, k + p <= min(m, n).
  * Re-orthonormalisation inside the power scheme (step 2; the algorithm as
  * printed has none, it is there for floating point): after every product by
