@@ -189,7 +189,7 @@ def _svd_check(sig, X, W, M, dt, name):
 
 
 @pytest.mark.parametrize("dt", ["f32", "f64"])
-@pytest.mark.parametrize("l", [2, 5, 20, 33, 64, 80, 96, 128, 129, 160, 288, 576])
+@pytest.mark.parametrize("l", [2, 5, 20, 33, 64, 80, 96, 128, 129, 160, 200, 288, 333, 576])
 def test_jacobi_matches_oracle(dt, l):
     say("jacobi", dt, l)
     M = workloads.gaussian_matrix(l, l, 40 + l, NPDT[dt])
