@@ -269,6 +269,20 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmParams P0) {
     return;
   }
   if (EPI == 1) {
+    // Replacement columns are rare and do not depend on the accumulators: the flags of this lane's TN
+    // columns are read once, the ordinary elements are stored on a short path, and the replacement
+    // values follow in a rolled loop, so that the generator is in the code once (inlined per element
+    // it made the kernel half again as slow, replacement or not).
+    unsigned dead_cols = 0u;
+    if (P.dead != nullptr) {
+#pragma unroll
+      for (int j = 0; j < TN; ++j) {
+        const int64_t col = n0 + wn0 + j * 16 + r16;
+        if (col < P.N && P.dead[col] != 0) dead_cols |= 1u << j;
+      }
+    }
+    TOut *Cp = (TOut *)P.C;
+    const TAcc alpha = (TAcc)P.alpha, beta = (TAcc)P.beta;
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -277,8 +291,27 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmParams P0) {
         for (int v = 0; v < 4; ++v) {
           const int64_t row = m0 + wm0 + i * 16 + Mfma<TAcc>::row(lane, v);
           const int64_t col = n0 + wn0 + j * 16 + r16;
-          if (row < P.M && col < P.N) store_result<TOut, TAcc, sizeof(TIn) == 4>(P, row, col, acc[i][j][v]);
+          if (row < P.M && col < P.N && !((dead_cols >> j) & 1u)) {
+            if (P.trans_c) {
+              Cp[col * P.ldc + row] = (TOut)(alpha * acc[i][j][v]);
+            } else {
+              TOut *dst = Cp + row * P.ldc + col;
+              TAcc val = alpha * acc[i][j][v];
+              if (beta != (TAcc)0) val += beta * (TAcc)(*dst);
+              *dst = (TOut)val;
+            }
+          }
         }
+    if (dead_cols != 0u) {
+#pragma unroll 1
+      for (int e = 0; e < TM * TN * 4; ++e) {
+        const int v = e & 3, j = (e >> 2) % TN, i = (e >> 2) / TN;
+        if (!((dead_cols >> j) & 1u)) continue;
+        const int64_t row = m0 + wm0 + i * 16 + Mfma<TAcc>::row(lane, v);
+        const int64_t col = n0 + wn0 + j * 16 + r16;
+        if (row < P.M && col < P.N) store_result<TOut, TAcc, sizeof(TIn) == 4>(P, row, col, (TAcc)0);
+      }
+    }
   }
   if (EPI == 2) {
     TOut *Cp = (TOut *)P.C;
