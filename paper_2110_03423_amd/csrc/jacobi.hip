@@ -50,11 +50,12 @@ template <typename T> __device__ __forceinline__ T half_row_sum(T v) {
   return v;
 }
 
-// Sum over the G = 4 or 8 lanes that share a column pair.
+// Sum over the G = 4, 8 or 16 lanes that share a column pair (16: the whole DPP row, by row_mirror).
 template <int G, typename T> __device__ __forceinline__ T group_sum(T v) {
   v += dpp_mov<0xB1>(v);
   v += dpp_mov<0x4E>(v);
-  if (G == 8) v += dpp_mov<0x141>(v);
+  if (G >= 8) v += dpp_mov<0x141>(v);
+  if (G == 16) v += dpp_mov<0x140>(v);
   return v;
 }
 
@@ -193,9 +194,13 @@ __device__ __forceinline__ float rotate_moving(jac_unit<T> (&x)[RPL / (8 / (int)
 
 // The stride is chosen so that the columns a half wavefront touches in one access (8 pairs of 4
 // lanes, or 4 pairs of 8) start 8 (16) banks apart: padded rows + 32 bytes for G = 4.
-__host__ __device__ inline int jacobi_rows_padded(int l) { return ((l + 15) / 16) * 16; }
+// Rows are padded to a whole number of 8-byte units per lane of the group (and to 16 at least).
+__host__ __device__ inline int jacobi_rows_padded(int l, int G, int elem_size) {
+  const int step = G * (8 / elem_size) > 16 ? G * (8 / elem_size) : 16;
+  return ((l + step - 1) / step) * step;
+}
 __host__ __device__ inline int jacobi_ldm(int l, int G, int elem_size) {
-  return jacobi_rows_padded(l) + (G == 4 ? 32 / elem_size : 2);
+  return jacobi_rows_padded(l, G, elem_size) + (G == 4 ? 32 / elem_size : 2);
 }
 
 template <typename T, typename TIn, int RPL, int G>
@@ -216,7 +221,7 @@ __global__ __launch_bounds__(64 * G) void jacobi_lds_kernel(const TIn *__restric
   T *nrm = Jc + (size_t)l * ldm;
   int *rnk = reinterpret_cast<int *>(nrm + l);
   __shared__ int rotations;
-  __shared__ T wave_sum[8];
+  __shared__ T wave_sum[16];
   __shared__ JacLevel lev[kJacLevels][kJacGroups];
 
   const int tid = threadIdx.x, nt = blockDim.x;
@@ -776,7 +781,7 @@ constexpr int kJbMaxSweeps = 24;
 // Lanes per column pair of the LDS-resident kernel.
 static int jacobi_group(rsvd_dtype dtype, int64_t l) {
   (void)dtype; (void)l;
-  return 8;        // 4 lanes per pair measured slower at every order
+  return 16;       // measured: 16 beats 8 from l = 20 to 128 (a round is one wavefront's dependent chain), 4 is slowest
 }
 
 static size_t jacobi_lds_bytes(rsvd_dtype dtype, int64_t l) {
@@ -788,7 +793,7 @@ static size_t jacobi_lds_bytes(rsvd_dtype dtype, int64_t l) {
 int jacobi_max_lds_order(const rsvd_ctx *ctx, rsvd_dtype dtype) {
   int l = 2;
   while (l < 128 && jacobi_lds_bytes(dtype, l + 1) + 4096 <= ctx->lds_per_block) ++l;
-  return l;      // 128 = 8 lanes per pair x 16 rows each lane keeps in registers
+  return l;      // 128 columns = 64 pairs x 16 lanes = the largest workgroup
 }
 
 // Units (8 bytes) per lane for order l: ceil(l / V / 32), rounded up to an instantiated value.
@@ -901,6 +906,24 @@ static hipError_t launch_lds(hipStream_t s, int nt, size_t lds, const void *M, i
 template <typename T, typename TIn>
 static hipError_t launch_lds_g(hipStream_t s, int nt, int G, int rpl, size_t lds, const void *M, int l, void *sigma,
                                void *X, void *W, DevInfo *info, int batch, int64_t stride) {
+  if (G == 16) {
+    // fp32 rows come in pairs (8-byte units), fp64 rows singly
+    if constexpr (sizeof(T) == 8) {
+      switch (rpl) {
+        case 1: return launch_lds<T, TIn, 1, 16>(s, nt, lds, M, l, sigma, X, W, info, batch, stride);
+        case 3: return launch_lds<T, TIn, 3, 16>(s, nt, lds, M, l, sigma, X, W, info, batch, stride);
+        case 5: return launch_lds<T, TIn, 5, 16>(s, nt, lds, M, l, sigma, X, W, info, batch, stride);
+        default: break;
+      }
+    }
+    switch (rpl) {
+      case 2: return launch_lds<T, TIn, 2, 16>(s, nt, lds, M, l, sigma, X, W, info, batch, stride);
+      case 4: return launch_lds<T, TIn, 4, 16>(s, nt, lds, M, l, sigma, X, W, info, batch, stride);
+      case 6: return launch_lds<T, TIn, 6, 16>(s, nt, lds, M, l, sigma, X, W, info, batch, stride);
+      case 8: return launch_lds<T, TIn, 8, 16>(s, nt, lds, M, l, sigma, X, W, info, batch, stride);
+      default: return hipErrorNotSupported;
+    }
+  }
   if (G == 8) {
     switch (rpl) {
       case 2: return launch_lds<T, TIn, 2, 8>(s, nt, lds, M, l, sigma, X, W, info, batch, stride);
@@ -945,7 +968,7 @@ hipError_t jacobi_launch(rsvd_ctx *ctx, hipStream_t s, rsvd_dtype dtype, int64_t
   const int G = jacobi_group(dtype, l);
   int nt = (int)align_up((size_t)npairs * G, 64);
   if (nt > 64 * G) nt = 64 * G;
-  const int g = jacobi_rows_padded((int)l) / G;          // rows per lane
+  const int g = jacobi_rows_padded((int)l, G, (int)dtype_size(dtype)) / G;          // rows per lane
   const size_t lds = jacobi_lds_bytes(dtype, l);
   ProfScope ps(ctx, s, PK_JACOBI);
   if (dtype == RSVD_F32) {
