@@ -50,7 +50,7 @@ template <typename T> __device__ __forceinline__ T half_row_sum(T v) {
   return v;
 }
 
-// Sum over the G = 4, 8 or 16 lanes that share a column pair (16: the whole DPP row, by row_mirror).
+// Sum over the G = 4, 8 or 16 lanes that share a column pair (16, the one in use: a whole DPP row).
 template <int G, typename T> __device__ __forceinline__ T group_sum(T v) {
   v += dpp_mov<0xB1>(v);
   v += dpp_mov<0x4E>(v);
@@ -192,15 +192,15 @@ __device__ __forceinline__ float rotate_moving(jac_unit<T> (&x)[RPL / (8 / (int)
   return ratio;
 }
 
-// The stride is chosen so that the columns a half wavefront touches in one access (8 pairs of 4
-// lanes, or 4 pairs of 8) start 8 (16) banks apart: padded rows + 32 bytes for G = 4.
 // Rows are padded to a whole number of 8-byte units per lane of the group (and to 16 at least).
+// Column stride: the 16 lanes of a group read one contiguous run of 128 bytes, i.e. every LDS bank
+// once, whatever the stride; the two extra rows only keep consecutive columns off the same phase.
 __host__ __device__ inline int jacobi_rows_padded(int l, int G, int elem_size) {
   const int step = G * (8 / elem_size) > 16 ? G * (8 / elem_size) : 16;
   return ((l + step - 1) / step) * step;
 }
 __host__ __device__ inline int jacobi_ldm(int l, int G, int elem_size) {
-  return jacobi_rows_padded(l, G, elem_size) + (G == 4 ? 32 / elem_size : 2);
+  return jacobi_rows_padded(l, G, elem_size) + 2;
 }
 
 template <typename T, typename TIn, int RPL, int G>
@@ -924,28 +924,7 @@ static hipError_t launch_lds_g(hipStream_t s, int nt, int G, int rpl, size_t lds
       default: return hipErrorNotSupported;
     }
   }
-  if (G == 8) {
-    switch (rpl) {
-      case 2: return launch_lds<T, TIn, 2, 8>(s, nt, lds, M, l, sigma, X, W, info, batch, stride);
-      case 4: return launch_lds<T, TIn, 4, 8>(s, nt, lds, M, l, sigma, X, W, info, batch, stride);
-      case 6: return launch_lds<T, TIn, 6, 8>(s, nt, lds, M, l, sigma, X, W, info, batch, stride);
-      case 8: return launch_lds<T, TIn, 8, 8>(s, nt, lds, M, l, sigma, X, W, info, batch, stride);
-      case 10: return launch_lds<T, TIn, 10, 8>(s, nt, lds, M, l, sigma, X, W, info, batch, stride);
-      case 12: return launch_lds<T, TIn, 12, 8>(s, nt, lds, M, l, sigma, X, W, info, batch, stride);
-      case 14: return launch_lds<T, TIn, 14, 8>(s, nt, lds, M, l, sigma, X, W, info, batch, stride);
-      default: return launch_lds<T, TIn, 16, 8>(s, nt, lds, M, l, sigma, X, W, info, batch, stride);
-    }
-  }
-  switch (rpl) {
-    case 4: return launch_lds<T, TIn, 4, 4>(s, nt, lds, M, l, sigma, X, W, info, batch, stride);
-    case 8: return launch_lds<T, TIn, 8, 4>(s, nt, lds, M, l, sigma, X, W, info, batch, stride);
-    case 12: return launch_lds<T, TIn, 12, 4>(s, nt, lds, M, l, sigma, X, W, info, batch, stride);
-    case 16: return launch_lds<T, TIn, 16, 4>(s, nt, lds, M, l, sigma, X, W, info, batch, stride);
-    case 20: return launch_lds<T, TIn, 20, 4>(s, nt, lds, M, l, sigma, X, W, info, batch, stride);
-    case 24: return launch_lds<T, TIn, 24, 4>(s, nt, lds, M, l, sigma, X, W, info, batch, stride);
-    case 28: return launch_lds<T, TIn, 28, 4>(s, nt, lds, M, l, sigma, X, W, info, batch, stride);
-    default: return launch_lds<T, TIn, 32, 4>(s, nt, lds, M, l, sigma, X, W, info, batch, stride);
-  }
+  return hipErrorNotSupported;
 }
 
 hipError_t jacobi_launch(rsvd_ctx *ctx, hipStream_t s, rsvd_dtype dtype, int64_t l, const void *M,
