@@ -32,7 +32,7 @@ inline size_t dtype_size(rsvd_dtype d) { return d == RSVD_F32 ? 4 : 8; }
 // Kernel classes reported by the profiling interface.
 enum ProfKind {
   PK_SKETCH = 0, PK_GEMM_AX, PK_GEMM_AX_REDUCE, PK_GEMM_ATX, PK_GEMM_ATX_REDUCE, PK_GRAM, PK_GRAM_REDUCE,
-  PK_CHOL, PK_APPLY, PK_JACOBI, PK_LIFT, PK_SMALL, PK_COUNT      // PK_SMALL also covers the mean / shift vectors of the centred variant
+  PK_CHOL, PK_APPLY, PK_JACOBI, PK_LIFT, PK_SMALL, PK_COUNT      // PK_SMALL also covers the column means of the centred variant
 };
 
 // Brackets one kernel launch with a HIP event pair when profiling is on.

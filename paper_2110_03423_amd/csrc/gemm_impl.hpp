@@ -154,15 +154,15 @@ struct TileStage {
 
 // Epilogues (EPI):
 //   0  the kernel can only store its tile as it is (or as a split-K partial);
-//   1  the full epilogue (scaling, accumulation, rank-one term, transposed store, replacement columns);
+//   1  the full epilogue (scaling, accumulation, transposed store, replacement columns);
 //   2  C = alpha * acc + beta * C only, with all of a thread's old values of C loaded before the
 //      first store (element by element the loads would queue behind the stores, one memory
 //      round trip each);
 //   3  as 0, with the column offsets P.a_shift taken away from A while its tiles are staged
 //      (the centred products: A - 1 mu^T is never formed, and no cancellation happens after
 //      the fact as it would with a rank-one correction of the product).
-// Separate instantiations, because the full epilogue inlines the Philox and Box-Muller code once per
-// accumulator element and the products with A never need it.
+// Separate instantiations: the full epilogue carries the Philox and Box-Muller code and more registers,
+// which the products with A never need.
 template <typename TIn, typename TAcc, typename TOut, bool TA, int BM, int BN, int WGM, int WGN, int VEC, int EPI,
           int BK = 32>
 __global__ __launch_bounds__(256) void gemm_kernel(const GemmParams P0) {
