@@ -409,12 +409,12 @@ __device__ __forceinline__ float rotate_pair_panel(T *Pc, T *Tc, int ldp, int ld
 
 // Cross-phase version: the column of the first block (x, NV units per lane) and its
 // column of T (tx: entries lg and lg + 32) stay in registers for all rounds of the launch;
-// only the column q of the second block and its column of T go through LDS.
+// only the column of the second block (qp: its place in LDS) and its column qt of T go through LDS.
 template <typename T, int NV>
 __device__ __forceinline__ float rotate_moving_panel(jac_unit<T> (&x)[NV], T (&tx)[2], T *Pc, T *Tc, int ldp, int ldt,
-                                                    int rows_t, int q, int lg, T tol, T floor2) {
+                                                    int rows_t, int qp, int qt, int lg, T tol, T floor2) {
   constexpr int V = 8 / sizeof(T);
-  jac_unit<T> *mq = reinterpret_cast<jac_unit<T> *>(Pc + q * ldp) + lg;
+  jac_unit<T> *mq = reinterpret_cast<jac_unit<T> *>(Pc + qp * ldp) + lg;
   jac_unit<T> y[NV];
 #pragma unroll
   for (int r = 0; r < NV; ++r) y[r] = mq[32 * r];
@@ -442,7 +442,7 @@ __device__ __forceinline__ float rotate_moving_panel(jac_unit<T> (&x)[NV], T (&t
     x[r] = c * xo - s * y[r];
     mq[32 * r] = s * xo + c * y[r];
   }
-  T *tq = Tc + q * ldt;
+  T *tq = Tc + qt * ldt;
 #pragma unroll
   for (int j = 0; j < 2; ++j) {
     const int i = lg + 32 * j;
@@ -605,33 +605,37 @@ __global__ __launch_bounds__(1024) void jb_panel_kernel(T *__restrict__ Mt, T *_
 
   constexpr int ldp = jb_ldp<T, NV>();
   const int ldt = (2 * b) + 2;
+  // LDS holds ONE block of columns: the block itself in the diagonal phase, the second ("moving")
+  // block in the cross phase, whose first block lives in registers from global memory to global
+  // memory.
   T *Pc = reinterpret_cast<T *>(lds_raw);
-  T *Tc = Pc + (size_t)(2 * b) * ldp;
+  T *Tc = Pc + (size_t)b * ldp;
   __shared__ int rotations;
+  const int lds_blk = (phase == 0) ? bi : bj;
+  const int lds_cols = (phase == 0) ? cols_i : cols_j;
 
   const int tid = threadIdx.x, nt = blockDim.x;
-  auto gcol = [&](int c) { return c < cols_i ? bi * b + c : bj * b + (c - cols_i); };
   // panel in: a wavefront takes whole columns, two at a time, and issues every load of both
   // before the first LDS store (the loads are the latency to hide)
   constexpr int LPW = (ldp + 63) / 64;      // elements per lane per column
   const int lane64 = tid & 63, wave = tid >> 6, nwave = nt >> 6;
   auto panel_in = [&](const T *__restrict__ G) {
-    for (int c0 = wave; c0 < 2 * b; c0 += 2 * nwave) {
+    for (int c0 = wave; c0 < b; c0 += 2 * nwave) {
       T v[2][LPW];
 #pragma unroll
       for (int u = 0; u < 2; ++u) {
         const int c = c0 + u * nwave;
-        const T *src = G + (int64_t)gcol(c < ncols ? c : 0) * l;
+        const T *src = G + (int64_t)(lds_blk * b + (c < lds_cols ? c : 0)) * l;
 #pragma unroll
         for (int j = 0; j < LPW; ++j) {
           const int r = lane64 + 64 * j;
-          v[u][j] = (c < ncols && r < l) ? src[r] : (T)0;
+          v[u][j] = (c < lds_cols && r < l) ? src[r] : (T)0;
         }
       }
 #pragma unroll
       for (int u = 0; u < 2; ++u) {
         const int c = c0 + u * nwave;
-        if (c < 2 * b) {
+        if (c < b) {
 #pragma unroll
           for (int j = 0; j < LPW; ++j) {
             const int r = lane64 + 64 * j;
@@ -642,8 +646,8 @@ __global__ __launch_bounds__(1024) void jb_panel_kernel(T *__restrict__ Mt, T *_
     }
   };
   auto panel_out = [&](T *__restrict__ G) {
-    for (int c = wave; c < ncols; c += nwave) {
-      T *dst = G + (int64_t)gcol(c) * l;
+    for (int c = wave; c < lds_cols; c += nwave) {
+      T *dst = G + (int64_t)(lds_blk * b + c) * l;
 #pragma unroll
       for (int j = 0; j < LPW; ++j) {
         const int r = lane64 + 64 * j;
@@ -657,11 +661,29 @@ __global__ __launch_bounds__(1024) void jb_panel_kernel(T *__restrict__ Mt, T *_
     Tc[idx] = (r == c && c < ncols) ? (T)1 : (T)0;
   }
   if (tid == 0) rotations = 0;
-  __syncthreads();
 
   const T floor2 = (T)(Eps<T>::value * Eps<T>::value * hdr->fro2);
   const int group = tid >> 5, lg = tid & 31;                   // 32 groups of 32 lanes, b <= 32
+  constexpr int V = 8 / (int)sizeof(T);
   float rho = 0.f;
+  // cross phase: lane group g keeps column g of the first block (and its column of T) for all b rounds
+  const bool act = phase != 0 && group < cols_i;
+  jac_unit<T> x[NV];
+  T tx[2] = {(T)0, (T)0};
+  if (act) {
+    const T *src = Mt + (int64_t)(bi * b + group) * l;
+#pragma unroll
+    for (int r = 0; r < NV; ++r)
+#pragma unroll
+      for (int e = 0; e < V; ++e) {
+        const int row = (lg + 32 * r) * V + e;
+        x[r][e] = row < l ? src[row] : (T)0;
+      }
+#pragma unroll
+    for (int j = 0; j < 2; ++j) tx[j] = (lg + 32 * j == group) ? (T)1 : (T)0;     // column `group` of the identity
+  }
+  __syncthreads();
+
   if (phase == 0) {
     const int n2 = ncols + (ncols & 1);
     for (int r = 0; r < n2 - 1; ++r) {
@@ -676,29 +698,14 @@ __global__ __launch_bounds__(1024) void jb_panel_kernel(T *__restrict__ Mt, T *_
       __syncthreads();
     }
   } else {
-    // lane group g keeps column g of the first block (and its column of T) for all b rounds
-    const bool act = group < cols_i;
-    jac_unit<T> x[NV];
-    T tx[2] = {(T)0, (T)0};
-    if (act) {
-      const jac_unit<T> *mp = reinterpret_cast<const jac_unit<T> *>(Pc + group * ldp) + lg;
-#pragma unroll
-      for (int r = 0; r < NV; ++r) x[r] = mp[32 * r];
-#pragma unroll
-      for (int j = 0; j < 2; ++j)
-        if (lg + 32 * j < ncols) tx[j] = Tc[group * ldt + lg + 32 * j];
-    }
     for (int r = 0; r < b; ++r) {
       int qi = group + r;
       if (qi >= b) qi -= b;
       if (act && qi < cols_j)
-        rho = fmaxf(rho, rotate_moving_panel<T, NV>(x, tx, Pc, Tc, ldp, ldt, ncols, cols_i + qi, lg, tol, floor2));
+        rho = fmaxf(rho, rotate_moving_panel<T, NV>(x, tx, Pc, Tc, ldp, ldt, ncols, qi, cols_i + qi, lg, tol, floor2));
       __syncthreads();
     }
     if (act) {
-      jac_unit<T> *mp = reinterpret_cast<jac_unit<T> *>(Pc + group * ldp) + lg;
-#pragma unroll
-      for (int r = 0; r < NV; ++r) mp[32 * r] = x[r];
 #pragma unroll
       for (int j = 0; j < 2; ++j)
         if (lg + 32 * j < ncols) Tc[group * ldt + lg + 32 * j] = tx[j];
@@ -713,6 +720,16 @@ __global__ __launch_bounds__(1024) void jb_panel_kernel(T *__restrict__ Mt, T *_
     return;
   }
   panel_out(Mt);
+  if (act) {
+    T *dst = Mt + (int64_t)(bi * b + group) * l;
+#pragma unroll
+    for (int r = 0; r < NV; ++r)
+#pragma unroll
+      for (int e = 0; e < V; ++e) {
+        const int row = (lg + 32 * r) * V + e;
+        if (row < l) dst[row] = x[r][e];
+      }
+  }
   T *Tg = Tring + ((size_t)slot * nblk + blockIdx.x) * (size_t)(4 * b * b);
   for (int idx = tid; idx < 4 * b * b; idx += nt) {
     const int c = idx / (2 * b), k = idx - c * (2 * b);
@@ -806,14 +823,16 @@ static int jb_units_per_lane(rsvd_dtype dtype, int64_t l) {
   return 0;
 }
 
-// block width for the panel kernel: 2b padded columns plus T must fit in LDS
+// block width for the panel kernel: b padded columns plus the 2b x 2b T must fit in LDS
 static int jb_block_width(const rsvd_ctx *ctx, rsvd_dtype dtype, int64_t l) {
   const size_t es = dtype_size(dtype);
   const int nv = jb_units_per_lane(dtype, l);
   if (nv == 0) return 0;
   const size_t ldp = (size_t)32 * nv * (8 / es) + 2;
-  for (int b = 32; b >= 8; b -= 8) {      // (16 and 24 measured alike at l = 288 and 576, 8 slower)
-    const size_t need = ((size_t)(2 * b) * ldp + (size_t)(2 * b) * (2 * b + 2)) * es + 1024;
+  // Measured from l = 130 to 576 in both precisions: 16 beats 24 and 32 (a round is bound by instruction issue,
+  // so fewer wavefronts per SIMD make it shorter, which outweighs the larger number of launches), 8 is slower.
+  for (int b = 16; b >= 8; b -= 8) {
+    const size_t need = ((size_t)b * ldp + (size_t)(2 * b) * (2 * b + 2)) * es + 1024;   // one block of columns + T
     if (need <= ctx->lds_per_block) return b;
   }
   return 0;
@@ -848,7 +867,9 @@ static hipError_t jacobi_block_launch(rsvd_ctx *ctx, hipStream_t s, rsvd_dtype d
   const int nblk2 = nblk + (nblk & 1);
   const int nv = jb_units_per_lane(dtype, l);
   const size_t ldp = (size_t)32 * nv * (8 / es) + 2;
-  const size_t lds = ((size_t)(2 * b) * ldp + (size_t)(2 * b) * (2 * b + 2)) * es;   // (covers the J role: 2b x 72)
+  const size_t lds_rot = ((size_t)b * ldp + (size_t)(2 * b) * (2 * b + 2)) * es;
+  const size_t lds_j = ((size_t)(2 * b) * (kJbRowChunk + 8) + (size_t)(2 * b) * (2 * b + 2)) * es;   // jb_apply_t
+  const size_t lds = lds_rot > lds_j ? lds_rot : lds_j;
   const int chunks = (l + kJbRowChunk - 1) / kJbRowChunk;
   ProfScope ps(ctx, s, PK_JACOBI);
   hipLaunchKernelGGL((jb_init_kernel<T>), dim3(1), dim3(1024), 0, s, M, l, Mt, Jt, hdr);
