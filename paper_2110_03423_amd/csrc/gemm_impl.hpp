@@ -380,11 +380,13 @@ struct TileChoice {
 };
 
 // Tile shapes instantiated below (see the dispatch switch).
-inline TileChoice choose_tile(int64_t M, int64_t N, int64_t K, size_t acc_size, bool trans_a) {
+inline TileChoice choose_tile(int64_t M, int64_t N, int64_t K, size_t acc_size, bool trans_a, bool upper = false) {
   TileChoice t;
   if (N <= 128) {
     t.bm = 64;
     t.bn = (int)(ceil_div(N, 16) * 16);
+    // symmetric result wider than 96: two column tiles, so that the tile under the diagonal can be skipped
+    if (upper && N > 96) t.bn = 64;
   } else if (acc_size == 8) {
     // fp64 accumulators: the 64-row tile with one wavefront per 16 rows keeps the register
     // count low enough for two workgroups per CU
@@ -504,7 +506,7 @@ struct GemmDispatch {
     const TileChoice t = choose_tile(M, N, K, sizeof(TAcc), trans_a);
     SplitChoice c = choose_split(ctx, t, M, N, K, 0);
     if (M == N) {                  // a symmetric (upper-only) product of this shape may split further
-      const SplitChoice cu = choose_split(ctx, t, M, N, K, 0, true);
+      const SplitChoice cu = choose_split(ctx, choose_tile(M, N, K, sizeof(TAcc), trans_a, true), M, N, K, 0, true);
       if (cu.splits > c.splits) c = cu;
     }
     return c.splits > 1 ? (size_t)c.splits * (size_t)M * (size_t)N * sizeof(TAcc) : 0;
@@ -512,7 +514,7 @@ struct GemmDispatch {
 
   static hipError_t launch(rsvd_ctx *ctx, hipStream_t s, const GemmDesc &d) {
     if (d.M <= 0 || d.N <= 0) return hipSuccess;
-    const TileChoice t = choose_tile(d.M, d.N, d.K, sizeof(TAcc), d.trans_a != 0);
+    const TileChoice t = choose_tile(d.M, d.N, d.K, sizeof(TAcc), d.trans_a != 0, d.upper_only != 0);
     if (d.batch < 1 || d.batch > 65535) return hipErrorInvalidValue;
     SplitChoice c = choose_split(ctx, t, d.M, d.N, d.K, d.force_splits, d.upper_only != 0, d.batch);
     if (c.splits > 1) {

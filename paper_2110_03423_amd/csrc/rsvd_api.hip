@@ -235,7 +235,7 @@ static int orthonormalize(rsvd_ctx *ctx, hipStream_t s, rsvd_dtype dtype, const 
     g.prof_kind = PK_GRAM;
     g.batch = w.batch; g.stride_a = g.stride_b = g.stride_c = g.stride_partial = w.stride;
     g.skip_flag = skip_flag; g.stride_flag = w.stride;
-    g.upper_only = (l > chol_max_block(ctx)) ? 1 : 0;   // the blocked factorisation reads the upper triangle only
+    g.upper_only = (l > 96) ? 1 : 0;   // both factorisations read the upper block triangle only; below that one tile covers G
     // small orders: the Cholesky kernel adds the split-K partials itself
     int splits = 1;
     g.skip_reduce = (l <= chol_max_block(ctx)) ? 1 : 0;
