@@ -44,6 +44,7 @@ struct GemmParams {
   //   *skip_flag != 0: the launch does nothing;  *alt_flag != 0: B_alt takes the place of B
   const int *skip_flag; const int *alt_flag; const void *B_alt; int64_t stride_flag;
   int skip_now;             // filled in on the device
+  int reduce_groups;        // split-K reduction: threads per output element (1, 2, 4 or 8)
 };
 
 // The parameters of problem blockIdx.y of a batched launch.
@@ -347,29 +348,48 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmParams P0) {
   }
 }
 
+// Sum of the split-K partials.  SG (1, 2, 4 or 8, P.reduce_groups) threads share one element: thread
+// group g adds the partials g, g + SG, g + 2 SG, ... (eight loads in flight each), and the SG sums are
+// added in the order g = 0, 1, ... through LDS - a fixed order for a given launch, so the result stays
+// bitwise reproducible.  A small output with many partials (a Gram matrix of a tall panel) otherwise
+// has too few threads to keep the memory system busy.
 template <typename TIn, typename TAcc, typename TOut>
 __global__ __launch_bounds__(256) void splitk_reduce_kernel(const GemmParams P0) {
   const GemmParams P = select_problem(P0);
   if (P.skip_now) return;
+  __shared__ TAcc part[256];
   const int64_t total = P.M * P.N;
-  for (int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; e < total;
-       e += (int64_t)gridDim.x * blockDim.x) {
+  const int SG = P.reduce_groups;
+  const int EB = 256 / SG;                       // elements per workgroup and pass
+  const int g = (int)threadIdx.x / EB, el = (int)threadIdx.x - g * EB;
+  for (int64_t base = (int64_t)blockIdx.x * EB; base < total; base += (int64_t)gridDim.x * EB) {
+    const int64_t e = base + el;
     const int64_t row = e / P.N;
     const int64_t col = e - row * P.N;
-    if (P.upper_bm > 0 && (col / P.upper_bn + 1) * P.upper_bn <= (row / P.upper_bm) * P.upper_bm) continue;
-    const TAcc *p = (const TAcc *)P.partial + e;
+    const bool live = e < total &&
+                      !(P.upper_bm > 0 && (col / P.upper_bn + 1) * P.upper_bn <= (row / P.upper_bm) * P.upper_bm);
     TAcc sum = (TAcc)0;
-    // eight loads in flight per step; the additions keep their fixed order
-    int s = 0;
-    for (; s + 8 <= P.splits; s += 8) {
-      TAcc v[8];
+    if (live) {
+      const TAcc *p = (const TAcc *)P.partial + e;
+      int sp = g;
+      for (; sp + 7 * SG < P.splits; sp += 8 * SG) {
+        TAcc v[8];
 #pragma unroll
-      for (int u = 0; u < 8; ++u) v[u] = p[(int64_t)(s + u) * total];
+        for (int u = 0; u < 8; ++u) v[u] = p[(int64_t)(sp + u * SG) * total];
 #pragma unroll
-      for (int u = 0; u < 8; ++u) sum += v[u];
+        for (int u = 0; u < 8; ++u) sum += v[u];
+      }
+      for (; sp < P.splits; sp += SG) sum += p[(int64_t)sp * total];
     }
-    for (; s < P.splits; ++s) sum += p[(int64_t)s * total];
-    store_result<TOut, TAcc, sizeof(TIn) == 4>(P, row, col, sum);
+    if (SG > 1) {
+      part[threadIdx.x] = sum;
+      __syncthreads();
+      if (g == 0) {
+        for (int h = 1; h < SG; ++h) sum += part[h * EB + el];
+      }
+      __syncthreads();
+    }
+    if (live && g == 0) store_result<TOut, TAcc, sizeof(TIn) == 4>(P, row, col, sum);
   }
 }
 
@@ -537,6 +557,7 @@ struct GemmDispatch {
     P.stride_a = d.stride_a; P.stride_b = d.stride_b; P.stride_c = d.stride_c; P.stride_partial = d.stride_partial;
     P.stride_dead = d.stride_dead; P.seed_step = d.seed_step;
     P.skip_flag = d.skip_flag; P.alt_flag = d.alt_flag; P.B_alt = d.B_alt; P.stride_flag = d.stride_flag; P.skip_now = 0;
+    P.reduce_groups = 1;
     // 16-byte vector loads need aligned bases, leading dimensions and extents.
     constexpr int V = 16 / sizeof(TIn);
     const int64_t a_contig = d.trans_a ? d.M : d.K;
@@ -553,7 +574,11 @@ struct GemmDispatch {
     if (d.splits_out != nullptr) *d.splits_out = c.splits;
     if (c.splits > 1 && !(d.skip_reduce && c.splits <= d.skip_reduce_max)) {
       ProfScope ps(ctx, s, d.prof_kind + 1);
-      int64_t blocks = ceil_div(d.M * d.N, 256);
+      // threads per element: enough of them to put ~64k loads in flight, at least eight partials each
+      int sg = 1;
+      while (sg < 8 && d.M * d.N * d.batch * sg < 65536 && c.splits >= 16 * sg) sg *= 2;
+      P.reduce_groups = sg;
+      int64_t blocks = ceil_div(d.M * d.N, 256 / sg);
       if (blocks > 8192) blocks = 8192;
       hipLaunchKernelGGL((splitk_reduce_kernel<TIn, TAcc, TOut>), dim3((unsigned)blocks, (unsigned)d.batch), dim3(256),
                          0, s, P);
