@@ -53,7 +53,8 @@ typedef enum {
   RSVD_ERR_NONFINITE = 1,   /* a Gram matrix held a non-finite entry (non-finite input) */
   RSVD_ERR_NO_CONVERGENCE = 2, /* Jacobi did not converge within the sweep cap */
   RSVD_ERR_HIP = 3,         /* a HIP runtime call failed; see rsvd_last_hip_error */
-  RSVD_ERR_UNSUPPORTED = 4  /* shape outside what the kernels support (l too large) */
+  RSVD_ERR_UNSUPPORTED = 4, /* shape outside what the kernels support (l too large) */
+  RSVD_ERR_NO_DEVICE = 5    /* the context was created with RSVD_DEVICE_NONE: it can size and check, not run */
 } rsvd_status;
 
 /* Diagnostics written by rsvd_run / stage calls when the caller asks for them
@@ -74,7 +75,13 @@ typedef struct {
 } rsvd_info;
 
 /* Create / destroy a context bound to HIP device `device`.  Host-side only:
- * queries device properties, allocates nothing on the device. */
+ * queries device properties, allocates nothing on the device.
+ * device = RSVD_DEVICE_NONE gives a planning context that makes no HIP call at
+ * all (a scheduler or a build machine without a GPU can size workspaces and
+ * validate arguments with it): the workspace queries answer for an MI355X,
+ * every other call checks its arguments as usual and then returns
+ * RSVD_ERR_NO_DEVICE instead of launching. */
+#define RSVD_DEVICE_NONE (-1)
 int rsvd_create(rsvd_ctx **ctx, int device);
 int rsvd_destroy(rsvd_ctx *ctx);
 

@@ -5,4 +5,4 @@ in include/rsvd.h; this package only marshals arguments.  PyTorch provides the
 device memory and the stream.
 """
 from .binding import (Rsvd, RsvdError, library_path, load_library, F32, F64,  # noqa: F401
-                      JOB_S, JOB_SV, JOB_SUV)
+                      JOB_S, JOB_SV, JOB_SUV, DEVICE_NONE)

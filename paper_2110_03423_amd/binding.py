@@ -3,6 +3,8 @@ import ctypes as C
 import os
 
 F32, F64 = 0, 1
+DEVICE_NONE = -1        # rsvd_create: planning context, no HIP call
+ERR_NO_DEVICE = 5
 JOB_S, JOB_SV, JOB_SUV = 0, 1, 2
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
@@ -91,14 +93,23 @@ class Rsvd:
     """One context per device.  Methods mirror the C entry points by name."""
 
     def __init__(self, device=0):
-        import torch
-        self.torch = torch
+        """device=None gives a planning context (RSVD_DEVICE_NONE): workspace sizes and argument checks only,
+        no GPU and no torch needed."""
         self.lib = load_library()
-        self.device = torch.device("cuda", device)
-        h = C.c_void_p()
-        self._check(self.lib.rsvd_create(C.byref(h), device))
-        self.h = h
         self._ws = None
+        h = C.c_void_p()
+        if device is None:
+            self.torch = None
+            self.device = None
+            rc = self.lib.rsvd_create(C.byref(h), DEVICE_NONE)
+        else:
+            import torch
+            self.torch = torch
+            self.device = torch.device("cuda", device)
+            rc = self.lib.rsvd_create(C.byref(h), device)
+        if rc != 0:
+            raise RsvdError(rc, "rsvd_create failed (no such device?)")
+        self.h = h
 
     def close(self):
         if getattr(self, "h", None):

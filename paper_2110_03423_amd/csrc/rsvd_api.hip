@@ -330,8 +330,15 @@ extern "C" {
 int rsvd_create(rsvd_ctx **out, int device) {
   if (out == nullptr) return -1;
   *out = nullptr;
+  // RSVD_DEVICE_NONE: a planning context with the MI355X's figures, touching no HIP call
   hipDeviceProp_t prop;
-  if (hipGetDeviceProperties(&prop, device) != hipSuccess) return -2;
+  memset(&prop, 0, sizeof(prop));
+  if (device == RSVD_DEVICE_NONE) {
+    prop.multiProcessorCount = 256;
+    prop.sharedMemPerBlock = 160 * 1024;
+  } else if (device < 0 || hipGetDeviceProperties(&prop, device) != hipSuccess) {
+    return -2;
+  }
   rsvd_ctx *c = new (std::nothrow) rsvd_ctx;
   if (c == nullptr) return RSVD_ERR_HIP;
   c->device = device;
@@ -364,6 +371,7 @@ const char *rsvd_status_string(int code) {
     case RSVD_ERR_NO_CONVERGENCE: return "Jacobi SVD did not converge within the sweep cap";
     case RSVD_ERR_HIP: return "HIP runtime error";
     case RSVD_ERR_UNSUPPORTED: return "problem shape not supported";
+    case RSVD_ERR_NO_DEVICE: return "planning context (RSVD_DEVICE_NONE): arguments are valid, nothing was launched";
     default: return code < 0 ? "invalid argument" : "unknown status";
   }
 }
@@ -454,6 +462,7 @@ static int run_impl(rsvd_ctx *ctx, void *stream, rsvd_dtype dtype, rsvd_job job,
   if (l > jacobi_max_lds_order(ctx, dtype) && jacobi_scratch_bytes(ctx, dtype, l) == 0) return RSVD_ERR_UNSUPPORTED;
   if (batch > 1 && (l > jacobi_max_lds_order(ctx, dtype) || l > chol_max_block(ctx) || center))
     return RSVD_ERR_UNSUPPORTED;
+  if (ctx->device < 0) return RSVD_ERR_NO_DEVICE;
   hipStream_t s = (hipStream_t)stream;
   const Layout &L = w.L;
   void *bM0 = w.at<void>(L.bufM[0]), *bM1 = w.at<void>(L.bufM[1]);
@@ -607,6 +616,7 @@ int rsvd_stage_sketch(rsvd_ctx *ctx, void *stream, rsvd_dtype dtype, uint64_t se
   if (rows * cols == 0) return 0;
   if (Omega == nullptr) return -8;
   if (ldo < cols) return -9;
+  if (ctx->device < 0) return RSVD_ERR_NO_DEVICE;
   RSVD_TRY(sketch_launch((hipStream_t)stream, dtype, seed, stream_id, rows, cols, Omega, ldo), "sketch");
   return 0;
 }
@@ -617,6 +627,7 @@ int rsvd_stage_philox_raw(rsvd_ctx *ctx, void *stream, uint64_t seed, uint32_t s
   if (n_groups < 0) return -6;
   if (n_groups == 0) return 0;
   if (out == nullptr) return -7;
+  if (ctx->device < 0) return RSVD_ERR_NO_DEVICE;
   RSVD_TRY(philox_raw_launch((hipStream_t)stream, seed, stream_id, first_group, n_groups, out), "philox");
   return 0;
 }
@@ -640,6 +651,7 @@ static int stage_gemm(rsvd_ctx *ctx, void *stream, rsvd_dtype dtype, int trans_a
   w.base = (char *)workspace;
   if (workspace == nullptr || ((uintptr_t)workspace & 255) != 0) return -13;
   if (workspace_bytes < w.L.total) return -14;
+  if (ctx->device < 0) return RSVD_ERR_NO_DEVICE;
   if (trans_a) return product(ctx, (hipStream_t)stream, dtype, w, 1, n, l, m, A, lda, X, ldx, Y, ldy, 0, true, PK_GEMM_ATX);
   return product(ctx, (hipStream_t)stream, dtype, w, 0, m, l, n, A, lda, X, ldx, Y, ldy, 0, true, PK_GEMM_AX);
 }
@@ -670,6 +682,7 @@ int rsvd_stage_orth(rsvd_ctx *ctx, void *stream, rsvd_dtype dtype, int64_t rows,
   w.base = (char *)workspace;
   if (workspace == nullptr || ((uintptr_t)workspace & 255) != 0) return -11;
   if (workspace_bytes < w.L.total) return -12;
+  if (ctx->device < 0) return RSVD_ERR_NO_DEVICE;
   hipStream_t s = (hipStream_t)stream;
   RSVD_TRY(zero_ints_launch(s, w.at<int>(w.L.info), 4), "zero info");
   int rc = orthonormalize(ctx, s, dtype, w, rows, l, Y, ldy, w.at<void>(w.L.bufM[1]),
@@ -698,6 +711,7 @@ int rsvd_stage_small_svd(rsvd_ctx *ctx, void *stream, rsvd_dtype dtype, int64_t 
   if (workspace == nullptr || ((uintptr_t)workspace & 255) != 0) return -13;
   if (workspace_bytes < w.L.total) return -14;
   if (l > jacobi_max_lds_order(ctx, dtype) && jacobi_scratch_bytes(ctx, dtype, l) == 0) return RSVD_ERR_UNSUPPORTED;
+  if (ctx->device < 0) return RSVD_ERR_NO_DEVICE;
   hipStream_t s = (hipStream_t)stream;
   RSVD_TRY(zero_ints_launch(s, w.at<int>(w.L.info), 4), "zero info");
   int rc = small_svd(ctx, s, dtype, w, n, l, Bt, ldbt, w.at<void>(w.L.bufN[1]), seed, 16u);
@@ -722,6 +736,7 @@ int rsvd_stage_jacobi(rsvd_ctx *ctx, void *stream, rsvd_dtype dtype, int64_t l, 
   w.base = (char *)workspace;
   if (workspace == nullptr || ((uintptr_t)workspace & 255) != 0) return -9;
   if (workspace_bytes < w.L.total) return -10;
+  if (ctx->device < 0) return RSVD_ERR_NO_DEVICE;
   hipStream_t s = (hipStream_t)stream;
   RSVD_TRY(zero_ints_launch(s, w.at<int>(w.L.info), 4), "zero info");
   const void *Min = M;
@@ -754,6 +769,7 @@ int rsvd_stage_lift(rsvd_ctx *ctx, void *stream, rsvd_dtype dtype, int64_t m, in
   if (ldw < k) return -10;
   if (U == nullptr) return -11;
   if (ldu < (transpose_out ? m : k)) return -12;
+  if (ctx->device < 0) return RSVD_ERR_NO_DEVICE;
   Ws w;
   w.base = nullptr;
   memset(&w.L, 0, sizeof(w.L));
