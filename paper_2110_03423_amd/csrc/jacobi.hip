@@ -527,13 +527,14 @@ __device__ __forceinline__ JbPair jb_pair(int phase, int round, int g, int l, in
   return p;
 }
 
-constexpr int kJbRowChunk = 64;
+constexpr int kJbRowChunk = 64;      // one row per lane of a wavefront when the chunk is staged (jb_apply_t)
 
 // J[rows of chunk, panel] <- J[rows of chunk, panel] T for block pair `pr`: the old entries staged
 // through LDS, a (64 x 2b) by (2b x 2b) product in 16 x 16 blocks.
 template <typename T>
 __device__ __forceinline__ void jb_apply_t(T *__restrict__ Jt, const T *__restrict__ Tg, int l, int b, const JbPair &pr,
                                            int chunk, T *lds) {
+  static_assert(kJbRowChunk == 64, "the staging loop below moves one row per lane of a wavefront");
   constexpr int LDJ = kJbRowChunk + 8;
   const int ldt = 2 * b + 2;
   T *Pj = lds;                       // [2b][LDJ]: Pj[k][i] = J[i0 + i][panel column k]
