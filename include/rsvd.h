@@ -69,7 +69,7 @@ typedef struct {
                               earlier columns is below ~1e-6 of its norm (the
                               resolution of a Gram matrix held in fp64), so a
                               non-zero count also says that directions of A
-                              weaker than ~1e-7 sigma_1 were not resolved */
+                              weaker than ~1e-6 sigma_1 were not resolved */
   int32_t skipped_reorth;   /* 1: the condition estimate of the first panel let the power scheme drop one of
                              * its two re-orthonormalisations per iteration (see rsvd_run); else 0 */
 } rsvd_info;
