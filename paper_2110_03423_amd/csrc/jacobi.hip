@@ -168,9 +168,9 @@ __device__ __forceinline__ float rotate_moving(jac_unit<T> (&x)[RPL / (8 / (int)
   beta = group_sum<G>(beta);
   gamma = group_sum<G>(gamma);
   if (alpha <= floor2 || beta <= floor2) return 0.f;
-  const T limit = tol * fast_sqrt(alpha * beta);
-  if (!(fabs(gamma) > limit)) return 0.f;
-  const float ratio = (float)(fabs(gamma) * fast_rsq(alpha * beta));
+  const T rel = fabs(gamma) * fast_rsq(alpha * beta);          // |x.y| / (|x| |y|)
+  if (!(rel > tol)) return 0.f;
+  const float ratio = (float)rel;
   jac_unit<T> v[NV];
   load_column<T, RPL, G>(Jc + q * ldm, lg, v);
   T c, s;
@@ -388,9 +388,9 @@ __device__ __forceinline__ float rotate_pair_panel(T *Pc, T *Tc, int ldp, int ld
   beta = group32_sum(beta);
   gamma = group32_sum(gamma);
   if (alpha <= floor2 || beta <= floor2) return 0.f;
-  const T limit = tol * fast_sqrt(alpha * beta);
-  if (!(fabs(gamma) > limit)) return 0.f;
-  const float ratio = (float)(fabs(gamma) * fast_rsq(alpha * beta));
+  const T rel = fabs(gamma) * fast_rsq(alpha * beta);          // |x.y| / (|x| |y|)
+  if (!(rel > tol)) return 0.f;
+  const float ratio = (float)rel;
   T c, s;
   rotation_params(alpha, beta, gamma, c, s);
 #pragma unroll
@@ -431,9 +431,9 @@ __device__ __forceinline__ float rotate_moving_panel(jac_unit<T> (&x)[NV], T (&t
   beta = group32_sum(beta);
   gamma = group32_sum(gamma);
   if (alpha <= floor2 || beta <= floor2) return 0.f;
-  const T limit = tol * fast_sqrt(alpha * beta);
-  if (!(fabs(gamma) > limit)) return 0.f;
-  const float ratio = (float)(fabs(gamma) * fast_rsq(alpha * beta));
+  const T rel = fabs(gamma) * fast_rsq(alpha * beta);          // |x.y| / (|x| |y|)
+  if (!(rel > tol)) return 0.f;
+  const float ratio = (float)rel;
   T c, s;
   rotation_params(alpha, beta, gamma, c, s);
 #pragma unroll
