@@ -168,7 +168,7 @@ __device__ __forceinline__ float rotate_moving(jac_unit<T> (&x)[RPL / (8 / (int)
   beta = group_sum<G>(beta);
   gamma = group_sum<G>(gamma);
   if (alpha <= floor2 || beta <= floor2) return 0.f;
-  const T rel = fabs(gamma) * fast_rsq(alpha * beta);          // |x.y| / (|x| |y|)
+  const T rel = fabs(gamma) * fast_rsq(alpha * beta);        // |x.y| / (|x| |y|); the matrix was scaled to unit size
   if (!(rel > tol)) return 0.f;
   const float ratio = (float)rel;
   jac_unit<T> v[NV];
@@ -261,6 +261,18 @@ __global__ __launch_bounds__(64 * G) void jacobi_lds_kernel(const TIn *__restric
   __syncthreads();
   fro2 = 0;
   for (int w = 0; w < (nt >> 6); ++w) fro2 += wave_sum[w];
+  // Scale M by a power of two to ||M||_F ~ 1 (exact; undone when sigma is written): products of squared
+  // column norms then stay inside the range of the type whatever the scale of the input.
+  T unscale = (T)1;
+  if (fro2 > (T)0 && fro2 < (T)3e38) {
+    int ex;
+    (void)frexp((double)fro2, &ex);                       // fro2 = f 2^ex, 1/2 <= f < 1
+    const T sc = (T)ldexp(1.0, -(ex / 2));
+    unscale = (T)ldexp(1.0, ex / 2);
+    for (int idx = tid; idx < l * ldm; idx += nt) Mc[idx] *= sc;
+    fro2 *= sc * sc;
+    __syncthreads();
+  }
   const T floor2 = Eps<T>::value * Eps<T>::value * fro2;
 
   const int group = tid / G, lg = tid % G;       // G lanes per column pair
@@ -320,7 +332,7 @@ __global__ __launch_bounds__(64 * G) void jacobi_lds_kernel(const TIn *__restric
       rank += (o > mine || (o == mine && i < j)) ? 1 : 0;
     }
     rnk[j] = rank;
-    sigma[rank] = mine;
+    sigma[rank] = mine * unscale;
   }
   __syncthreads();
   for (int idx = tid; idx < l * l; idx += nt) {
@@ -388,7 +400,7 @@ __device__ __forceinline__ float rotate_pair_panel(T *Pc, T *Tc, int ldp, int ld
   beta = group32_sum(beta);
   gamma = group32_sum(gamma);
   if (alpha <= floor2 || beta <= floor2) return 0.f;
-  const T rel = fabs(gamma) * fast_rsq(alpha * beta);          // |x.y| / (|x| |y|)
+  const T rel = fabs(gamma) * fast_rsq(alpha * beta);        // |x.y| / (|x| |y|); the matrix was scaled to unit size
   if (!(rel > tol)) return 0.f;
   const float ratio = (float)rel;
   T c, s;
@@ -431,7 +443,7 @@ __device__ __forceinline__ float rotate_moving_panel(jac_unit<T> (&x)[NV], T (&t
   beta = group32_sum(beta);
   gamma = group32_sum(gamma);
   if (alpha <= floor2 || beta <= floor2) return 0.f;
-  const T rel = fabs(gamma) * fast_rsq(alpha * beta);          // |x.y| / (|x| |y|)
+  const T rel = fabs(gamma) * fast_rsq(alpha * beta);        // |x.y| / (|x| |y|); the matrix was scaled to unit size
   if (!(rel > tol)) return 0.f;
   const float ratio = (float)rel;
   T c, s;
@@ -456,34 +468,58 @@ __device__ __forceinline__ float rotate_moving_panel(jac_unit<T> (&x)[NV], T (&t
 }
 
 // scratch header shared by the block-Jacobi kernels
+constexpr int kJbFroParts = 64;
 struct JbHeader {
-  double fro2;            // ||M||_F^2
+  double fro2;            // ||M||_F^2 of the scaled matrix
+  double unscale;         // the singular values of M are those of the scaled matrix times this
   int counters[64];       // per outer sweep: bit pattern of the largest relative inner product rotated away
+  double partial[kJbFroParts];   // sums of squares, one per workgroup of jb_fro_kernel
 };
 
-template <typename T>
-__global__ __launch_bounds__(1024) void jb_init_kernel(const double *__restrict__ M, int l, T *__restrict__ Mt,
-                                                       T *__restrict__ Jt, JbHeader *hdr) {
-  __shared__ double wave_sum[16];
-  const int tid = threadIdx.x, nt = blockDim.x;
-  double fro2 = 0;
-  for (int64_t idx = tid; idx < (int64_t)l * l; idx += nt) {
-    const int r = (int)(idx / l), c = (int)(idx - (int64_t)r * l);
-    const T v = (T)M[idx];
-    Mt[(int64_t)c * l + r] = v;
-    Jt[idx] = (r == c) ? (T)1 : (T)0;
-    fro2 += (double)v * (double)v;
+// ||M||_F^2 in kJbFroParts partial sums (fixed assignment of elements and fixed order: reproducible).
+__global__ __launch_bounds__(256) void jb_fro_kernel(const double *__restrict__ M, int l, JbHeader *hdr) {
+  __shared__ double wave_sum[4];
+  const int tid = threadIdx.x;
+  double s2 = 0;
+  for (int64_t idx = (int64_t)blockIdx.x * 256 + tid; idx < (int64_t)l * l; idx += (int64_t)kJbFroParts * 256) {
+    const double v = M[idx];
+    s2 += v * v;
   }
 #pragma unroll
-  for (int off = 32; off > 0; off >>= 1) fro2 += __shfl_xor(fro2, off, 64);
-  if ((tid & 63) == 0) wave_sum[tid >> 6] = fro2;
+  for (int off = 32; off > 0; off >>= 1) s2 += __shfl_xor(s2, off, 64);
+  if ((tid & 63) == 0) wave_sum[tid >> 6] = s2;
   __syncthreads();
-  if (tid == 0) {
-    double t = 0;
-    for (int w = 0; w < (nt >> 6); ++w) t += wave_sum[w];
-    hdr->fro2 = t;
+  if (tid == 0) hdr->partial[blockIdx.x] = (wave_sum[0] + wave_sum[1]) + (wave_sum[2] + wave_sum[3]);
+}
+
+// Mt = (sc M)^T in the working type, Jt = I, with sc the power of two that brings ||M||_F to ~1 (exact, undone
+// when the singular values are written): products of squared column norms then stay inside the range of
+// the type whatever the scale of the input.  Grid of workgroups, each taking a slab of elements.
+template <typename T>
+__global__ __launch_bounds__(256) void jb_init_kernel(const double *__restrict__ M, int l, T *__restrict__ Mt,
+                                                      T *__restrict__ Jt, JbHeader *hdr) {
+  double fro2 = 0;
+  for (int i = 0; i < kJbFroParts; ++i) fro2 += hdr->partial[i];
+  double sc = 1.0, unscale = 1.0;
+  if (fro2 > 0.0 && fro2 <= 1.79e308) {
+    int ex;
+    (void)frexp(fro2, &ex);
+    sc = ldexp(1.0, -(ex / 2));
+    unscale = ldexp(1.0, ex / 2);
   }
-  if (tid < 64) hdr->counters[tid] = 0;
+  for (int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; idx < (int64_t)l * l;
+       idx += (int64_t)gridDim.x * blockDim.x) {
+    const int r = (int)(idx / l), c = (int)(idx - (int64_t)r * l);
+    Mt[(int64_t)c * l + r] = (T)(M[idx] * sc);
+    Jt[idx] = (r == c) ? (T)1 : (T)0;
+  }
+  if (blockIdx.x == 0) {
+    if (threadIdx.x < 64) hdr->counters[threadIdx.x] = 0;
+    if (threadIdx.x == 0) {
+      hdr->fro2 = fro2 * sc * sc;
+      hdr->unscale = unscale;
+    }
+  }
 }
 
 // Padded column length (elements) of the panel layout: 32 lanes x NV units.
@@ -767,7 +803,7 @@ __global__ __launch_bounds__(256) void jb_rank_kernel(const T *__restrict__ nrm,
       rank += (o > mine || (o == mine && i < j)) ? 1 : 0;
     }
     rnk[j] = rank;
-    sigma[rank] = mine;
+    sigma[rank] = mine * (T)hdr->unscale;
   }
   if (j == 0 && info != nullptr) {
     const float rho_last = 0.25f * sqrtf((float)(Eps<T>::value * sqrt((T)l)));
@@ -873,7 +909,12 @@ static hipError_t jacobi_block_launch(rsvd_ctx *ctx, hipStream_t s, rsvd_dtype d
   const size_t lds = lds_rot > lds_j ? lds_rot : lds_j;
   const int chunks = (l + kJbRowChunk - 1) / kJbRowChunk;
   ProfScope ps(ctx, s, PK_JACOBI);
-  hipLaunchKernelGGL((jb_init_kernel<T>), dim3(1), dim3(1024), 0, s, M, l, Mt, Jt, hdr);
+  hipLaunchKernelGGL(jb_fro_kernel, dim3(kJbFroParts), dim3(256), 0, s, M, l, hdr);
+  {
+    int64_t blocks = ((int64_t)l * l + 255) / 256;
+    if (blocks > 1024) blocks = 1024;
+    hipLaunchKernelGGL((jb_init_kernel<T>), dim3((unsigned)blocks), dim3(256), 0, s, M, l, Mt, Jt, hdr);
+  }
 #define RSVD_JB_CASE(NVV)                                                                                        \
   case NVV: {                                                                                                    \
     static bool attr_set = false;                                                                                \

@@ -231,6 +231,27 @@ def test_centered_variant_with_dominant_means(dt, m, n, k, p, q, scale):
     assert err_g <= 1.01 * err_o + 50 * eps * np.linalg.norm(Ac)
 
 
+@pytest.mark.parametrize("m,n,k,p", [(800, 300, 20, 10), (900, 500, 150, 10)])     # LDS-resident and block Jacobi
+@pytest.mark.parametrize("e", [40, -40])
+def test_input_scale_does_not_matter_in_fp32(m, n, k, p, e):
+    """A scaled by 2^e (exactly): singular values scale by 2^e, vectors stay.  Products of two squared column
+    norms of the small factor leave the fp32 range at these scales (sigma^4 ~ 1e+-54); the Jacobi kernels must
+    not form them."""
+    say("scale", m, n, k, p, e)
+    cfg = scaled(CONFIGS[2], m, n, k=k, p=p)
+    A = workloads.build(cfg)
+    S0, U0, Vt0, info0 = ctx().rsvd_run(to_dev(A), k, p, 1, seed=3)
+    S1, U1, Vt1, info1 = ctx().rsvd_run(to_dev(np.ldexp(A, e).astype(np.float32)), k, p, 1, seed=3)
+    assert info0.status == 0 and info1.status == 0
+    assert info1.jacobi_sweeps == info0.jacobi_sweeps
+    S0, U0, Vt0, S1, U1, Vt1 = (to_np(t).astype(np.float64) for t in (S0, U0, Vt0, S1, U1, Vt1))
+    np.testing.assert_allclose(np.ldexp(S1, -e), S0, rtol=1e-5)
+    ns = int(parity.significant(S0, "f32", m, n).sum())
+    assert parity.orthonormality(U1[:, :ns]) <= parity.jacobi_tol(k + p, "f32")
+    assert parity.orthonormality(Vt1[:ns].T) <= parity.jacobi_tol(k + p, "f32")
+    assert np.abs(np.abs(np.sum(U0[:, :5] * U1[:, :5], axis=0)) - 1).max() <= 1e-3
+
+
 @pytest.mark.parametrize("m,n,q,expect", [
     (6000, 300, 3, 1),      # tall, q = 3: the m-side factorisations inside the power scheme are dropped
     (300, 6000, 2, 1),      # wide: the n-side ones
