@@ -369,6 +369,113 @@ static hipError_t launch_block(hipStream_t s, const double *G, int64_t ldg, int 
   return hipGetLastError();
 }
 
+// Blocks of X = R^-1 above the diagonal blocks, given R (upper triangular, l x l) and the inverted diagonal
+// blocks X_jj (nb x nb, nb = 16 * NW) already in place in X.  Column c of X depends on nothing but R and the
+// X_ii: block row i of a column is  X_i = -X_ii (R[i, i+1 ..] X[i+1 .., c]),  from the diagonal block upwards.  So
+// one workgroup takes a strip of 16 columns through the whole back substitution with the strip in LDS, every
+// strip at once - one launch where a blocked forward scheme needs two small products per block column, each
+// waiting for the one before.  Wavefront w owns rows 16 w .. 16 w + 15 of the block row in hand.
+//   LDS: the strip ((rows up to the end of its diagonal block) x 17), one block row of products (nb x 17) and
+//   a chunk of R (nb x 34).
+template <int NW>
+__global__ __launch_bounds__(64 * NW) void tri_inverse_strip_kernel(const double *__restrict__ R,
+                                                                    double *__restrict__ X, int l,
+                                                                    const int *skip_flag) {
+  if (skip_flag != nullptr && *skip_flag != 0) return;
+  constexpr int nb = 16 * NW, LDS_ = 17;
+  const int c0 = (int)blockIdx.x * 16;
+  const int j = c0 / nb, j0 = j * nb;
+  if (j == 0) return;                                   // the first block column is its diagonal block
+  const int kend = (j0 + nb < l) ? j0 + nb : l;         // rows of the strip that the diagonal block supplies end here
+  extern __shared__ double tri_smem[];
+  double *Xs = tri_smem;                                // [kend][17]
+  double *Ts = Xs + (size_t)kend * LDS_;                // [nb][17]
+  constexpr int CK = 32, RLD = CK + 2;                  // chunk of R: nb rows x CK columns, padded rows
+  constexpr int PER = (nb * (CK / 2) + 64 * NW - 1) / (64 * NW);   // pairs of elements per thread and chunk
+  double *Rs = Ts + (size_t)nb * LDS_;                  // [nb][RLD]
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  const int r16 = lane & 15, kq = lane >> 4;
+  for (int idx = tid; idx < (kend - j0) * 16; idx += 64 * NW) {
+    const int r = j0 + idx / 16, c = idx % 16;
+    Xs[r * LDS_ + c] = (c0 + c < l) ? X[(int64_t)r * l + c0 + c] : 0.0;
+  }
+  __syncthreads();
+  for (int i = j - 1; i >= 0; --i) {
+    const int i0 = i * nb;
+    // operands of the second product (row 16 w + r16 of X_ii, columns 16 w ..): independent of everything this
+    // kernel computes, so they travel while the first product runs
+    constexpr int NX = nb / 4;
+    double xv[NX];
+    {
+      const double *Xrow = X + (int64_t)(i0 + 16 * w + r16) * l + i0;
+#pragma unroll
+      for (int u = 0; u < NX; ++u) {
+        const int k = 16 * w + 4 * u + kq;
+        xv[u] = (k < nb) ? Xrow[k] : 0.0;
+      }
+    }
+    // Ts = R[i0 : i0 + nb, i0 + nb : kend] Xs[i0 + nb : kend, :], the block row of R staged through LDS in
+    // chunks of CK columns with coalesced loads (a lane fetching its own row of R touches sixteen cache lines
+    // per instruction, and that, not the arithmetic, was the whole cost of a first version)
+    {
+      f64x4 acc = {0.0, 0.0, 0.0, 0.0};
+      double stage[2 * PER];
+      auto fetch = [&](int kk) {
+#pragma unroll
+        for (int t = 0; t < PER; ++t) {
+          const int e = tid + 64 * NW * t;                  // pair of columns e % (CK / 2) of row e / (CK / 2)
+          const int row = e / (CK / 2), k = kk + 2 * (e % (CK / 2));
+          const double *src = R + (int64_t)(i0 + row) * l + k;
+          stage[2 * t] = (row < nb && k < kend) ? src[0] : 0.0;
+          stage[2 * t + 1] = (row < nb && k + 1 < kend) ? src[1] : 0.0;
+        }
+      };
+      fetch(i0 + nb);
+      for (int kk = i0 + nb; kk < kend; kk += CK) {
+#pragma unroll
+        for (int t = 0; t < PER; ++t) {
+          const int e = tid + 64 * NW * t;
+          const int row = e / (CK / 2), c = 2 * (e % (CK / 2));
+          if (row < nb) {
+            Rs[row * RLD + c] = stage[2 * t];
+            Rs[row * RLD + c + 1] = stage[2 * t + 1];
+          }
+        }
+        __syncthreads();
+        if (kk + CK < kend) fetch(kk + CK);
+#pragma unroll
+        for (int u = 0; u < CK / 4; ++u) {
+          const int k = kk + 4 * u + kq;
+          const double bv = (k < kend) ? Xs[k * LDS_ + r16] : 0.0;
+          acc = Mfma<double>::run(Rs[(16 * w + r16) * RLD + 4 * u + kq], bv, acc);
+        }
+        __syncthreads();
+      }
+#pragma unroll
+      for (int v = 0; v < 4; ++v) Ts[(16 * w + Mfma<double>::row(lane, v)) * LDS_ + r16] = acc[v];
+    }
+    __syncthreads();
+    // Xs[i0 : i0 + nb, :] = -X_ii Ts   (X_ii is upper triangular: columns from this row block on; its operands
+    // were fetched before the product above)
+    {
+      f64x4 acc = {0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+      for (int u = 0; u < NX; ++u) {
+        const int k = 16 * w + 4 * u + kq;
+        const double bv = (k < nb) ? Ts[k * LDS_ + r16] : 0.0;
+        acc = Mfma<double>::run(xv[u], bv, acc);
+      }
+#pragma unroll
+      for (int v = 0; v < 4; ++v) Xs[(i0 + 16 * w + Mfma<double>::row(lane, v)) * LDS_ + r16] = -acc[v];
+    }
+    __syncthreads();
+  }
+  for (int idx = tid; idx < j0 * 16; idx += 64 * NW) {
+    const int r = idx / 16, c = idx % 16;
+    if (c0 + c < l) X[(int64_t)r * l + c0 + c] = Xs[r * LDS_ + c];
+  }
+}
+
 hipError_t chol_inverse_launch(rsvd_ctx *ctx, hipStream_t s, rsvd_dtype out_dtype, int64_t l, double *G,
                                int64_t ldg, int n_parts, int64_t part_stride, double tau, void *Rinv, double *R,
                                int *dead, DevInfo *info, double *scratch, int batch, int64_t stride,
@@ -389,6 +496,10 @@ hipError_t chol_inverse_launch(rsvd_ctx *ctx, hipStream_t s, rsvd_dtype out_dtyp
   // Blocked right-looking factorisation; diagonal blocks by the kernel above,
   // panels and trailing updates by the fp64 GEMM.  Rf/Xf hold R and R^-1 in fp64.
   const int nb = 96 <= nbmax ? 96 : nbmax;
+  // R^-1 above the diagonal blocks: one strip kernel after the factorisation when its strip fits in LDS
+  // (l up to ~1000), else two products per block column inside the loop
+  const size_t strip_lds = ((size_t)(l + nb) * 17 + (size_t)nb * 34) * sizeof(double);
+  const bool strips = nb == 96 && strip_lds + 4096 <= (size_t)ctx->lds_per_block;
   double *g0 = scratch;
   double *Xf = g0 + ((l + 1) & ~(int64_t)1);
   double *Rf = Xf + l * l;
@@ -428,7 +539,7 @@ hipError_t chol_inverse_launch(rsvd_ctx *ctx, hipStream_t s, rsvd_dtype out_dtyp
       t.skip_flag = skip_flag;
       if ((e = gemm_launch_f64(ctx, s, t)) != hipSuccess) return e;
     }
-    if (j0 > 0) {
+    if (j0 > 0 && !strips) {
       // inverse, block column j: X[0:j0, j] = -X[0:j0, 0:j0] (R[0:j0, j] X_jj)
       GemmDesc a;
       a.M = j0; a.N = b; a.K = b;
@@ -443,6 +554,19 @@ hipError_t chol_inverse_launch(rsvd_ctx *ctx, hipStream_t s, rsvd_dtype out_dtyp
       c.C = Xf + j0; c.ldc = l; c.alpha = -1.0; c.force_splits = 1; c.skip_flag = skip_flag;
       if ((e = gemm_launch_f64(ctx, s, c)) != hipSuccess) return e;
     }
+  }
+  if (strips) {
+    static bool attr_set = false;
+    if (!attr_set) {
+      (void)hipFuncSetAttribute(reinterpret_cast<const void *>(&tri_inverse_strip_kernel<6>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 4096);
+      (void)hipGetLastError();
+      attr_set = true;
+    }
+    ProfScope ps(ctx, s, PK_SMALL);
+    hipLaunchKernelGGL((tri_inverse_strip_kernel<6>), dim3((unsigned)ceil_div(l, 16)), dim3(384), strip_lds, s, Rf, Xf,
+                       (int)l, skip_flag);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
   }
   if (out_dtype == RSVD_F32) {
     hipLaunchKernelGGL((convert_matrix_kernel<float>), dim3(512), dim3(256), 0, s, Xf, l * l, (float *)Rinv);
