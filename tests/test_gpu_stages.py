@@ -124,7 +124,7 @@ def test_lift(dt, m, l, k, tr):
 @pytest.mark.parametrize("dt", ["f32", "f64"])
 @pytest.mark.parametrize("rows,l,cond", [(512, 20, 10.0), (3000, 80, 1e3), (1000, 120, 50.0), (129, 33, 5.0),
                                          (10000, 64, 1e2), (2000, 160, 30.0), (3000, 288, 1e2), (5000, 576, 10.0),
-                                         (1500, 200, 1e3)])
+                                         (1500, 200, 1e3), (2500, 900, 10.0)])     # 900: past the strip inverse's LDS limit
 def test_orth_full_rank_matches_householder(dt, rows, l, cond):
     say("orth", dt, rows, l, cond)
     Y = workloads.graded_matrix(rows, l, cond, seed=20, dtype=NPDT[dt])
