@@ -136,3 +136,23 @@ def test_batched_rejects_what_it_cannot_do():
     with pytest.raises(RsvdError) as e:
         c.rsvd_run_batched(A, 8, 8, 1, workspace=ws[:4096])   # workspace too small
     assert e.value.code == -24
+
+
+def test_a_non_finite_problem_does_not_touch_its_neighbours():
+    """One matrix of the batch holds a NaN: the call reports it, the other problems come out as they do alone."""
+    import torch
+    say("batched: one poisoned problem")
+    c = ctx()
+    A = np.stack([workloads.gaussian_matrix(400, 150, 60 + b, np.float32) for b in range(3)])
+    clean = c.rsvd_run_batched(torch.from_numpy(A).to("cuda:0"), 10, 20, 2, seed=5)
+    assert clean[3].status == 0
+    A[1, 3, 3] = np.nan
+    Ad = torch.from_numpy(A).to("cuda:0")
+    from paper_2110_03423_amd import RsvdError
+    with pytest.raises(RsvdError) as err:
+        c.rsvd_run_batched(Ad, 10, 20, 2, seed=5)
+    assert err.value.code == 1
+    S, U, Vt, _ = c.rsvd_run_batched(Ad, 10, 20, 2, seed=5, want_info=False)
+    torch.cuda.synchronize()
+    for b in (0, 2):
+        assert torch.equal(S[b], clean[0][b]) and torch.equal(U[b], clean[1][b]) and torch.equal(Vt[b], clean[2][b])

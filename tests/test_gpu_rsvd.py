@@ -280,3 +280,64 @@ def test_ill_conditioned_panel_keeps_the_full_schedule():
     A1 = workloads.build(cfg1)
     _, _, _, info = ctx().rsvd_run(to_dev(A1), cfg1.k, cfg1.p, 2, seed=0)
     assert info.skipped_reorth == 0 and info.refilled_columns > 0
+
+
+@pytest.mark.parametrize("dt", ["f32", "f64"])
+def test_degenerate_inputs(dt):
+    """Zero and constant matrices, a single row, a single column, 1 x 1: finite outputs, the singular values of the
+    textbook answer, orthonormal left vectors; nothing hangs and nothing is flagged."""
+    say("degenerate", dt)
+    T = np.float32 if dt == "f32" else np.float64
+    eps = parity.EPS[dt]
+    c = ctx()
+
+    def run(A, k, p, q):
+        S, U, Vt, info = c.rsvd_run(to_dev(np.ascontiguousarray(A.astype(T))), k, p, q, seed=1)
+        S, U, Vt = (to_np(t).astype(np.float64) for t in (S, U, Vt))
+        assert info.status == 0
+        assert np.isfinite(S).all() and np.isfinite(U).all() and np.isfinite(Vt).all()
+        return S, U, Vt, info
+
+    S, U, Vt, info = run(np.zeros((300, 200)), 5, 5, 2)
+    assert (S == 0).all() and info.refilled_columns > 0
+    assert parity.orthonormality(U) <= 50 * eps                    # arbitrary, but orthonormal
+    S, U, Vt, _ = run(np.full((300, 200), 3.0), 4, 4, 1)
+    assert S[0] == pytest.approx(3.0 * np.sqrt(300 * 200), rel=20 * eps) and (S[1:] <= 1e3 * eps * S[0]).all()
+    assert np.abs(np.abs(U[:, 0]) - 1 / np.sqrt(300)).max() <= 50 * eps
+    x = workloads.gaussian_matrix(500, 1, 5)
+    S, U, Vt, _ = run(x, 1, 0, 2)                                  # one column
+    assert S[0] == pytest.approx(np.linalg.norm(x.astype(T).astype(np.float64)), rel=20 * eps)
+    assert abs(abs(Vt[0, 0]) - 1) <= 10 * eps
+    S, U, Vt, _ = run(x.T, 1, 0, 2)                                # one row
+    assert S[0] == pytest.approx(np.linalg.norm(x.astype(T).astype(np.float64)), rel=20 * eps)
+    assert abs(abs(U[0, 0]) - 1) <= 10 * eps
+    S, U, Vt, _ = run(np.array([[-2.5]]), 1, 0, 3)
+    assert S[0] == pytest.approx(2.5, rel=10 * eps) and U[0, 0] * Vt[0, 0] == pytest.approx(-1.0, rel=10 * eps)
+
+
+def test_two_contexts_on_two_streams():
+    """Calls on different contexts, workspaces and streams may overlap in time: each gives, bit for bit, what it
+    gives alone."""
+    import torch
+    from paper_2110_03423_amd import Rsvd, F32
+    say("two streams")
+    cfgs = [scaled(CONFIGS[2], 6000, 1500, k=48, p=16), scaled(CONFIGS[5], 3000, 1400, k=150, p=10)]
+    As = [to_dev(workloads.build(cf)) for cf in cfgs]
+    alone = []
+    for A, cf in zip(As, cfgs):
+        S, U, Vt, info = ctx().rsvd_run(A, cf.k, cf.p, 2, seed=7)
+        assert info.status == 0
+        alone.append([t.clone() for t in (S, U, Vt)])
+    ctxs = [Rsvd(0), Rsvd(0)]
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    wss = [torch.empty(c.workspace_bytes(F32, cf.m, cf.n, cf.k, cf.p), dtype=torch.uint8, device="cuda:0")
+           for c, cf in zip(ctxs, cfgs)]
+    torch.cuda.synchronize()
+    for rep in range(3):
+        res = []
+        for c, st, ws, A, cf in zip(ctxs, streams, wss, As, cfgs):
+            with torch.cuda.stream(st):
+                res.append(c.rsvd_run(A, cf.k, cf.p, 2, seed=7, workspace=ws, want_info=False))
+        torch.cuda.synchronize()
+        for got, want in zip(res, alone):
+            assert all(torch.equal(g, w) for g, w in zip(got[:3], want)), f"repetition {rep}"
