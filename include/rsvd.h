@@ -74,8 +74,10 @@ typedef struct {
                              * its two re-orthonormalisations per iteration (see rsvd_run); else 0 */
 } rsvd_info;
 
-/* Create / destroy a context bound to HIP device `device`.  Host-side only:
- * queries device properties, allocates nothing on the device.
+/* Create / destroy a context for HIP device `device`.  Host-side only:
+ * queries device properties, allocates nothing on the device.  The calls
+ * below launch on the caller's stream and never switch devices: that device
+ * must be the current one when they are made.
  * device = RSVD_DEVICE_NONE gives a planning context that makes no HIP call at
  * all (a scheduler or a build machine without a GPU can size workspaces and
  * validate arguments with it): the workspace queries answer for an MI355X,
