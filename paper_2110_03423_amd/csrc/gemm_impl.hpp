@@ -393,6 +393,39 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const GemmParams P0)
   }
 }
 
+// Plain sum of the partials (no scaling, no replacement columns, no transposition, full matrix), sixteen bytes
+// of accumulator type per thread: the reduction of the products with A, which is pure memory traffic.
+template <typename TAcc, typename TOut>
+__global__ __launch_bounds__(256) void splitk_reduce_plain_kernel(const GemmParams P0) {
+  const GemmParams P = select_problem(P0);
+  if (P.skip_now) return;
+  constexpr int V = 16 / sizeof(TAcc);
+  static_assert(sizeof(TAcc) == sizeof(TOut), "same width in and out");
+  typedef TAcc vacc __attribute__((ext_vector_type(V)));
+  typedef TOut vout __attribute__((ext_vector_type(V)));
+  const int64_t total = P.M * P.N, groups = total / V;
+  for (int64_t gi = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; gi < groups; gi += (int64_t)gridDim.x * blockDim.x) {
+    const int64_t e = gi * V;
+    const int64_t row = e / P.N, col = e - row * P.N;
+    const vacc *p = reinterpret_cast<const vacc *>((const TAcc *)P.partial + e);
+    const int64_t step = total / V;
+    vacc sum = (vacc)(TAcc)0;
+    int sp = 0;
+    for (; sp + 4 <= P.splits; sp += 4) {
+      vacc v[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) v[u] = p[(int64_t)(sp + u) * step];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) sum += v[u];
+    }
+    for (; sp < P.splits; ++sp) sum += p[(int64_t)sp * step];
+    vout o;
+#pragma unroll
+    for (int u = 0; u < V; ++u) o[u] = (TOut)sum[u];
+    *reinterpret_cast<vout *>((TOut *)P.C + row * P.ldc + col) = o;
+  }
+}
+
 // ---------------------------------------------------------------- host side
 
 struct TileChoice {
@@ -471,6 +504,13 @@ inline SplitChoice choose_split(const rsvd_ctx *ctx, const TileChoice &t, int64_
   c.splits = (int)ceil_div(K, c.k_per_split);
   if (c.splits < 1) c.splits = 1;
   return c;
+}
+
+template <typename TAcc, typename TOut>
+inline void launch_plain_reduce(hipStream_t s, const GemmParams &P, unsigned blocks, unsigned batch) {
+  if constexpr (sizeof(TAcc) == sizeof(TOut)) {
+    hipLaunchKernelGGL((splitk_reduce_plain_kernel<TAcc, TOut>), dim3(blocks, batch), dim3(256), 0, s, P);
+  }
 }
 
 template <typename TIn, typename TAcc, typename TOut>
@@ -574,6 +614,18 @@ struct GemmDispatch {
     if (d.splits_out != nullptr) *d.splits_out = c.splits;
     if (c.splits > 1 && !(d.skip_reduce && c.splits <= d.skip_reduce_max)) {
       ProfScope ps(ctx, s, d.prof_kind + 1);
+      constexpr int V16 = 16 / sizeof(TAcc);
+      const bool plain = sizeof(TAcc) == sizeof(TOut) && d.alpha == 1.0 && d.beta == 0.0 && d.dead == nullptr &&
+                         !d.trans_c && !d.upper_only && d.N % V16 == 0 && d.ldc % V16 == 0 &&
+                         (uintptr_t)d.C % 16 == 0 && (uintptr_t)d.partial % 16 == 0 &&
+                         (d.batch == 1 || (d.stride_c % 16 == 0 && d.stride_partial % 16 == 0)) &&
+                         d.M * d.N >= 262144;       // (smaller outputs do better with one element per thread)
+      if (plain) {
+        int64_t blocks = ceil_div(d.M * d.N / V16, 256);
+        if (blocks > 8192) blocks = 8192;
+        launch_plain_reduce<TAcc, TOut>(s, P, (unsigned)blocks, (unsigned)d.batch);
+        return hipGetLastError();
+      }
       // threads per element: enough of them to put ~64k loads in flight, at least eight partials each
       int sg = 1;
       while (sg < 8 && d.M * d.N * d.batch * sg < 65536 && c.splits >= 16 * sg) sg *= 2;
