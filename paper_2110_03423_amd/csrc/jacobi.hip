@@ -246,13 +246,22 @@ __global__ __launch_bounds__(64 * G) void jacobi_lds_kernel(const TIn *__restric
     }
   }
   T fro2 = 0;
-  for (int idx = tid; idx < l * ldm; idx += nt) {
-    const int c = idx / ldm, r = idx - c * ldm;
-    T v = (T)0;
-    if (r < l) v = (T)M[r * l + c];
-    Mc[idx] = v;
-    Jc[idx] = (r == c) ? (T)1 : (T)0;
-    fro2 += v * v;
+  {
+    // M is row-major in global memory and column-major in LDS: consecutive threads take consecutive elements
+    // of a row (one cache line per 16 or 8 of them); the padding rows of the columns are cleared apart
+    const int pad = ldm - l;
+    for (int idx = tid; idx < l * pad; idx += nt) {
+      const int c = idx / pad, r = l + (idx - c * pad);
+      Mc[c * ldm + r] = (T)0;
+      Jc[c * ldm + r] = (T)0;
+    }
+    for (int idx = tid; idx < l * l; idx += nt) {
+      const int r = idx / l, c = idx - r * l;
+      const T v = (T)M[idx];
+      Mc[c * ldm + r] = v;
+      Jc[c * ldm + r] = (r == c) ? (T)1 : (T)0;
+      fro2 += v * v;
+    }
   }
 #pragma unroll
   for (int off = 32; off > 0; off >>= 1) fro2 += __shfl_xor(fro2, off, 64);
