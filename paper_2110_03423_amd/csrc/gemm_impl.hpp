@@ -488,11 +488,12 @@ inline SplitChoice choose_split(const rsvd_ctx *ctx, const TileChoice &t, int64_
     // Aim at four workgroups per CU (measured better than two from l = 16, where the kernels are HBM
     // bound and need the loads in flight, to l = 576), rounded to the nearest factor so that a grid
     // that nearly fills the chip is left alone.  Every split pays a prologue and a tile-sized
-    // partial store: at least 4 k-tiles per split for the 64-row tiles, 8 for the larger ones.
+    // partial store: at least 4 k-tiles per split for the 64-row tiles (2 for a small Gram matrix, whose few
+    // workgroups are bound by the chain of dependent loads, one per k-tile), 8 for the larger ones.
     const int64_t want = 4 * (int64_t)ctx->cu_count;
     tiles *= batch;                  // a batch fills the chip with fewer splits per problem
     if (tiles < want) s = (want + tiles / 2) / tiles;
-    const int64_t min_k = (t.bm * t.bn > 64 * 128) ? 8 : 4;
+    const int64_t min_k = (t.bm * t.bn > 64 * 128) ? 8 : (M == N && M <= 128 ? 2 : 4);
     const int64_t max_by_k = ktiles / min_k > 0 ? ktiles / min_k : 1;
     if (s > max_by_k) s = max_by_k;
     if (s > 256) s = 256;
