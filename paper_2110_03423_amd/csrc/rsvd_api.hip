@@ -222,8 +222,16 @@ static int orthonormalize(rsvd_ctx *ctx, hipStream_t s, rsvd_dtype dtype, const 
   const GemmKind kind = dtype == RSVD_F32 ? GEMM_F32 : GEMM_F64;
   const GemmKind gram = dtype == RSVD_F32 ? GEMM_F32_ACC64 : GEMM_F64;
   const Layout &L = w.L;
-  // pivot threshold: rounding level of the fp64 Gram matrix and its elimination
-  const double tau = 32.0 * 2.220446049250313e-16 * ((double)l + sqrt((double)rows));
+  // pivot threshold (on squared norms): the rounding level of the fp64 Gram matrix and its elimination - and, for
+  // fp32 panels, the rounding level of the panel itself: a column that is a product in fp32 carries noise of
+  // ~1e-6 of its norm, and what is left of it below that after the earlier columns is that noise, not a
+  // direction.  Kept as one, it is blown up by 1e6 in the triangular solve, and a second round no longer brings
+  // the basis to working precision (seen as a reconstruction error of 400 eps on an exactly rank-deficient input).
+  double tau = 32.0 * 2.220446049250313e-16 * ((double)l + sqrt((double)rows));
+  if (dtype == RSVD_F32) {
+    const double rel = 32.0 * 1.1920929e-07;           // 3.8e-6 of the column norm
+    if (rel * rel > tau) tau = rel * rel;
+  }
   void *src = Y; int64_t lds_ = ldy;
   void *dst = tmp; int64_t ldd = l;
   for (int round = 0; round < rounds; ++round) {
