@@ -81,20 +81,17 @@ __device__ __forceinline__ double fast_sqrt(double x) { return x * fast_rsq(x); 
 
 // Rotation (c, s) that orthogonalises two columns with squared norms alpha, beta
 // and inner product gamma != 0:  zeta = (beta - alpha) / (2 gamma),
-// t = sign(zeta) / (|zeta| + sqrt(1 + zeta^2)), c = 1 / sqrt(1 + t^2), s = c t  (the textbook form).
-// The same rotation without forming zeta or t: with d = beta - alpha, g = 2 gamma and w = 1 / sqrt(d^2 + g^2),
-//   c^2 = (1 + |d| w) / 2,   s = sign(d) g w / (2 c)
-// (two reciprocal square roots on the serial path of a pair instead of two reciprocals, a square root and a
-// reciprocal square root; no cancellation for small angles, where s -> gamma / (beta - alpha)).
+// t = sign(zeta) / (|zeta| + sqrt(1 + zeta^2)), c = 1 / sqrt(1 + t^2), s = c t.
 template <typename T>
 __device__ __forceinline__ void rotation_params(T alpha, T beta, T gamma, T &c, T &s) {
-  const T d = beta - alpha, g = (T)2 * gamma;
-  const T w = fast_rsq(d * d + g * g);
-  const T x = (T)0.5 + (T)0.5 * fabs(d) * w;          // c^2
-  const T q = fast_rsq(x);
-  c = x * q;
-  const T h = (T)0.5 * g * w * q;
-  s = d < (T)0 ? -h : h;
+  const T zeta = (beta - alpha) * fast_rcp((T)2 * gamma);
+  const T az = fabs(zeta);
+  T t;
+  if (az > (T)1e7) t = (T)0.5 * fast_rcp(az);                   // avoids overflow of zeta^2
+  else t = fast_rcp(az + fast_sqrt((T)1 + zeta * zeta));
+  t = zeta < (T)0 ? -t : t;
+  c = fast_rsq((T)1 + t * t);
+  s = c * t;
 }
 
 // Pair i of round r in a tournament of n2 (even) players: player n2-1 stays,
