@@ -199,6 +199,10 @@ def test_jacobi_matches_oracle(dt, l):
     assert info.status == 0 and 1 <= info.jacobi_sweeps <= 20
     M64 = M.astype(np.float64)
     _svd_check(sig, X, W, M64, dt, "gaussian")
+    # every column goes through ~l rotations per sweep: their rounding errors must add up like a random walk
+    # (a rotation whose c^2 + s^2 is off by a few 1e-8 in the same direction every time shows up here)
+    want = np.linalg.svd(M64, compute_uv=False)
+    assert np.abs(sig - want).max() <= 20 * np.finfo(NPDT[dt]).eps * np.sqrt(l) * want[0]
     if l <= 33:       # brute-force Jacobi oracle on the small ones: vectors up to sign
         Xo, so, Wo, _ = ojacobi.jacobi_svd(M64)
         tol = 1e3 * np.finfo(NPDT[dt]).eps / np.min(np.abs(np.diff(so)) / so[:-1]) if l > 1 else 1
