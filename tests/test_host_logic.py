@@ -16,6 +16,10 @@ PTR = C.c_void_p(1 << 20)          # "device memory", 256-byte aligned
 
 @pytest.fixture(scope="module")
 def plan():
+    import os
+    if not os.path.exists(binding.library_path()):
+        from paper_2110_03423_amd import build
+        build.build_library()
     return binding.Rsvd(device=None)
 
 
@@ -138,8 +142,8 @@ def test_stage_entry_points_check_then_decline(plan):
     assert lib.rsvd_stage_lift(h, None, F32, 500, 40, 30, PTR, 40, PTR, 30, PTR, 499, 1, None, 0) == -12   # transposed: ldu >= m
 
 
-def test_no_such_device_is_an_error():
+def test_no_such_device_is_an_error(plan):
     h = C.c_void_p()
-    lib = binding.load_library()
+    lib = plan.lib
     assert lib.rsvd_create(C.byref(h), -7) == -2 and not h.value
     assert lib.rsvd_create(None, 0) == -1
