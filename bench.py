@@ -5,10 +5,15 @@
 
 A step is one full rsvd_run (sketch, range product, power iterations with
 re-orthonormalisation, projection, small SVD, lift) on a synthetic matrix that
-is already resident in HBM.  Prints one JSON line: wall time per call, the
-roofline position of the kernel class that takes the most time (measured with
-HIP events around every kernel launch in a second pass over the same steps),
-and the CPU oracle timed on the host cores for the same workload.
+is already resident in HBM.  The default workload is configuration 5 (fp32
+65536 x 16384, k = 512, p = 64, q = 1: the largest one and the one the matrix-core
+target is stated on).  Prints one JSON line: wall time per call, the roofline
+position of the kernel that takes the most time (measured with HIP events
+around every kernel launch in a second pass over the same steps; the two
+products with A are one kernel template and are priced together), the CPU
+oracle timed on the host cores for the same workload, and under
+`other_configs` the wall time and dominant kernel of the other four
+configurations from shorter runs.
 """
 import argparse
 import json
@@ -23,54 +28,55 @@ if ROOT not in sys.path:
 # MI355X published peaks
 PEAK_HBM = 8.0e12                                # B/s
 PEAK_MFMA = {"f32": 157.3e12, "f64": 78.6e12}    # dense matrix FLOP/s
-PEAK_VALU = {"f32": 157.3e12, "f64": 78.6e12}    # vector FLOP/s (256 CUs, 2.4 GHz)
+
+# Kernel classes that are one kernel template doing one job are priced together: the two products with A
+# (Y = A X and Z = A^T X are `gemm_kernel` with op(A) = A / A^T, 2 m n l flops and one pass over A each).
+GROUPS = {"a_pass": ("gemm_ax", "gemm_atx")}
+# Single-workgroup kernels on the serial path (a chain of dependent pivots / rotation rounds): bounded by latency,
+# not by a flop or byte rate; reported as time (and sweeps) only.
+LATENCY_BOUND = ("cholesky", "jacobi", "small")
 
 
-# HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this script at configuration 2,
-# scaled by the same counters on a plain 1 GiB copy (figures and commands: profiles/rsvd_run_cfg2_hbm_counters.md).
-MEASURED_TRAFFIC = {2: {"cholesky": 0.14e6, "jacobi": 0.12e6, "gemm_atx": 103.8e6, "gemm_ax": 108.5e6,
-                        "gram": 6.6e6, "apply_rinv": 7.1e6}}
+def measured_traffic(workload, kernel):
+    """HBM bytes per launch from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE summaries under profiles/ (each holds a
+    line `traffic-json: {...}` keyed by workload and kernel class), or None when no counter run backs the pair."""
+    import glob
+    for path in sorted(glob.glob(os.path.join(ROOT, "profiles", "*hbm_counters*.md"))):
+        for line in open(path):
+            if line.startswith("traffic-json:"):
+                try:
+                    table = json.loads(line[len("traffic-json:"):])
+                except ValueError:
+                    continue
+                if workload in table and kernel in table[workload]:
+                    return float(table[workload][kernel])
+    return None
 
 
-def kernel_models(cfg):
-    """Algorithmic flops and HBM bytes of ONE launch of each kernel class (unit: one launch)."""
-    m, n, l, k = cfg.m, cfg.n, cfg.l, cfg.k
+def launch_model(name, cfg):
+    """Algorithmic flops and bytes of ONE launch of a kernel class (every operand counted once), or None."""
+    m, n, l, k, q = cfg.m, cfg.n, cfg.l, cfg.k, cfg.q
     sz = 4 if cfg.dtype == "f32" else 8
-    models = {
-        # products with A: read A once, read the skinny operand, write the result
-        "gemm_ax": dict(flops=2.0 * m * n * l, bytes=(m * n + n * l + m * l) * sz, mfma=cfg.dtype),
-        "gemm_atx": dict(flops=2.0 * m * n * l, bytes=(m * n + m * l + n * l) * sz, mfma=cfg.dtype),
-        # small dense stages (latency / ALU bound): flops of the textbook algorithm
-        "cholesky": dict(flops=(5.0 / 3.0) * l ** 3, bytes=2 * l * l * 8, alu="f64"),
-        "sketch": dict(flops=None, bytes=n * l * sz),
-    }
-    return models
-
-
-def per_launch_model(name, cfg, launches_per_call):
-    """Flops / bytes of one launch for classes whose size alternates between m and n rows."""
-    m, n, l, k = cfg.m, cfg.n, cfg.l, cfg.k
-    sz = 4 if cfg.dtype == "f32" else 8
-    q = cfg.q
-    n_m, n_n = 2 * (q + 1), 2 * (q + 1)            # CholeskyQR rounds on m x l and on n x l panels
+    if name in ("a_pass", "gemm_ax", "gemm_atx"):
+        # read A once, read the skinny operand, write the result
+        return dict(flops=2.0 * m * n * l, bytes=(m * n + n * l + m * l) * sz, mfma=cfg.dtype)
+    # classes whose launches alternate between m-row and n-row panels: q + 1 CholeskyQR passes on each side,
+    # the average launch is priced
+    rows = (m + n) / 2.0
     if name == "gram":
-        rows = (n_m * m + n_n * n) / (n_m + n_n)
         return dict(flops=2.0 * rows * l * l, bytes=rows * l * sz + l * l * 8, mfma="f64")
     if name == "apply_rinv":
-        rows = (n_m * m + n_n * n) / (n_m + n_n)
         return dict(flops=2.0 * rows * l * l, bytes=2 * rows * l * sz + l * l * sz, mfma=cfg.dtype)
     if name == "lift":
-        rows = (m + n) / 2.0
         return dict(flops=2.0 * rows * l * k, bytes=rows * (l + k) * sz, mfma=cfg.dtype)
-    if name == "jacobi":
-        # one sweep = l(l-1)/2 pair visits, each 3 inner products and 2 rotated column pairs of length l
-        sweeps = launches_per_call if launches_per_call else 1
-        return dict(flops=9.0 * l ** 3 * sweeps, bytes=3 * l * l * sz, alu=cfg.dtype)
-    return kernel_models(cfg).get(name)
+    if name == "sketch":
+        return dict(flops=None, bytes=n * l * sz)
+    return None
 
 
-def roofline_for(name, avg_ms, cfg, sweeps=None):
-    mod = per_launch_model(name, cfg, sweeps)
+def roofline_for(name, avg_ms, cfg):
+    """Position of one launch of `name` (average duration avg_ms) against the roofline that bounds it."""
+    mod = launch_model(name, cfg)
     if mod is None or avg_ms <= 0:
         return None
     t = avg_ms * 1e-3
@@ -80,15 +86,23 @@ def roofline_for(name, avg_ms, cfg, sweeps=None):
         peak = PEAK_MFMA[mod["mfma"]]
         return dict(bound="mfma", achieved=flops / t / 1e12, peak=peak / 1e12, unit="TFLOP/s",
                     frac=flops / t / peak, traffic=None, kernel=name, avg_us=avg_ms * 1e3)
-    if "alu" in mod and flops:
-        # single-workgroup kernels on the serial path: priced against the vector peak
-        # (one workgroup can use one of the 256 CUs: frac_one_cu prices it against that share)
-        peak = PEAK_VALU[mod["alu"]]
-        return dict(bound="alu", achieved=flops / t / 1e12, peak=peak / 1e12, unit="TFLOP/s",
-                    frac=flops / t / peak, frac_one_cu=flops / t / (peak / 256.0), traffic=None, kernel=name,
-                    avg_us=avg_ms * 1e3)
     return dict(bound="hbm", achieved=mod["bytes"] / t / 1e9, peak=PEAK_HBM / 1e9, unit="GB/s",
                 frac=mod["bytes"] / t / PEAK_HBM, traffic=None, kernel=name, avg_us=avg_ms * 1e3)
+
+
+def grouped(kernels):
+    """Per-class timings with the classes of GROUPS merged (launch-weighted)."""
+    out = dict(kernels)
+    for gname, members in GROUPS.items():
+        have = [kernels[x] for x in members if x in kernels]
+        if not have:
+            continue
+        for x in members:
+            out.pop(x, None)
+        ms = sum(h["ms_per_call"] for h in have)
+        cnt = sum(h["launches_per_call"] for h in have)
+        out[gname] = dict(ms_per_call=ms, launches_per_call=cnt, avg_us=ms / cnt * 1e3)
+    return out
 
 
 def cpu_baseline(cfg, A_host, budget_s=20.0):
@@ -213,13 +227,104 @@ def batched(args):
             torch.cuda.empty_cache()
 
 
+def measure(ctx, cfg, A, steps, warmup, centered=False, with_graph=False, calibrate_copy=False):
+    """Time `steps` full rsvd_run calls on A (resident in HBM), then the same steps again with HIP events around
+    every kernel launch.  Returns wall time per call, its spread, the per-class kernel times and the diagnostics."""
+    import numpy as np
+    import torch
+    from paper_2110_03423_amd import F32, F64
+
+    dev = A.device
+    dt = F32 if cfg.dtype == "f32" else F64
+    ws = ctx.workspace(dt, cfg.m, cfg.n, cfg.k, cfg.p)
+    out = (torch.empty(cfg.k, dtype=A.dtype, device=dev), torch.empty((cfg.m, cfg.k), dtype=A.dtype, device=dev),
+           torch.empty((cfg.k, cfg.n), dtype=A.dtype, device=dev))
+    mean_buf = torch.empty(cfg.n, dtype=A.dtype, device=dev)
+
+    def step():
+        ctx.rsvd_run(A, cfg.k, cfg.p, cfg.q, seed=cfg.seed, workspace=ws, want_info=False, out=out,
+                     _mean=mean_buf if centered else None)
+
+    for _ in range(warmup):
+        step()
+    if calibrate_copy:
+        src = torch.ones(1 << 28, dtype=torch.float32, device=dev)      # 1 GiB read + 1 GiB written
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+    _, _, _, info = ctx.rsvd_run(A, cfg.k, cfg.p, cfg.q, seed=cfg.seed, workspace=ws, out=out)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        step()
+    torch.cuda.synchronize()
+    res = dict(ms_per_step=(time.perf_counter() - t0) * 1e3 / steps, info=info)
+
+    # per-call spread (paper's protocol: mean and standard deviation over repeated runs)
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(10)]
+    for a, b in evs:
+        a.record(); step(); b.record()
+    torch.cuda.synchronize()
+    per_call = np.array([a.elapsed_time(b) for a, b in evs])
+    res["mean_std_10"] = [round(float(per_call.mean()), 4), round(float(per_call.std()), 4)]
+
+    if with_graph:
+        # supplementary: the same call recorded once as a HIP graph and replayed (what a serving loop would do;
+        # the call allocates nothing and never synchronises when it gets its workspace and no diagnostics)
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            step()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            graph.replay()
+        torch.cuda.synchronize()
+        res["graph_ms"] = (time.perf_counter() - t0) * 1e3 / steps
+        del graph
+
+    # second pass over the same steps with HIP events around every kernel launch (recorded by the library on the
+    # stream it launches on)
+    ctx.rsvd_profile_enable(True)
+    for _ in range(steps):
+        step()
+    torch.cuda.synchronize()
+    prof = ctx.rsvd_profile_read()
+    ctx.rsvd_profile_enable(False)
+    res["kernels"] = {name: dict(ms_per_call=tot / steps, launches_per_call=cnt / steps, avg_us=tot / cnt * 1e3)
+                      for name, (tot, cnt) in prof.items()}
+    return res
+
+
+def dominant_roofline(cfg, kernels, info):
+    """The kernel (classes of one template grouped) with the largest share of the call, and where it sits against
+    its roofline.  A latency-bound class has no rate to quote: its entry carries time and sweeps instead."""
+    g = grouped(kernels)
+    name = max(g, key=lambda x: g[x]["ms_per_call"])
+    roof = roofline_for(name, g[name]["avg_us"] * 1e-3, cfg)
+    if roof is None:
+        roof = dict(bound="latency", achieved=None, peak=None, unit=None, frac=None, traffic=None, kernel=name,
+                    avg_us=g[name]["avg_us"], ms_per_call=g[name]["ms_per_call"], jacobi_sweeps=info.jacobi_sweeps)
+    else:
+        roof["traffic"] = measured_traffic(cfg.name, name)
+    roof["share_of_call"] = g[name]["ms_per_call"] / sum(v["ms_per_call"] for v in g.values())
+    return roof
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--config", type=int, default=2, help="benchmark configuration 1..5 (default 2)")
+    ap.add_argument("--config", type=int, default=5,
+                    help="benchmark configuration 1..5 (default 5: fp32 65536 x 16384, l = 576, the largest one)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
+    ap.add_argument("--no-others", action="store_true",
+                    help="skip the short runs of the other four configurations (extra key `other_configs`)")
     ap.add_argument("--centered", action="store_true",
                     help="time rsvd_run_centered (PCA front end: implicit column centring) instead of rsvd_run")
     ap.add_argument("--sweep", action="store_true",
@@ -235,10 +340,9 @@ def main():
               file=sys.stderr)
         sys.exit(2)
 
-    import numpy as np
     import torch
     import workloads
-    from paper_2110_03423_amd import Rsvd, F32, F64
+    from paper_2110_03423_amd import Rsvd
 
     if args.sweep:
         sweep(args)
@@ -248,83 +352,46 @@ def main():
         return
     cfg = workloads.CONFIGS[args.config]
     dev = "cuda:0"
-    A = workloads.build(cfg, device=dev)
     ctx = Rsvd(0)
-    dt = F32 if cfg.dtype == "f32" else F64
-    ws = ctx.workspace(dt, cfg.m, cfg.n, cfg.k, cfg.p)
-    out = (torch.empty(cfg.k, dtype=A.dtype, device=dev), torch.empty((cfg.m, cfg.k), dtype=A.dtype, device=dev),
-           torch.empty((cfg.k, cfg.n), dtype=A.dtype, device=dev))
-
-    mean_buf = torch.empty(cfg.n, dtype=A.dtype, device=dev)
-
-    def step():
-        ctx.rsvd_run(A, cfg.k, cfg.p, cfg.q, seed=cfg.seed, workspace=ws, want_info=False, out=out,
-                     _mean=mean_buf if args.centered else None)
-
-    for _ in range(args.warmup):
-        step()
-    if args.calibrate_copy:
-        src = torch.ones(1 << 28, dtype=torch.float32, device=dev)      # 1 GiB read + 1 GiB written
-        dst = torch.empty_like(src)
-        dst.copy_(src)
-        torch.cuda.synchronize()
-        del src, dst
-    _, _, _, info = ctx.rsvd_run(A, cfg.k, cfg.p, cfg.q, seed=cfg.seed, workspace=ws, out=out)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        step()
-    torch.cuda.synchronize()
-    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
-
-    # per-call spread (paper's protocol: mean and standard deviation over repeated runs)
-    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(10)]
-    for a, b in evs:
-        a.record(); step(); b.record()
-    torch.cuda.synchronize()
-    per_call = np.array([a.elapsed_time(b) for a, b in evs])
-
-    # supplementary: the same call recorded once as a HIP graph and replayed (what a serving loop would do;
-    # the call allocates nothing and never synchronises when it gets its workspace and no diagnostics)
-    side = torch.cuda.Stream()
-    side.wait_stream(torch.cuda.current_stream())
-    graph = torch.cuda.CUDAGraph()
-    with torch.cuda.graph(graph, stream=side):
-        step()
-    torch.cuda.synchronize()
-    graph.replay()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        graph.replay()
-    torch.cuda.synchronize()
-    graph_ms = (time.perf_counter() - t0) * 1e3 / args.steps
-    del graph
-
-    # second pass over the same steps with HIP events around every kernel launch
-    ctx.rsvd_profile_enable(True)
-    for _ in range(args.steps):
-        step()
-    torch.cuda.synchronize()
-    prof = ctx.rsvd_profile_read()
-    ctx.rsvd_profile_enable(False)
-    kernels = {name: dict(ms_per_call=tot / args.steps, launches_per_call=cnt / args.steps,
-                          avg_us=tot / cnt * 1e3) for name, (tot, cnt) in prof.items()}
-    dominant = max(kernels, key=lambda kname: kernels[kname]["ms_per_call"])
-    roof = roofline_for(dominant, kernels[dominant]["avg_us"] * 1e-3, cfg, info.jacobi_sweeps)
-    if roof is not None:
-        roof["traffic"] = MEASURED_TRAFFIC.get(args.config, {}).get(dominant)
+    A = workloads.build(cfg, device=dev)
+    res = measure(ctx, cfg, A, args.steps, args.warmup, centered=args.centered, with_graph=True,
+                  calibrate_copy=args.calibrate_copy)
+    info, kernels = res["info"], res["kernels"]
+    roof = dominant_roofline(cfg, kernels, info)
     stage_roof = {}
-    for name in kernels:
-        r = roofline_for(name, kernels[name]["avg_us"] * 1e-3, cfg, info.jacobi_sweeps)
+    for name, v in grouped(kernels).items():
+        r = roofline_for(name, v["avg_us"] * 1e-3, cfg)
         if r is not None:
             stage_roof[name] = dict(bound=r["bound"], achieved=round(r["achieved"], 3), unit=r["unit"],
-                                    frac=round(r["frac"], 4))
+                                    frac=round(r["frac"], 4), avg_us=round(v["avg_us"], 2))
+        elif name in LATENCY_BOUND:
+            stage_roof[name] = dict(bound="latency", ms_per_call=round(v["ms_per_call"], 4),
+                                    launches_per_call=round(v["launches_per_call"], 1))
 
     cpu = None
     if not args.no_cpu:
         cpu = cpu_baseline(cfg, A.cpu().numpy())
+    del A
+    torch.cuda.empty_cache()
 
+    # the other configurations, shorter: wall time per call and the dominant kernel's position
+    others = {}
+    if not args.no_others and not args.centered:
+        for cid, oc in workloads.CONFIGS.items():
+            if cid == args.config:
+                continue
+            Ao = workloads.build(oc, device=dev)
+            r = measure(ctx, oc, Ao, steps=10 if oc.m * oc.n > 1 << 27 else 20, warmup=2)
+            d = dominant_roofline(oc, r["kernels"], r["info"])
+            others[oc.name] = dict(dtype=oc.dtype, k=oc.k, p=oc.p, q=oc.q, ms_per_step=round(r["ms_per_step"], 4),
+                                   mean_std_10=r["mean_std_10"], jacobi_sweeps=r["info"].jacobi_sweeps,
+                                   dominant=d["kernel"], bound=d["bound"],
+                                   frac=None if d["frac"] is None else round(d["frac"], 4),
+                                   share_of_call=round(d["share_of_call"], 3))
+            del Ao
+            torch.cuda.empty_cache()
+
+    ms_per_step = res["ms_per_step"]
     line = {
         "metric": "rsvd_wall_time_ms",
         "value": round(ms_per_step, 4),
@@ -333,8 +400,8 @@ def main():
         "steps": args.steps,
         "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 4),
-        "ms_per_step_mean_std_10": [round(float(per_call.mean()), 4), round(float(per_call.std()), 4)],
-        "ms_per_step_graph_replay": round(graph_ms, 4),
+        "ms_per_step_mean_std_10": res["mean_std_10"],
+        "ms_per_step_graph_replay": round(res["graph_ms"], 4),
         "higher_is_better": False,
         "scaling": "weak",
         "vs_baseline": None,
@@ -347,6 +414,7 @@ def main():
         "kernels": {kname: {a: round(b, 4) for a, b in v.items()} for kname, v in kernels.items()},
         "stage_roofline": stage_roof,
         "cpu_baseline": cpu,
+        "other_configs": others,
     }
     print(json.dumps(line))
 
