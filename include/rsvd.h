@@ -54,7 +54,8 @@ typedef enum {
   RSVD_ERR_NO_CONVERGENCE = 2, /* Jacobi did not converge within the sweep cap */
   RSVD_ERR_HIP = 3,         /* a HIP runtime call failed; see rsvd_last_hip_error */
   RSVD_ERR_UNSUPPORTED = 4, /* shape outside what the kernels support (l too large) */
-  RSVD_ERR_NO_DEVICE = 5    /* the context was created with RSVD_DEVICE_NONE: it can size and check, not run */
+  RSVD_ERR_NO_DEVICE = 5,   /* the context was created with RSVD_DEVICE_NONE: it can size and check, not run */
+  RSVD_ERR_SCRATCH_LIMIT = 6 /* rsvd_run_static: the problem needs more than RSVD_STATIC_SCRATCH_BYTES of workspace */
 } rsvd_status;
 
 /* Diagnostics written by rsvd_run / stage calls when the caller asks for them
@@ -133,6 +134,30 @@ int rsvd_run(rsvd_ctx *ctx, void *stream, rsvd_dtype dtype, rsvd_job job,
              int k, int p, int q, uint64_t seed,
              void *S, void *U, int64_t ldu, void *Vt, int64_t ldvt,
              void *workspace, size_t workspace_bytes, rsvd_info *info);
+
+/*
+ * rsvd_run for callers that cannot allocate device memory and have no workspace
+ * to hand over: code under HIP graph capture, tight serving loops, harnesses
+ * that forbid hipMalloc.  Same computation, same kernels and same results as
+ * rsvd_run (bit for bit); the workspace is a buffer of
+ * RSVD_STATIC_SCRATCH_BYTES (32 MiB) that lives inside the loaded library, one
+ * copy per GPU, held until the process ends.  The call allocates nothing and
+ * frees nothing (with per-kernel profiling off, its default).
+ *   - A problem whose rsvd_workspace_bytes() exceeds the buffer is turned away
+ *     with RSVD_ERR_SCRATCH_LIMIT before anything is launched (the paper's
+ *     10000 x 2000, k + p = 80 benchmark shape needs 29 MiB and fits).
+ *   - Every call on one GPU uses the same buffer, whatever the context or the
+ *     stream: calls that overlap in time on one GPU race.  The buffer keeps the
+ *     contents of the call before; the kernels clear what they need cleared.
+ *   - info as for rsvd_run (non-NULL synchronises the stream).
+ * Arguments 1-17 as rsvd_run.  rsvd_static_scratch_bytes() returns the limit.
+ */
+#define RSVD_STATIC_SCRATCH_BYTES (32u << 20)
+int rsvd_run_static(rsvd_ctx *ctx, void *stream, rsvd_dtype dtype, rsvd_job job,
+                    int64_t m, int64_t n, const void *A, int64_t lda,
+                    int k, int p, int q, uint64_t seed,
+                    void *S, void *U, int64_t ldu, void *Vt, int64_t ldvt, rsvd_info *info);
+size_t rsvd_static_scratch_bytes(void);
 
 /*
  * The paper's PCA application: the same decomposition of the column-centred

@@ -40,6 +40,9 @@ PROTOTYPES = {
     "rsvd_workspace_bytes": [_VP, _INT, _I64, _I64, _INT, _INT, _INT, _INT, C.POINTER(_SZ)],
     "rsvd_run": [_VP, _VP, _INT, _INT, _I64, _I64, _VP, _I64, _INT, _INT, _INT, _U64,
                  _VP, _VP, _I64, _VP, _I64, _VP, _SZ, C.POINTER(_Info)],
+    "rsvd_run_static": [_VP, _VP, _INT, _INT, _I64, _I64, _VP, _I64, _INT, _INT, _INT, _U64,
+                        _VP, _VP, _I64, _VP, _I64, C.POINTER(_Info)],
+    "rsvd_static_scratch_bytes": [],
     "rsvd_run_centered": [_VP, _VP, _INT, _INT, _I64, _I64, _VP, _I64, _INT, _INT, _INT, _U64,
                           _VP, _VP, _I64, _VP, _I64, _VP, _SZ, C.POINTER(_Info), _VP],
     "rsvd_workspace_bytes_batched": [_VP, _INT, _INT, _I64, _I64, _INT, _INT, _INT, _INT, C.POINTER(_SZ)],
@@ -71,7 +74,12 @@ def load_library():
         for name, argtypes in PROTOTYPES.items():
             fn = getattr(lib, name)
             fn.argtypes = argtypes
-            fn.restype = C.c_char_p if name in ("rsvd_status_string", "rsvd_last_hip_error", "rsvd_profile_kind_name") else C.c_int
+            if name in ("rsvd_status_string", "rsvd_last_hip_error", "rsvd_profile_kind_name"):
+                fn.restype = C.c_char_p
+            elif name == "rsvd_static_scratch_bytes":
+                fn.restype = C.c_size_t
+            else:
+                fn.restype = C.c_int
         _LIB = lib
     return _LIB
 
@@ -189,6 +197,25 @@ class Rsvd:
         else:
             rc = self.lib.rsvd_run_centered(*args, _ptr(_mean))
         self._check(rc)
+        return S, U, Vt, (info if want_info else None)
+
+    def rsvd_run_static(self, A, k, p, q, seed=0, job=JOB_SUV, want_info=True, out=None):
+        """rsvd_run on the library's own static scratch buffer (no workspace argument).  `out` = (S, U, Vt)
+        tensors of the caller; without it they are allocated here, by torch, before the call."""
+        assert A.is_cuda and A.dim() == 2 and A.stride(1) == 1
+        m, n = A.shape
+        dt = _dtype_code(A)
+        if out is None:
+            S = self._empty((k,), A)
+            U = self._empty((m, k), A) if job == JOB_SUV else None
+            Vt = self._empty((k, n), A) if job >= JOB_SV else None
+        else:
+            S, U, Vt = out
+        info = _Info()
+        self._check(self.lib.rsvd_run_static(
+            self.h, self._stream(), dt, job, m, n, _ptr(A), A.stride(0), k, p, q, seed,
+            _ptr(S), _ptr(U), U.stride(0) if U is not None else 0,
+            _ptr(Vt), Vt.stride(0) if Vt is not None else 0, C.byref(info) if want_info else None))
         return S, U, Vt, (info if want_info else None)
 
     def rsvd_run_batched(self, A, k, p, q, seed=0, job=JOB_SUV, workspace=None, want_info=True, out=None):

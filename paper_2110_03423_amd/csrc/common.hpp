@@ -19,6 +19,7 @@ struct rsvd_ctx {
   std::vector<hipEvent_t> prof_events;   // pairs: start, stop
   std::vector<int> prof_kinds;           // one per pair
   size_t prof_used;                      // pairs recorded since the last read
+  void *static_scratch;                  // device address of this GPU's static scratch array (rsvd_run_static), or NULL
 };
 
 namespace rsvd {

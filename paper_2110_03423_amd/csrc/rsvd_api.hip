@@ -331,6 +331,12 @@ static bool valid_dtype(rsvd_dtype d) { return d == RSVD_F32 || d == RSVD_F64; }
 
 }  // namespace rsvd
 
+// Workspace of rsvd_run_static: device memory that belongs to the loaded library, one copy per GPU, held until
+// the process ends.  The name is a host-side handle only; its device address is looked up once per context
+// (hipGetSymbolAddress, in rsvd_create) and that address is what the kernels receive.
+constexpr size_t kStaticScratchBytes = (size_t)RSVD_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
 using namespace rsvd;
 
 extern "C" {
@@ -361,6 +367,23 @@ int rsvd_create(rsvd_ctx **out, int device) {
   c->hip_error[0] = 0;
   c->prof_on = false;
   c->prof_used = 0;
+  c->static_scratch = nullptr;
+  if (device >= 0) {
+    // address of this device's copy of the static scratch array (the device must be current for the lookup)
+    int cur = -1;
+    hipError_t e = hipGetDevice(&cur);
+    if (e == hipSuccess && cur != device) e = hipSetDevice(device);
+    if (e == hipSuccess) {
+      void *ptr = nullptr;
+      e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+      if (e == hipSuccess) c->static_scratch = ptr;
+      if (cur >= 0 && cur != device) (void)hipSetDevice(cur);
+    }
+    if (e != hipSuccess) {
+      snprintf(c->hip_error, sizeof(c->hip_error), "static scratch lookup: %s", hipGetErrorString(e));
+      (void)hipGetLastError();
+    }
+  }
   *out = c;
   return 0;
 }
@@ -380,6 +403,7 @@ const char *rsvd_status_string(int code) {
     case RSVD_ERR_HIP: return "HIP runtime error";
     case RSVD_ERR_UNSUPPORTED: return "problem shape not supported";
     case RSVD_ERR_NO_DEVICE: return "planning context (RSVD_DEVICE_NONE): arguments are valid, nothing was launched";
+    case RSVD_ERR_SCRATCH_LIMIT: return "problem needs more workspace than the static scratch buffer of rsvd_run_static holds";
     default: return code < 0 ? "invalid argument" : "unknown status";
   }
 }
@@ -578,6 +602,28 @@ int rsvd_run(rsvd_ctx *ctx, void *stream, rsvd_dtype dtype, rsvd_job job, int64_
   return run_impl(ctx, stream, dtype, job, m, n, A, lda, k, p, q, seed, S, U, ldu, Vt, ldvt, workspace,
                   workspace_bytes, info, 0, nullptr);
 }
+
+int rsvd_run_static(rsvd_ctx *ctx, void *stream, rsvd_dtype dtype, rsvd_job job, int64_t m, int64_t n, const void *A,
+                    int64_t lda, int k, int p, int q, uint64_t seed, void *S, void *U, int64_t ldu, void *Vt,
+                    int64_t ldvt, rsvd_info *info) {
+  if (ctx == nullptr) return -1;
+  // size check first (host arithmetic only), so that an oversized problem is turned away before anything else
+  size_t need = 0;
+  if (valid_dtype(dtype) && m >= 1 && n >= 1 && k >= 1 && p >= 0 && (int64_t)k + p <= (m < n ? m : n)) {
+    need = make_layout(ctx, dtype, m, n, (int64_t)k + p).total;
+    if (need > kStaticScratchBytes) return RSVD_ERR_SCRATCH_LIMIT;
+  }
+  void *ws = ctx->static_scratch;
+  if (ctx->device < 0) ws = reinterpret_cast<void *>((uintptr_t)256);      // planning context: checked, never used
+  if (ws == nullptr) {
+    if (ctx->hip_error[0] == 0) snprintf(ctx->hip_error, sizeof(ctx->hip_error), "static scratch is not available");
+    return RSVD_ERR_HIP;
+  }
+  return run_impl(ctx, stream, dtype, job, m, n, A, lda, k, p, q, seed, S, U, ldu, Vt, ldvt, ws, kStaticScratchBytes,
+                  info, 0, nullptr);
+}
+
+size_t rsvd_static_scratch_bytes(void) { return kStaticScratchBytes; }
 
 int rsvd_run_centered(rsvd_ctx *ctx, void *stream, rsvd_dtype dtype, rsvd_job job, int64_t m, int64_t n,
                       const void *A, int64_t lda, int k, int p, int q, uint64_t seed, void *S, void *U, int64_t ldu,

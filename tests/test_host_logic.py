@@ -94,6 +94,31 @@ def test_rsvd_run_checks_every_argument_then_declines_to_launch(plan):
     assert _run(lib, h, dtype=F64, m=4000, n=4000, lda=4000, ldvt=4000, k=700, p=0, ldu=700) == ERR_NO_DEVICE
 
 
+def test_static_scratch_entry_point_checks_size_and_arguments(plan):
+    """rsvd_run_static on the planning context: the size check against the 32 MiB buffer and the argument checks
+    of rsvd_run (positions 1-17 are the same), then the refusal to launch."""
+    lib, h = plan.lib, plan.h
+    SCRATCH_LIMIT = 6
+
+    def call(**kw):
+        a = dict(dtype=F32, job=JOB_SUV, m=1000, n=400, A=PTR, lda=400, k=20, p=10, q=2, S=PTR, U=PTR, ldu=20,
+                 Vt=PTR, ldvt=400)
+        a.update(kw)
+        return lib.rsvd_run_static(h, None, a["dtype"], a["job"], a["m"], a["n"], a["A"], a["lda"], a["k"], a["p"],
+                                   a["q"], 0, a["S"], a["U"], a["ldu"], a["Vt"], a["ldvt"], None)
+    limit = lib.rsvd_static_scratch_bytes()
+    assert limit == 32 << 20
+    assert call() == ERR_NO_DEVICE
+    assert call(A=None) == -7 and call(lda=399) == -8 and call(k=0) == -9 and call(S=None) == -13
+    assert lib.rsvd_run_static(None, None, F32, JOB_SUV, 10, 10, PTR, 10, 2, 2, 1, 0, PTR, PTR, 2, PTR, 10, None) == -1
+    # configuration 2 (the paper's benchmark shape) fits, configuration 3 does not
+    c2, c3 = workloads.CONFIGS[2], workloads.CONFIGS[3]
+    assert plan.workspace_bytes(F32, c2.m, c2.n, c2.k, c2.p) <= limit < plan.workspace_bytes(F32, c3.m, c3.n, c3.k, c3.p)
+    assert call(m=c2.m, n=c2.n, lda=c2.n, ldvt=c2.n, k=c2.k, p=c2.p, ldu=c2.k) == ERR_NO_DEVICE
+    assert call(m=c3.m, n=c3.n, lda=c3.n, ldvt=c3.n, k=c3.k, p=c3.p, ldu=c3.k) == SCRATCH_LIMIT
+    assert b"static scratch" in lib.rsvd_status_string(SCRATCH_LIMIT)
+
+
 def test_batched_entry_point_reports_positions_of_its_own_prototype(plan):
     lib, h = plan.lib, plan.h
 
