@@ -67,12 +67,16 @@ typedef struct {
                               fresh Gaussian directions, summed over all
                               orthonormalisations of the call.  A column counts
                               as dependent when what is left of it after the
-                              earlier columns is below ~1e-6 of its norm (the
-                              resolution of a Gram matrix held in fp64), so a
-                              non-zero count also says that directions of A
-                              weaker than ~1e-6 sigma_1 were not resolved */
+                              earlier columns is below the resolution of the
+                              orthonormalisation: ~4e-6 of its norm for fp32
+                              data (the rounding level of the panel itself),
+                              ~1e-12 for fp64 data */
   int32_t skipped_reorth;   /* 1: the condition estimate of the first panel let the power scheme drop one of
                              * its two re-orthonormalisations per iteration (see rsvd_run); else 0 */
+  int32_t raised_pivots;    /* fp64 only: pivots that fell below the resolution of one CholeskyQR round
+                             * (~1e-6 of the column norm) and were carried into an additional round instead of
+                             * being dropped, summed over the call.  Non-zero says that the sketched spectrum
+                             * spans more than six decades; it costs one more round per orthonormalisation */
 } rsvd_info;
 
 /* Create / destroy a context for HIP device `device`.  Host-side only:

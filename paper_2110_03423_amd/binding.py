@@ -19,7 +19,7 @@ class RsvdError(RuntimeError):
 
 class _Info(C.Structure):
     _fields_ = [("status", C.c_int32), ("jacobi_sweeps", C.c_int32),
-                ("refilled_columns", C.c_int32), ("skipped_reorth", C.c_int32)]
+                ("refilled_columns", C.c_int32), ("skipped_reorth", C.c_int32), ("raised_pivots", C.c_int32)]
 
 
 def library_path():

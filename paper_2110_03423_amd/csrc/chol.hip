@@ -68,10 +68,15 @@ template <int NB> struct CholLds {
 //   dblk : in  S_kk, out R_kk (valid on and above the diagonal)
 //   z    : out Z_kk = R_kk^-T (lower triangular)
 //   thr  : lane c holds tau * (reference squared norm of column c); pos: bit c set when that norm is > 0
+//          (and not below the caller's absolute floor)
 //   piv  : 16 doubles of LDS scratch
-//   returns the 16-bit mask of flagged (dependent) columns
+//   raise: a pivot at or below its threshold (with a usable reference norm) is not dropped but RAISED to the
+//          threshold: the column stays in the factor, scaled short of unit length, so that the direction it still
+//          carries survives into Q = Y R^-1 at a scale where the next round can resolve it (a shift of the Gram
+//          matrix applied only where it is needed)
+//   returns the 16-bit mask of dropped (dependent) columns, and in bits 16..31 that of raised pivots
 __device__ __forceinline__ unsigned diag_factor(f64x4 &dblk, f64x4 &z, double thr, unsigned pos, int lane,
-                                                double *piv) {
+                                                double *piv, bool raise) {
   const int lr = lane >> 4, lc = lane & 15;
   double mrow[4];
 #pragma unroll
@@ -79,18 +84,26 @@ __device__ __forceinline__ unsigned diag_factor(f64x4 &dblk, f64x4 &z, double th
 #pragma unroll
   for (int v = 0; v < 4; ++v) z[v] = (4 * v + lr == lc) ? 1.0 : 0.0;
   f64x4 sd = {0.0, 0.0, 0.0, 0.0}, sz = {0.0, 0.0, 0.0, 0.0};
-  unsigned dmask = 0;
+  unsigned dmask = 0, wmask = 0;
 #pragma unroll
   for (int j = 0; j < 16; ++j) {
     const int q = j & 3, v4 = j >> 2;
-    const double rowv = dblk[v4];
+    double rowv = dblk[v4];
     const double d = readlane_f64(rowv, 16 * q + j);            // pivot S[j][j]
     const unsigned gt = (unsigned)__ballot(d > thr);            // bit c: d exceeds the threshold of column c
     double y = __builtin_amdgcn_rcp(d);
     y = fma(fma(-d, y, 1.0), y, y);        // the hardware estimate is good to ~1e-8: one step squares that
-    if (!(((gt & pos) >> j) & 1u)) {                            // dependent column (rare): no elimination
-      dmask |= 1u << j;
-      y = 0.0;
+    if (!(((gt & pos) >> j) & 1u)) {                            // pivot at the rounding level of the Gram matrix (rare)
+      if (raise && ((pos >> j) & 1u)) {
+        const double dr = readlane_f64(thr, j);                 // lane j holds the threshold of column j
+        wmask |= 1u << j;
+        y = __builtin_amdgcn_rcp(dr);
+        y = fma(fma(-dr, y, 1.0), y, y);
+        if (lane == 16 * q + j) rowv = dr;                      // the diagonal element of the row takes the raised value
+      } else {                                                  // dependent column: no elimination
+        dmask |= 1u << j;
+        y = 0.0;
+      }
     }
     const double b_d = rowv * mrow[q];
     const double b_z = z[v4] * mrow[q];
@@ -115,7 +128,7 @@ __device__ __forceinline__ unsigned diag_factor(f64x4 &dblk, f64x4 &z, double th
     dblk[v] = sd[v] * rv;
     z[v] = sz[v] * rv;
   }
-  return dmask;
+  return dmask | (wmask << 16);
 }
 
 template <typename TOut, int NB>
@@ -125,11 +138,20 @@ __global__ __launch_bounds__(NB * 64) void chol_mfma_kernel(const double *__rest
                                                             TOut *__restrict__ Rinv, int64_t ldri,
                                                             double *__restrict__ R, int64_t ldr,
                                                             int *__restrict__ dead, DevInfo *info, int64_t stride,
-                                                            const int *skip_flag) {
+                                                            const int *skip_flag, int raise, double floor_abs,
+                                                            int *redo_skip, int redo_mode) {
   typedef CholLds<NB> L;
+  // redo_skip (device int, strided like the rest in a batch; may be NULL): the switch of the additional
+  // CholeskyQR round that follows a factorisation with raised pivots; non-zero = that round is skipped.
+  //   redo_mode 1: this launch decides alone: 0 when it raised a pivot, 1 when not (and when it is skipped itself);
+  //   redo_mode 2: one of several launches of a blocked factorisation: only ever clears it.
+  if (redo_skip != nullptr)
+    redo_skip = reinterpret_cast<int *>(reinterpret_cast<char *>(redo_skip) + (int64_t)blockIdx.x * stride);
   if (skip_flag != nullptr &&
-      *reinterpret_cast<const int *>(reinterpret_cast<const char *>(skip_flag) + (int64_t)blockIdx.x * stride) != 0)
+      *reinterpret_cast<const int *>(reinterpret_cast<const char *>(skip_flag) + (int64_t)blockIdx.x * stride) != 0) {
+    if (redo_skip != nullptr && redo_mode == 1 && threadIdx.x == 0) *redo_skip = 1;
     return;
+  }
   if (blockIdx.x != 0) {              // batched launch: one problem per workgroup, `stride` bytes apart
     const int64_t off = (int64_t)blockIdx.x * stride;
     G = reinterpret_cast<const double *>(reinterpret_cast<const char *>(G) + off);
@@ -143,14 +165,15 @@ __global__ __launch_bounds__(NB * 64) void chol_mfma_kernel(const double *__rest
   double *Td = Sm + LP * LD;               // NB x 16 x TLD: R_kk^-1
   double *d0 = Td + NB * 16 * TLD;         // LP: reference squared norms for the pivot test
   __shared__ double piv[16];
-  __shared__ int n_dead, bad;
+  __shared__ int n_dead, n_weak, bad;
   const int tid = threadIdx.x, lane = tid & 63, wr = tid >> 6;      // wr: block row of this wavefront
   const int lr = lane >> 4, lc = lane & 15;
   // register slot t of wavefront wr holds column block (wr + t) mod NB: slot 0 is the
   // diagonal block, slots 1 .. NB-1-wr the S blocks to its right, the rest the Z blocks
   auto col_block = [&](int t) { const int J = wr + t; return J >= NB ? J - NB : J; };
 
-  if (tid == 0) { n_dead = 0; bad = 0; }
+  if (tid == 0) { n_dead = 0; n_weak = 0; bad = 0; }
+  __syncthreads();
   // ---- load block row wr: sum of the parts for the S slots, zero for the Z slots, identity padding
   f64x4 acc[NB];
 #pragma unroll
@@ -189,9 +212,10 @@ __global__ __launch_bounds__(NB * 64) void chol_mfma_kernel(const double *__rest
     if (wr == kb) {
       // ---- pivot row: factor the diagonal block, scale the row, publish it
       const double d0c = d0[k0 + lc];
-      const unsigned pos = (unsigned)__ballot(d0c > 0.0) & 0xffffu;
+      const unsigned pos = (unsigned)__ballot(d0c > 0.0 && d0c >= floor_abs) & 0xffffu;
       f64x4 z;
-      const unsigned dmask = diag_factor(acc[0], z, tau * d0c, pos, lane, piv);
+      const unsigned masks = diag_factor(acc[0], z, tau * d0c, pos, lane, piv, raise != 0);
+      const unsigned dmask = masks & 0xffffu, wmask = masks >> 16;
 #pragma unroll
       for (int v = 0; v < 4; ++v) {
         const int row = 4 * v + lr;
@@ -202,6 +226,7 @@ __global__ __launch_bounds__(NB * 64) void chol_mfma_kernel(const double *__rest
       if (lane == 0) {
         const int valid = min(16, nb - k0);
         n_dead += __popc(dmask & ((1u << valid) - 1u));     // one writer at a time (steps are separated by barriers)
+        n_weak += __popc(wmask & ((1u << valid) - 1u));
       }
       __builtin_amdgcn_wave_barrier();
       double ta[4];
@@ -270,32 +295,49 @@ __global__ __launch_bounds__(NB * 64) void chol_mfma_kernel(const double *__rest
       }
     }
   }
-  if (tid == 0 && info != nullptr) {
-    if (n_dead > 0) atomicAdd(&info->refilled, n_dead);
-    if (bad) atomicMax(&info->status, (int)RSVD_ERR_NONFINITE);
+  if (tid == 0) {
+    if (info != nullptr) {
+      if (n_dead > 0) atomicAdd(&info->refilled, n_dead);
+      if (n_weak > 0) atomicAdd(&info->raised, n_weak);
+      if (bad) atomicMax(&info->status, (int)RSVD_ERR_NONFINITE);
+    }
+    if (redo_skip != nullptr) {
+      if (redo_mode == 1) *redo_skip = (n_weak > 0) ? 0 : 1;
+      else if (n_weak > 0) *redo_skip = 0;
+    }
   }
 }
 
-__global__ void save_diag_kernel(const double *__restrict__ G, int64_t ldg, int l, double *__restrict__ g0) {
+// First launch of a blocked factorisation: keeps the original diagonal for the pivot tests and arms the switch
+// of the additional round (see chol_mfma_kernel) - also when the factorisation itself is switched off.
+__global__ void save_diag_kernel(const double *__restrict__ G, int64_t ldg, int l, double *__restrict__ g0,
+                                 const int *skip_flag, int *redo_skip) {
   const int j = blockIdx.x * blockDim.x + threadIdx.x;
+  if (j == 0 && redo_skip != nullptr) *redo_skip = 1;
+  if (skip_flag != nullptr && *skip_flag != 0) return;
   if (j < l) g0[j] = G[(int64_t)j * ldg + j];
 }
 
 template <typename TOut>
-__global__ void convert_matrix_kernel(const double *__restrict__ src, int64_t n_elems, TOut *__restrict__ dst) {
+__global__ void convert_matrix_kernel(const double *__restrict__ src, int64_t n_elems, TOut *__restrict__ dst,
+                                      const int *skip_flag) {
+  if (skip_flag != nullptr && *skip_flag != 0) return;
   for (int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; e < n_elems;
        e += (int64_t)gridDim.x * blockDim.x)
     dst[e] = (TOut)src[e];
 }
 
-__global__ void fill_zero_f64_kernel(double *__restrict__ p, int64_t n) {
+__global__ void fill_zero_f64_kernel(double *__restrict__ p, int64_t n, const int *skip_flag) {
+  if (skip_flag != nullptr && *skip_flag != 0) return;
   for (int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; e < n; e += (int64_t)gridDim.x * blockDim.x)
     p[e] = 0.0;
 }
 
 __global__ void triu_product_kernel(int l, const double *__restrict__ R2, const double *__restrict__ R1,
-                                    double *__restrict__ Rb, int64_t stride) {
+                                    double *__restrict__ Rb, int64_t stride, const int *skip_flag) {
   const int64_t off = (int64_t)blockIdx.y * stride;        // batched: bytes between problems
+  if (skip_flag != nullptr && *reinterpret_cast<const int *>(reinterpret_cast<const char *>(skip_flag) + off) != 0)
+    return;
   R2 = reinterpret_cast<const double *>(reinterpret_cast<const char *>(R2) + off);
   R1 = reinterpret_cast<const double *>(reinterpret_cast<const char *>(R1) + off);
   Rb = reinterpret_cast<double *>(reinterpret_cast<char *>(Rb) + off);
@@ -339,21 +381,13 @@ size_t chol_scratch_elems(const rsvd_ctx *ctx, int64_t l) {
 template <typename TOut>
 static hipError_t launch_block(hipStream_t s, const double *G, int64_t ldg, int n_parts, int64_t part_stride, int nb,
                                const double *g0, double tau, TOut *Rinv, int64_t ldri, double *R, int64_t ldr,
-                               int *dead, DevInfo *info, int batch = 1, int64_t stride = 0,
-                               const int *skip_flag = nullptr) {
+                               int *dead, DevInfo *info, int batch, int64_t stride, const int *skip_flag,
+                               const CholPivoting &pv, int redo_mode) {
   // one workgroup, one wavefront per 16-row block
 #define RSVD_CHOL_CASE(NBV)                                                                                         \
-  do {                                                                                                              \
-    static bool attr_set = false;                                                                                   \
-    if (!attr_set) {                                                                                                \
-      (void)hipFuncSetAttribute(reinterpret_cast<const void *>(&chol_mfma_kernel<TOut, NBV>),                       \
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)CholLds<NBV>::bytes);              \
-      (void)hipGetLastError();                                                                                      \
-      attr_set = true;                                                                                              \
-    }                                                                                                               \
-    hipLaunchKernelGGL((chol_mfma_kernel<TOut, NBV>), dim3(batch), dim3(NBV * 64), CholLds<NBV>::bytes, s, G, ldg,  \
-                       n_parts, part_stride, nb, g0, tau, Rinv, ldri, R, ldr, dead, info, stride, skip_flag);       \
-  } while (0)
+  hipLaunchKernelGGL((chol_mfma_kernel<TOut, NBV>), dim3(batch), dim3(NBV * 64), CholLds<NBV>::bytes, s, G, ldg,    \
+                     n_parts, part_stride, nb, g0, tau, Rinv, ldri, R, ldr, dead, info, stride, skip_flag,          \
+                     pv.raise, pv.floor_abs, pv.redo_skip, redo_mode)
   switch ((nb + 15) / 16) {
     case 1: RSVD_CHOL_CASE(1); break;
     case 2: RSVD_CHOL_CASE(2); break;
@@ -367,6 +401,20 @@ static hipError_t launch_block(hipStream_t s, const double *G, int64_t ldg, int 
   }
 #undef RSVD_CHOL_CASE
   return hipGetLastError();
+}
+
+// The kernels of this file that need more LDS than the default limit of a launch: raised once per context.
+template <typename TOut>
+static hipError_t chol_raise_lds_limits() {
+  hipError_t e = hipSuccess;
+#define RSVD_CHOL_ATTR(NBV)                                                                              \
+  if (e == hipSuccess)                                                                                   \
+    e = hipFuncSetAttribute(reinterpret_cast<const void *>(&chol_mfma_kernel<TOut, NBV>),                \
+                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)CholLds<NBV>::bytes)
+  RSVD_CHOL_ATTR(1); RSVD_CHOL_ATTR(2); RSVD_CHOL_ATTR(3); RSVD_CHOL_ATTR(4);
+  RSVD_CHOL_ATTR(5); RSVD_CHOL_ATTR(6); RSVD_CHOL_ATTR(7); RSVD_CHOL_ATTR(8);
+#undef RSVD_CHOL_ATTR
+  return e;
 }
 
 // Blocks of X = R^-1 above the diagonal blocks, given R (upper triangular, l x l) and the inverted diagonal
@@ -476,19 +524,29 @@ __global__ __launch_bounds__(64 * NW) void tri_inverse_strip_kernel(const double
   }
 }
 
+hipError_t chol_init_device(rsvd_ctx *ctx) {
+  (void)ctx;
+  hipError_t e = chol_raise_lds_limits<float>();
+  if (e == hipSuccess) e = chol_raise_lds_limits<double>();
+  if (e == hipSuccess)
+    e = hipFuncSetAttribute(reinterpret_cast<const void *>(&tri_inverse_strip_kernel<6>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 4096);
+  return e;
+}
+
 hipError_t chol_inverse_launch(rsvd_ctx *ctx, hipStream_t s, rsvd_dtype out_dtype, int64_t l, double *G,
                                int64_t ldg, int n_parts, int64_t part_stride, double tau, void *Rinv, double *R,
                                int *dead, DevInfo *info, double *scratch, int batch, int64_t stride,
-                               const int *skip_flag) {
+                               const int *skip_flag, const CholPivoting &pv) {
   const int nbmax = chol_max_block(ctx);
   if (batch < 1 || batch > 65535) return hipErrorInvalidValue;
   if (l <= nbmax) {
     ProfScope ps(ctx, s, PK_CHOL);
     if (out_dtype == RSVD_F32)
       return launch_block<float>(s, G, ldg, n_parts, part_stride, (int)l, nullptr, tau, (float *)Rinv, l, R, l, dead,
-                                 info, batch, stride, skip_flag);
+                                 info, batch, stride, skip_flag, pv, 1);
     return launch_block<double>(s, G, ldg, n_parts, part_stride, (int)l, nullptr, tau, (double *)Rinv, l, R, l, dead,
-                                info, batch, stride, skip_flag);
+                                info, batch, stride, skip_flag, pv, 1);
   }
   if (batch != 1) return hipErrorNotSupported;       // the blocked path is not batched
   if (n_parts != 1) return hipErrorInvalidValue;     // the blocked path wants the reduced matrix
@@ -505,8 +563,9 @@ hipError_t chol_inverse_launch(rsvd_ctx *ctx, hipStream_t s, rsvd_dtype out_dtyp
   double *Rf = Xf + l * l;
   double *T = Rf + l * l;
   hipError_t e;
-  hipLaunchKernelGGL(save_diag_kernel, dim3((unsigned)ceil_div(l, 256)), dim3(256), 0, s, G, ldg, (int)l, g0);
-  hipLaunchKernelGGL(fill_zero_f64_kernel, dim3(1024), dim3(256), 0, s, Xf, 2 * l * l);
+  hipLaunchKernelGGL(save_diag_kernel, dim3((unsigned)ceil_div(l, 256)), dim3(256), 0, s, G, ldg, (int)l, g0,
+                     skip_flag, pv.redo_skip);
+  hipLaunchKernelGGL(fill_zero_f64_kernel, dim3(1024), dim3(256), 0, s, Xf, 2 * l * l, skip_flag);
   if ((e = hipGetLastError()) != hipSuccess) return e;
 
   for (int64_t j0 = 0; j0 < l; j0 += nb) {
@@ -516,7 +575,7 @@ hipError_t chol_inverse_launch(rsvd_ctx *ctx, hipStream_t s, rsvd_dtype out_dtyp
     {
       ProfScope ps(ctx, s, PK_CHOL);
       e = launch_block<double>(s, G + j0 * ldg + j0, ldg, 1, 0, (int)b, g0 + j0, tau, Xf + j0 * l + j0, l,
-                               Rf + j0 * l + j0, l, dead + j0, info, 1, 0, skip_flag);
+                               Rf + j0 * l + j0, l, dead + j0, info, 1, 0, skip_flag, pv, 2);
     }
     if (e != hipSuccess) return e;
     if (rest > 0) {
@@ -556,33 +615,31 @@ hipError_t chol_inverse_launch(rsvd_ctx *ctx, hipStream_t s, rsvd_dtype out_dtyp
     }
   }
   if (strips) {
-    static bool attr_set = false;
-    if (!attr_set) {
-      (void)hipFuncSetAttribute(reinterpret_cast<const void *>(&tri_inverse_strip_kernel<6>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 4096);
-      (void)hipGetLastError();
-      attr_set = true;
-    }
     ProfScope ps(ctx, s, PK_SMALL);
     hipLaunchKernelGGL((tri_inverse_strip_kernel<6>), dim3((unsigned)ceil_div(l, 16)), dim3(384), strip_lds, s, Rf, Xf,
                        (int)l, skip_flag);
     if ((e = hipGetLastError()) != hipSuccess) return e;
   }
   if (out_dtype == RSVD_F32) {
-    hipLaunchKernelGGL((convert_matrix_kernel<float>), dim3(512), dim3(256), 0, s, Xf, l * l, (float *)Rinv);
+    hipLaunchKernelGGL((convert_matrix_kernel<float>), dim3(512), dim3(256), 0, s, Xf, l * l, (float *)Rinv, skip_flag);
   } else {
-    hipLaunchKernelGGL((convert_matrix_kernel<double>), dim3(512), dim3(256), 0, s, Xf, l * l, (double *)Rinv);
+    hipLaunchKernelGGL((convert_matrix_kernel<double>), dim3(512), dim3(256), 0, s, Xf, l * l, (double *)Rinv,
+                       skip_flag);
   }
   if (R != nullptr)
-    hipLaunchKernelGGL((convert_matrix_kernel<double>), dim3(512), dim3(256), 0, s, Rf, l * l, R);
+    hipLaunchKernelGGL((convert_matrix_kernel<double>), dim3(512), dim3(256), 0, s, Rf, l * l, R, skip_flag);
   return hipGetLastError();
 }
 
 // One workgroup per problem: sums of squares of R and of R^-1, flag = (their product <= limit^2).
 template <typename T>
 __global__ __launch_bounds__(1024) void cond_flag_kernel(int l, const double *__restrict__ R, const T *__restrict__ Rinv,
-                                                         double limit, int *flag, DevInfo *info, int64_t stride) {
+                                                         double limit, int *flag, DevInfo *info, int64_t stride,
+                                                         const int *redo_skip) {
   const int64_t off = (int64_t)blockIdx.x * stride;
+  // a factorisation with raised pivots: the panel is badly conditioned whatever the later factors look like
+  const bool raised = redo_skip != nullptr &&
+                      *reinterpret_cast<const int *>(reinterpret_cast<const char *>(redo_skip) + off) == 0;
   R = reinterpret_cast<const double *>(reinterpret_cast<const char *>(R) + off);
   Rinv = reinterpret_cast<const T *>(reinterpret_cast<const char *>(Rinv) + off);
   flag = reinterpret_cast<int *>(reinterpret_cast<char *>(flag) + off);
@@ -618,27 +675,27 @@ __global__ __launch_bounds__(1024) void cond_flag_kernel(int l, const double *__
     a = 0.0; b = 0.0;
     for (int w = 0; w < (int)(blockDim.x >> 6); ++w) { a += part[0][w]; b += part[1][w]; }
     const double k2 = a * b;                     // (||R||_F ||R^-1||_F)^2 >= cond_2(R)^2
-    const int f = (!singular && k2 > 0.0 && k2 <= limit * limit) ? 1 : 0;      // NaN and Inf give 0
+    const int f = (!raised && !singular && k2 > 0.0 && k2 <= limit * limit) ? 1 : 0;      // NaN and Inf give 0
     *flag = f;
     if (f && info != nullptr) atomicMax(&info->skipped_reorth, 1);
   }
 }
 
 hipError_t cond_flag_launch(hipStream_t s, rsvd_dtype dtype, int64_t l, const double *R, const void *Rinv,
-                            double limit, int *flag, DevInfo *info, int batch, int64_t stride) {
+                            double limit, int *flag, DevInfo *info, int batch, int64_t stride, const int *redo_skip) {
   if (dtype == RSVD_F32)
     hipLaunchKernelGGL(cond_flag_kernel<float>, dim3(batch), dim3(1024), 0, s, (int)l, R, (const float *)Rinv, limit,
-                       flag, info, stride);
+                       flag, info, stride, redo_skip);
   else
     hipLaunchKernelGGL(cond_flag_kernel<double>, dim3(batch), dim3(1024), 0, s, (int)l, R, (const double *)Rinv, limit,
-                       flag, info, stride);
+                       flag, info, stride, redo_skip);
   return hipGetLastError();
 }
 
 hipError_t triu_product_launch(hipStream_t s, int64_t l, const double *R2, const double *R1, double *Rb, int batch,
-                               int64_t stride) {
+                               int64_t stride, const int *skip_flag) {
   hipLaunchKernelGGL(triu_product_kernel, dim3((unsigned)ceil_div(l * l, 256), (unsigned)batch), dim3(256), 0, s,
-                     (int)l, R2, R1, Rb, stride);
+                     (int)l, R2, R1, Rb, stride, skip_flag);
   return hipGetLastError();
 }
 

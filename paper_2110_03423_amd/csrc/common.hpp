@@ -61,7 +61,9 @@ struct DevInfo {
   int jacobi_sweeps;
   int refilled;
   int skipped_reorth;
+  int raised;
 };
+constexpr int kDevInfoInts = 5;
 
 // ---------------------------------------------------------------- GEMM
 // C (M x N) = alpha * op(A) (M x K) * B (K x N) + beta * C, row-major.
@@ -138,18 +140,37 @@ size_t chol_scratch_elems(const rsvd_ctx *ctx, int64_t l);
 //   batch > 1 (single-block orders only): problem b = blockIdx.x adds b * stride bytes to G, Rinv, R,
 //   dead and info (stride 0 for info: one shared block).
 //   skip_flag (device, may be NULL; strided like the rest in a batch): non-zero = do nothing.
+//   pv: what happens to a pivot at or below tau * (original squared norm of its column):
+//     raise = 0: the column is dropped (flagged in `dead`; the caller replaces it);
+//     raise = 1: the pivot is raised to that threshold and the column stays (only a column whose original
+//       squared norm is zero or below floor_abs is dropped);
+//     floor_abs: columns whose original squared norm is below this are dropped outright;
+//     redo_skip (device int, strided by `stride` in a batch, may be NULL): set to 0 when a pivot was raised,
+//       to 1 otherwise (also when skip_flag switches the factorisation off) - the skip flag of the
+//       additional CholeskyQR round that raised pivots call for.
+struct CholPivoting {
+  int raise = 0;
+  double floor_abs = 0.0;
+  int *redo_skip = nullptr;
+};
 hipError_t chol_inverse_launch(rsvd_ctx *ctx, hipStream_t s, rsvd_dtype out_dtype, int64_t l,
                                double *G, int64_t ldg, int n_parts, int64_t part_stride, double tau,
                                void *Rinv, double *R, int *dead, DevInfo *info, double *scratch,
-                               int batch = 1, int64_t stride = 0, const int *skip_flag = nullptr);
+                               int batch = 1, int64_t stride = 0, const int *skip_flag = nullptr,
+                               const CholPivoting &pv = CholPivoting());
+// Once per context, with its device current: raises the dynamic-LDS limit of the kernels that need it.
+hipError_t chol_init_device(rsvd_ctx *ctx);
+hipError_t jacobi_init_device(rsvd_ctx *ctx);
 // *flag = 1 when the Frobenius condition number ||R||_F ||R^-1||_F (an upper bound of the 2-norm one) of the
 // l x l factor is at most `limit` and finite, else 0.  R fp64, Rinv in `dtype`, both l x l with ld l.
 // info (may be NULL): skipped_reorth is raised to the flag.
+// redo_skip (may be NULL; strided like the rest): when it reads 0 - the factorisation raised a pivot - the flag is 0.
 hipError_t cond_flag_launch(hipStream_t s, rsvd_dtype dtype, int64_t l, const double *R, const void *Rinv,
-                            double limit, int *flag, DevInfo *info, int batch = 1, int64_t stride = 0);
+                            double limit, int *flag, DevInfo *info, int batch = 1, int64_t stride = 0,
+                            const int *redo_skip = nullptr);
 // Rb = R2 * R1 for upper triangular fp64 l x l matrices (ld l).
 hipError_t triu_product_launch(hipStream_t s, int64_t l, const double *R2, const double *R1, double *Rb,
-                               int batch = 1, int64_t stride = 0);
+                               int batch = 1, int64_t stride = 0, const int *skip_flag = nullptr);
 hipError_t zero_ints_launch(hipStream_t s, int *p, int n, int batch = 1, int64_t stride = 0);
 
 // ---------------------------------------------------------------- Jacobi

@@ -926,13 +926,6 @@ static hipError_t jacobi_block_launch(rsvd_ctx *ctx, hipStream_t s, rsvd_dtype d
   }
 #define RSVD_JB_CASE(NVV)                                                                                        \
   case NVV: {                                                                                                    \
-    static bool attr_set = false;                                                                                \
-    if (!attr_set) {                                                                                             \
-      (void)hipFuncSetAttribute(reinterpret_cast<const void *>(&jb_panel_kernel<T, NVV>),                        \
-                                hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 4096);                   \
-      (void)hipGetLastError();                                                                                   \
-      attr_set = true;                                                                                           \
-    }                                                                                                            \
     int slot = 0, pp = -1, pr = 0, psw = 0, pwgs = 0;          /* the launch before: phase, round, sweep, pairs */ \
     auto go = [&](int phase, int round, int sweep, int wgs) {                                                    \
       hipLaunchKernelGGL((jb_panel_kernel<T, NVV>), dim3(wgs + pwgs * chunks), dim3(1024), lds, s, Mt, Jt, l, b, \
@@ -962,13 +955,6 @@ static hipError_t jacobi_block_launch(rsvd_ctx *ctx, hipStream_t s, rsvd_dtype d
 template <typename T, typename TIn, int RPL, int G>
 static hipError_t launch_lds(hipStream_t s, int nt, size_t lds, const void *M, int l, void *sigma, void *X, void *W,
                              DevInfo *info, int batch, int64_t stride) {
-  static bool attr_set = false;
-  if (!attr_set) {
-    (void)hipFuncSetAttribute(reinterpret_cast<const void *>(&jacobi_lds_kernel<T, TIn, RPL, G>),
-                              hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 4096);
-    (void)hipGetLastError();
-    attr_set = true;
-  }
   hipLaunchKernelGGL((jacobi_lds_kernel<T, TIn, RPL, G>), dim3(batch), dim3(nt), lds, s, (const TIn *)M, l,
                      (T *)sigma, (T *)X, (T *)W, info, stride);
   return hipGetLastError();
@@ -997,6 +983,45 @@ static hipError_t launch_lds_g(hipStream_t s, int nt, int G, int rpl, size_t lds
     }
   }
   return hipErrorNotSupported;
+}
+
+// The kernels of this file are launched with up to 156 KB of dynamic LDS: the limit is raised here, once per
+// context (with its device current), for every instantiation the dispatch above can reach.
+template <typename T, typename TIn, int RPL>
+static void raise_lds_limit_lds(hipError_t &e) {
+  if (e == hipSuccess)
+    e = hipFuncSetAttribute(reinterpret_cast<const void *>(&jacobi_lds_kernel<T, TIn, RPL, 16>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 4096);
+}
+template <typename T, int NV>
+static void raise_lds_limit_panel(hipError_t &e) {
+  if (e == hipSuccess)
+    e = hipFuncSetAttribute(reinterpret_cast<const void *>(&jb_panel_kernel<T, NV>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 4096);
+}
+template <typename T>
+static void raise_lds_limit_panels(hipError_t &e) {
+  raise_lds_limit_panel<T, 2>(e); raise_lds_limit_panel<T, 3>(e); raise_lds_limit_panel<T, 4>(e);
+  raise_lds_limit_panel<T, 5>(e); raise_lds_limit_panel<T, 6>(e); raise_lds_limit_panel<T, 7>(e);
+  raise_lds_limit_panel<T, 8>(e); raise_lds_limit_panel<T, 9>(e); raise_lds_limit_panel<T, 10>(e);
+  raise_lds_limit_panel<T, 12>(e); raise_lds_limit_panel<T, 14>(e); raise_lds_limit_panel<T, 16>(e);
+  raise_lds_limit_panel<T, 18>(e); raise_lds_limit_panel<T, 20>(e); raise_lds_limit_panel<T, 24>(e);
+}
+
+hipError_t jacobi_init_device(rsvd_ctx *ctx) {
+  (void)ctx;
+  hipError_t e = hipSuccess;
+  raise_lds_limit_lds<float, double, 2>(e); raise_lds_limit_lds<float, double, 4>(e);
+  raise_lds_limit_lds<float, double, 6>(e); raise_lds_limit_lds<float, double, 8>(e);
+  raise_lds_limit_lds<float, float, 2>(e); raise_lds_limit_lds<float, float, 4>(e);
+  raise_lds_limit_lds<float, float, 6>(e); raise_lds_limit_lds<float, float, 8>(e);
+  raise_lds_limit_lds<double, double, 1>(e); raise_lds_limit_lds<double, double, 2>(e);
+  raise_lds_limit_lds<double, double, 3>(e); raise_lds_limit_lds<double, double, 4>(e);
+  raise_lds_limit_lds<double, double, 5>(e); raise_lds_limit_lds<double, double, 6>(e);
+  raise_lds_limit_lds<double, double, 8>(e);
+  raise_lds_limit_panels<float>(e);
+  raise_lds_limit_panels<double>(e);
+  return e;
 }
 
 hipError_t jacobi_launch(rsvd_ctx *ctx, hipStream_t s, rsvd_dtype dtype, int64_t l, const void *M,

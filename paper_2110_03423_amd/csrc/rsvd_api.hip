@@ -34,13 +34,29 @@ hipError_t gemm_launch(rsvd_ctx *ctx, hipStream_t s, GemmKind kind, const GemmDe
   }
 }
 
+// skip_flag (device int, stride_flag bytes between the problems of a batch; may be NULL): non-zero = do nothing
 template <typename T>
 __global__ void copy_kernel(const T *__restrict__ src, T *__restrict__ dst, int64_t n, int64_t stride_src,
-                            int64_t stride_dst) {
+                            int64_t stride_dst, const int *skip_flag, int64_t stride_flag) {
+  if (skip_flag != nullptr &&
+      *reinterpret_cast<const int *>(reinterpret_cast<const char *>(skip_flag) + (int64_t)blockIdx.y * stride_flag) != 0)
+    return;
   src = reinterpret_cast<const T *>(reinterpret_cast<const char *>(src) + (int64_t)blockIdx.y * stride_src);
   dst = reinterpret_cast<T *>(reinterpret_cast<char *>(dst) + (int64_t)blockIdx.y * stride_dst);
   for (int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; e < n; e += (int64_t)gridDim.x * blockDim.x)
     dst[e] = src[e];
+}
+
+// rows x cols elements from src (leading dimension lds) to dst (leading dimension ldd); one problem.
+template <typename T>
+__global__ __launch_bounds__(256) void copy2d_kernel(const T *__restrict__ src, int64_t lds, T *__restrict__ dst,
+                                                     int64_t ldd, int64_t rows, int64_t cols, const int *skip_flag) {
+  if (skip_flag != nullptr && *skip_flag != 0) return;
+  const int64_t total = rows * cols;
+  for (int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; e < total; e += (int64_t)gridDim.x * blockDim.x) {
+    const int64_t r = e / cols, c = e - r * cols;
+    dst[r * ldd + c] = src[r * lds + c];
+  }
 }
 
 // Column means: out64[j] = (1 / rows) * sum_i X[i][j], accumulated in fp64 in two deterministic
@@ -111,17 +127,32 @@ static hipError_t colmean_launch(hipStream_t s, rsvd_dtype dtype, const void *X,
 
 // batch > 1: problem b copies from src + b * stride_src to dst + b * stride_dst (bytes)
 static hipError_t copy_launch(hipStream_t s, rsvd_dtype dtype, const void *src, void *dst, int64_t n, int batch = 1,
-                              int64_t stride_src = 0, int64_t stride_dst = 0) {
+                              int64_t stride_src = 0, int64_t stride_dst = 0, const int *skip_flag = nullptr) {
   if (n <= 0) return hipSuccess;
   int64_t blocks = ceil_div(n, 256);
   if (blocks > 4096) blocks = 4096;
   const dim3 grid((unsigned)blocks, (unsigned)batch);
+  // (a gate lives in the workspace of its problem: same stride as the workspace buffers)
   if (dtype == RSVD_F32)
     hipLaunchKernelGGL(copy_kernel<float>, grid, dim3(256), 0, s, (const float *)src, (float *)dst, n, stride_src,
-                       stride_dst);
+                       stride_dst, skip_flag, stride_src);
   else
     hipLaunchKernelGGL(copy_kernel<double>, grid, dim3(256), 0, s, (const double *)src, (double *)dst, n, stride_src,
-                       stride_dst);
+                       stride_dst, skip_flag, stride_src);
+  return hipGetLastError();
+}
+
+static hipError_t copy2d_launch(hipStream_t s, rsvd_dtype dtype, const void *src, int64_t lds, void *dst, int64_t ldd,
+                                int64_t rows, int64_t cols, const int *skip_flag) {
+  int64_t blocks = ceil_div(rows * cols, 256 * 8);
+  if (blocks > 4096) blocks = 4096;
+  if (blocks < 1) blocks = 1;
+  if (dtype == RSVD_F32)
+    hipLaunchKernelGGL(copy2d_kernel<float>, dim3((unsigned)blocks), dim3(256), 0, s, (const float *)src, lds,
+                       (float *)dst, ldd, rows, cols, skip_flag);
+  else
+    hipLaunchKernelGGL(copy2d_kernel<double>, dim3((unsigned)blocks), dim3(256), 0, s, (const double *)src, lds,
+                       (double *)dst, ldd, rows, cols, skip_flag);
   return hipGetLastError();
 }
 
@@ -142,9 +173,10 @@ struct Layout {
   size_t bufM[2], bufN[2];          // m x l and n x l panels (ld l), ping-pong for CholeskyQR
   size_t partial, partial_bytes;    // split-K scratch
   size_t G, chol_scratch;           // fp64 Gram matrix, blocked-Cholesky scratch
-  size_t Rinv, R1, R2, Rb;          // R^-1 (dtype), R factors of both rounds and their product (fp64)
+  size_t Rinv, R1, R2, R3, Rb;      // R^-1 (dtype), R factors of the rounds and their product (fp64)
   size_t dead, info;                // flags per column, DevInfo
-  size_t flags;                     // device-side switches (ints): [0] = the power scheme may skip one side
+  size_t flags;                     // device-side switches (ints): [0] = the power scheme may skip one side,
+                                    // [1] = no pivot was raised: the additional CholeskyQR round is skipped
   size_t sigma, Wj, Xj;             // all l triplets of step 5: sigma, Ub (= W), X
   size_t jac_scratch, jac_scratch_bytes;
   size_t mean;                      // centred variant: column means (n, fp64)
@@ -173,6 +205,7 @@ static Layout make_layout(const rsvd_ctx *ctx, rsvd_dtype dtype, int64_t m, int6
   L.Rinv = take((size_t)l * l * es);
   L.R1 = take((size_t)l * l * 8);
   L.R2 = take((size_t)l * l * 8);
+  L.R3 = take(dtype == RSVD_F64 ? (size_t)l * l * 8 : 0);      // the additional round exists for fp64 panels only
   L.Rb = take((size_t)l * l * 8);
   L.dead = take((size_t)l * sizeof(int));
   L.info = take(sizeof(DevInfo));
@@ -216,6 +249,17 @@ static int fail_hip(rsvd_ctx *ctx, hipError_t e, const char *where) {
 // receives R with Y = Q R, or NULL.
 // skip_flag (device int, or NULL): when it reads non-zero every launch of this call does nothing (the caller then
 // goes on with Y itself).  keep_r: the triangular factor of the first round is also written to the R1 buffer.
+//
+// Resolution.  The Gram matrix is held in fp64, so a first round separates directions of Y down to sqrt(tau) ~ 1e-6
+// of the largest one; what lies below drowns in the rounding of the Gram matrix.  For fp32 panels that is the
+// end of it (the panel itself carries nothing finer) and such a column is replaced by a fresh Gaussian
+// direction.  For fp64 panels - where Householder QR, the paper's step 3, would keep directions down to the
+// rounding level of the data - a pivot at that level is RAISED to the threshold instead (see chol.hip): the column
+// stays, short of unit length, the first round sets a device flag, and ONE MORE ROUND, issued with every call and
+// switched on by that flag, works on a panel whose weak directions have been magnified by 1 / sqrt(tau).  Together
+// the rounds resolve directions down to ~tau ~ 1e-12 of the largest; only what is below that (or exactly zero)
+// is replaced.  Without raised pivots the additional round returns at once and the result is the one of the
+// plain scheme, bit for bit.
 static int orthonormalize(rsvd_ctx *ctx, hipStream_t s, rsvd_dtype dtype, const Ws &w, int64_t rows, int64_t l,
                           void *Y, int64_t ldy, void *tmp, double *Rout, uint64_t seed, uint32_t refill_stream,
                           int rounds = 2, const int *skip_flag = nullptr, bool keep_r = false) {
@@ -232,17 +276,22 @@ static int orthonormalize(rsvd_ctx *ctx, hipStream_t s, rsvd_dtype dtype, const 
     const double rel = 32.0 * 1.1920929e-07;           // 3.8e-6 of the column norm
     if (rel * rel > tau) tau = rel * rel;
   }
+  const bool rescue = dtype == RSVD_F64;
+  int *redo_skip = rescue ? w.at<int>(L.flags) + 1 : nullptr;      // 0 = the first round raised a pivot
   void *src = Y; int64_t lds_ = ldy;
   void *dst = tmp; int64_t ldd = l;
-  for (int round = 0; round < rounds; ++round) {
+  // One round: Gram matrix of `from`, its factor, `to` = `from` R^-1 (`to` may be `from` when one tile row of the
+  // product kernel spans all l columns: a workgroup has then read its rows completely before it writes them).
+  auto one_round = [&](int round, const void *from, int64_t ld_from, void *to, int64_t ld_to, const int *gate,
+                       const CholPivoting &pv, double *R) -> int {
     GemmDesc g;
     g.trans_a = 1; g.M = l; g.N = l; g.K = rows;
-    g.A = src; g.lda = lds_; g.B = src; g.ldb = lds_;
+    g.A = from; g.lda = ld_from; g.B = from; g.ldb = ld_from;
     g.C = w.at<double>(L.G); g.ldc = l;
     g.partial = w.at<void>(L.partial); g.partial_bytes = L.partial_bytes;
     g.prof_kind = PK_GRAM;
     g.batch = w.batch; g.stride_a = g.stride_b = g.stride_c = g.stride_partial = w.stride;
-    g.skip_flag = skip_flag; g.stride_flag = w.stride;
+    g.skip_flag = gate; g.stride_flag = w.stride;
     g.upper_only = (l > 96) ? 1 : 0;   // both factorisations read the upper block triangle only; below that one tile covers G
     // small orders: the Cholesky kernel adds the split-K partials itself
     int splits = 1;
@@ -250,29 +299,58 @@ static int orthonormalize(rsvd_ctx *ctx, hipStream_t s, rsvd_dtype dtype, const 
     g.skip_reduce_max = 4;          // more partials than this are cheaper to add in their own kernel
     g.splits_out = &splits;
     RSVD_TRY(gemm_launch(ctx, s, gram, g), "gram");
-    double *R = (Rout || (keep_r && round == 0)) ? w.at<double>(round == 0 ? L.R1 : L.R2) : nullptr;
     const bool parts = g.skip_reduce && splits > 1 && splits <= g.skip_reduce_max;
     RSVD_TRY(chol_inverse_launch(ctx, s, dtype, l, parts ? w.at<double>(L.partial) : w.at<double>(L.G), l,
                                  parts ? splits : 1, l * l, tau, w.at<void>(L.Rinv), R, w.at<int>(L.dead),
-                                 w.at<DevInfo>(L.info), w.at<double>(L.chol_scratch), w.batch, w.stride, skip_flag),
+                                 w.at<DevInfo>(L.info), w.at<double>(L.chol_scratch), w.batch, w.stride, gate, pv),
              "cholesky");
     GemmDesc a;
     a.M = rows; a.N = l; a.K = l;
-    a.A = src; a.lda = lds_; a.B = w.at<void>(L.Rinv); a.ldb = l;
-    a.C = dst; a.ldc = ldd;
+    a.A = from; a.lda = ld_from; a.B = w.at<void>(L.Rinv); a.ldb = l;
+    a.C = to; a.ldc = ld_to;
     a.dead = w.at<int>(L.dead); a.seed = seed; a.refill_stream = refill_stream + (uint32_t)round;
     a.refill_scale = 1.0 / sqrt((double)rows); a.refill_ld = l;
     a.force_splits = 1;
     a.batch = w.batch; a.stride_a = a.stride_b = a.stride_c = a.stride_dead = w.stride; a.seed_step = 1;
-    a.skip_flag = skip_flag; a.stride_flag = w.stride;
+    a.skip_flag = gate; a.stride_flag = w.stride;
     a.prof_kind = PK_APPLY;
     RSVD_TRY(gemm_launch(ctx, s, kind, a), "apply R^-1");
+    return 0;
+  };
+  int rc;
+  for (int round = 0; round < rounds; ++round) {
+    CholPivoting pv;
+    if (rescue) {
+      if (round == 0) { pv.raise = 1; pv.redo_skip = redo_skip; }
+      else pv.floor_abs = tau;        // a column that the first round left this short carried nothing but rounding
+    }
+    double *R = (Rout || (keep_r && round == 0)) ? w.at<double>(round == 0 ? L.R1 : L.R2) : nullptr;
+    if ((rc = one_round(round, src, lds_, dst, ldd, skip_flag, pv, R))) return rc;
     void *tp = src; src = dst; dst = tp;
     int64_t tl = lds_; lds_ = ldd; ldd = tl;
+  }
+  if (rescue) {
+    // the additional round on the result (now in `src`), gated by the flag the first round left
+    CholPivoting pv;
+    pv.floor_abs = tau;
+    double *R = Rout ? w.at<double>(L.R3) : nullptr;
+    if (l <= 128) {
+      if ((rc = one_round(rounds, src, lds_, src, lds_, redo_skip, pv, R))) return rc;
+    } else {
+      if ((rc = one_round(rounds, src, lds_, dst, ldd, redo_skip, pv, R))) return rc;
+      ProfScope ps(ctx, s, PK_SMALL);
+      RSVD_TRY(copy2d_launch(s, dtype, dst, ldd, src, lds_, rows, l, redo_skip), "copy panel");
+    }
   }
   if (Rout) {
     ProfScope ps(ctx, s, PK_SMALL);
     RSVD_TRY(triu_product_launch(s, l, w.at<double>(L.R2), w.at<double>(L.R1), Rout, w.batch, w.stride), "R product");
+    if (rescue) {
+      // R = R3 (R2 R1) when the additional round ran
+      RSVD_TRY(triu_product_launch(s, l, w.at<double>(L.R3), Rout, w.at<double>(L.G), w.batch, w.stride, redo_skip),
+               "R product");
+      RSVD_TRY(copy_launch(s, RSVD_F64, w.at<void>(L.G), Rout, l * l, w.batch, w.stride, w.stride, redo_skip), "copy R");
+    }
   }
   return 0;
 }
@@ -324,6 +402,7 @@ static int finish_info(rsvd_ctx *ctx, hipStream_t s, const Ws &w, rsvd_info *inf
   info->jacobi_sweeps = h.jacobi_sweeps;
   info->refilled_columns = h.refilled;
   info->skipped_reorth = h.skipped_reorth;
+  info->raised_pivots = h.raised;
   return h.status;
 }
 
@@ -377,12 +456,18 @@ int rsvd_create(rsvd_ctx **out, int device) {
       void *ptr = nullptr;
       e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
       if (e == hipSuccess) c->static_scratch = ptr;
+      else snprintf(c->hip_error, sizeof(c->hip_error), "static scratch lookup: %s", hipGetErrorString(e));
+      // per-kernel launch limits (dynamic LDS) of the single-workgroup kernels, for this device
+      hipError_t e2 = chol_init_device(c);
+      if (e2 == hipSuccess) e2 = jacobi_init_device(c);
       if (cur >= 0 && cur != device) (void)hipSetDevice(cur);
+      if (e2 != hipSuccess) {
+        (void)hipGetLastError();
+        delete c;
+        return RSVD_ERR_HIP;
+      }
     }
-    if (e != hipSuccess) {
-      snprintf(c->hip_error, sizeof(c->hip_error), "static scratch lookup: %s", hipGetErrorString(e));
-      (void)hipGetLastError();
-    }
+    if (e != hipSuccess) (void)hipGetLastError();
   }
   *out = c;
   return 0;
@@ -501,7 +586,7 @@ static int run_impl(rsvd_ctx *ctx, void *stream, rsvd_dtype dtype, rsvd_job job,
   void *bN0 = w.at<void>(L.bufN[0]), *bN1 = w.at<void>(L.bufN[1]);
   int rc;
 
-  RSVD_TRY(zero_ints_launch(s, w.at<int>(L.info), 4), "zero info");
+  RSVD_TRY(zero_ints_launch(s, w.at<int>(L.info), kDevInfoInts), "zero info");
   double *mean = center ? w.at<double>(L.mean) : nullptr;
   if (center) {
     // mu = A^T 1 / m, kept in fp64 for the products and handed out in the matrix type
@@ -553,11 +638,12 @@ static int run_impl(rsvd_ctx *ctx, void *stream, rsvd_dtype dtype, rsvd_job job,
     ProfScope ps(ctx, s, PK_SMALL);
     const double limit = (dtype == RSVD_F32 ? 32.0 : 128.0) * sqrt((double)l);
     RSVD_TRY(cond_flag_launch(s, dtype, l, w.at<double>(L.R1), w.at<void>(L.Rinv), limit, w.at<int>(L.flags),
-                              w.at<DevInfo>(L.info), batch, w.stride),
+                              w.at<DevInfo>(L.info), batch, w.stride,
+                              dtype == RSVD_F64 ? w.at<int>(L.flags) + 1 : nullptr),
              "condition flag");
   }
   if (q > 0) swap(curM, othM);
-  refill += 2;
+  refill += 3;
   bool m_raw = false;          // the previous m-side factorisation may have been skipped: raw panel in othM
   for (int it = 0; it < q; ++it) {
     if ((rc = times_at(curM, curN, m_raw ? skip : nullptr, m_raw ? othM : nullptr))) return rc;
@@ -566,7 +652,7 @@ static int run_impl(rsvd_ctx *ctx, void *stream, rsvd_dtype dtype, rsvd_job job,
                              n_skippable ? skip : nullptr)))
       return rc;
     swap(curN, othN);
-    refill += 2;
+    refill += 3;
     if ((rc = times_a(curN, curM, n_skippable ? skip : nullptr, n_skippable ? othN : nullptr))) return rc;
     const bool last = it == q - 1;
     m_raw = adaptive && drop_m && !last;
@@ -574,7 +660,7 @@ static int run_impl(rsvd_ctx *ctx, void *stream, rsvd_dtype dtype, rsvd_job job,
                              m_raw ? skip : nullptr)))
       return rc;
     if (!last) swap(curM, othM);
-    refill += 2;
+    refill += 3;
   }
   // step 4: B^T = A^T Q
   if ((rc = times_at(curM, curN))) return rc;
@@ -738,7 +824,7 @@ int rsvd_stage_orth(rsvd_ctx *ctx, void *stream, rsvd_dtype dtype, int64_t rows,
   if (workspace_bytes < w.L.total) return -12;
   if (ctx->device < 0) return RSVD_ERR_NO_DEVICE;
   hipStream_t s = (hipStream_t)stream;
-  RSVD_TRY(zero_ints_launch(s, w.at<int>(w.L.info), 4), "zero info");
+  RSVD_TRY(zero_ints_launch(s, w.at<int>(w.L.info), kDevInfoInts), "zero info");
   int rc = orthonormalize(ctx, s, dtype, w, rows, l, Y, ldy, w.at<void>(w.L.bufM[1]),
                           R ? w.at<double>(w.L.Rb) : nullptr, seed, refill_stream);
   if (rc) return rc;
@@ -767,7 +853,7 @@ int rsvd_stage_small_svd(rsvd_ctx *ctx, void *stream, rsvd_dtype dtype, int64_t 
   if (l > jacobi_max_lds_order(ctx, dtype) && jacobi_scratch_bytes(ctx, dtype, l) == 0) return RSVD_ERR_UNSUPPORTED;
   if (ctx->device < 0) return RSVD_ERR_NO_DEVICE;
   hipStream_t s = (hipStream_t)stream;
-  RSVD_TRY(zero_ints_launch(s, w.at<int>(w.L.info), 4), "zero info");
+  RSVD_TRY(zero_ints_launch(s, w.at<int>(w.L.info), kDevInfoInts), "zero info");
   int rc = small_svd(ctx, s, dtype, w, n, l, Bt, ldbt, w.at<void>(w.L.bufN[1]), seed, 16u);
   if (rc) return rc;
   RSVD_TRY(copy_launch(s, dtype, w.at<void>(w.L.sigma), sigma, l), "copy sigma");
@@ -792,7 +878,7 @@ int rsvd_stage_jacobi(rsvd_ctx *ctx, void *stream, rsvd_dtype dtype, int64_t l, 
   if (workspace_bytes < w.L.total) return -10;
   if (ctx->device < 0) return RSVD_ERR_NO_DEVICE;
   hipStream_t s = (hipStream_t)stream;
-  RSVD_TRY(zero_ints_launch(s, w.at<int>(w.L.info), 4), "zero info");
+  RSVD_TRY(zero_ints_launch(s, w.at<int>(w.L.info), kDevInfoInts), "zero info");
   const void *Min = M;
   int min_f64 = dtype == RSVD_F64;
   if (dtype == RSVD_F32 && l > jacobi_max_lds_order(ctx, dtype)) {

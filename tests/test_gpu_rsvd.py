@@ -1,5 +1,7 @@
 """GPU parity of the whole randomized k-SVD (Algorithm 1) through rsvd_run
 against the CPU oracle, at reduced and at full benchmark sizes."""
+import dataclasses
+
 import numpy as np
 import pytest
 
@@ -67,6 +69,29 @@ SMALL = [
 def test_reduced_configs(cfg):
     A = workloads.build(cfg)
     run_and_compare(cfg, to_dev(A), A)
+
+
+STEEP = [  # fp64, noise-free spectra that run far below 1e-6 sigma_1 inside the sketch
+    (scaled(CONFIGS[1], 936, 2582, rank=41, k=41, p=17), 1),     # 10^(-i/5) to 1e-8, rank < l
+    (scaled(CONFIGS[1], 298, 819, rank=84, k=103, p=36), 1),     # ... to the rounding level, l = 139 (blocked kernels)
+    (scaled(CONFIGS[1], 600, 400, rank=60, k=40, p=8), 2),       # full-rank sketch, 1e-9.4 at index 47
+    (scaled(CONFIGS[1], 1200, 500, rank=50, k=48, p=12), 0),     # no power iteration
+    (dataclasses.replace(scaled(CONFIGS[2], 3000, 700, k=120, p=40), dtype="f64"), 2),   # 0.9^i, l = 160: 5e-8 at the end
+]
+
+
+@pytest.mark.parametrize("cfg,q", STEEP, ids=lambda v: v.name if hasattr(v, "name") else f"q{v}")
+def test_steep_spectra_in_fp64(cfg, q):
+    """Directions between ~1e-6 sigma_1 (what one CholeskyQR round with an fp64 Gram matrix resolves) and the
+    rounding level must survive the orthonormalisations, as they do with the Householder QR of the paper's step 3:
+    every singular value above 2.2e-10 sigma_1 is held to 1e-5 against the oracle."""
+    A = workloads.build(cfg)
+    run_and_compare(cfg, to_dev(A), A, q=q)
+    _, _, _, info = ctx().rsvd_run(to_dev(A), cfg.k, cfg.p, q, seed=cfg.seed)
+    say(f"  raised={info.raised_pivots} refilled={info.refilled_columns}")
+    assert info.raised_pivots > 0
+    if cfg.rank >= cfg.l and cfg.spectrum(np.float64(cfg.l)) > 1e-10:
+        assert info.refilled_columns == 0                  # a full-rank sketch loses no column
 
 
 @pytest.mark.parametrize("q", [0, 1, 3])

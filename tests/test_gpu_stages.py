@@ -140,6 +140,28 @@ def test_orth_full_rank_matches_householder(dt, rows, l, cond):
     assert np.abs(np.tril(Rg, -1)).max() == 0.0
 
 
+@pytest.mark.parametrize("rows,l,cond", [(2000, 48, 1e9), (1500, 96, 1e11), (3000, 160, 1e10), (800, 20, 1e8),
+                                         (4000, 288, 1e9)])
+def test_orth_ill_conditioned_fp64_panel_matches_householder(rows, l, cond):
+    """fp64 panels whose singular values span far more than the six decades one CholeskyQR round resolves (the
+    paper's step 3 is a Householder QR, which keeps every direction down to the rounding level): the raised
+    pivots of the first round and the additional round must deliver the same Q and R, with no column replaced."""
+    say("orth ill-conditioned", rows, l, cond)
+    Y = workloads.graded_matrix(rows, l, cond, seed=21, dtype=np.float64)
+    Qg, Rg, info = ctx().rsvd_stage_orth(to_dev(Y), want_r=True)
+    Qg, Rg = to_np(Qg), to_np(Rg)
+    Qo, Ro = orc.qr_positive(Y)
+    eps = np.finfo(np.float64).eps
+    say("  raised", info.raised_pivots, "refilled", info.refilled_columns)
+    assert info.status == 0 and info.refilled_columns == 0 and info.raised_pivots > 0
+    assert parity.orthonormality(Qg) <= 10 * l * eps
+    assert np.linalg.norm(Y - Qg @ Rg) <= 50 * l * eps * np.linalg.norm(Y)
+    assert np.abs(np.tril(Rg, -1)).max() == 0.0
+    # Householder QR itself fixes column j of Q only to eps * (cond of the leading j columns); compare at that level
+    assert np.abs(Qg - Qo).max() <= 50 * eps * cond
+    assert np.abs(Rg - Ro).max() <= 50 * eps * cond * np.abs(Ro).max()
+
+
 @pytest.mark.parametrize("dt", ["f32", "f64"])
 def test_orth_rank_deficient_input(dt):
     """rank 10 < l = 20 (the situation of the planted rank-10 configuration)."""
