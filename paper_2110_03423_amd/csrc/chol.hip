@@ -70,11 +70,14 @@ template <int NB> struct CholLds {
 //   thr  : lane c holds tau * (reference squared norm of column c); pos: bit c set when that norm is > 0
 //          (and not below the caller's absolute floor)
 //   piv  : 16 doubles of LDS scratch
-//   raise: a pivot at or below its threshold (with a usable reference norm) is not dropped but RAISED to the
-//          threshold: the column stays in the factor, scaled short of unit length, so that the direction it still
-//          carries survives into Q = Y R^-1 at a scale where the next round can resolve it (a shift of the Gram
-//          matrix applied only where it is needed)
-//   returns the 16-bit mask of dropped (dependent) columns, and in bits 16..31 that of raised pivots
+//   raise: a pivot at or below its threshold (with a usable reference norm) does not drop its column but SETS IT
+//          ASIDE: the pivot takes the value of the threshold, the row is not used to eliminate anything (its
+//          part of R is the diagonal element alone), so the column comes out of Q = Y R^-1 as what is left of it
+//          after the columns before it, divided by sqrt(threshold): short of unit length, with the direction it
+//          still carries magnified to where the next round can resolve it, and with no large entries in R^-1
+//          (eliminating with a raised pivot instead couples the weak rows by ratios far above one, and their
+//          inverse overflowed on a sketch with ~100 such rows)
+//   returns the 16-bit mask of dropped (dependent) columns, and in bits 16..31 that of the columns set aside
 __device__ __forceinline__ unsigned diag_factor(f64x4 &dblk, f64x4 &z, double thr, unsigned pos, int lane,
                                                 double *piv, bool raise) {
   const int lr = lane >> 4, lc = lane & 15;
@@ -94,15 +97,13 @@ __device__ __forceinline__ unsigned diag_factor(f64x4 &dblk, f64x4 &z, double th
     double y = __builtin_amdgcn_rcp(d);
     y = fma(fma(-d, y, 1.0), y, y);        // the hardware estimate is good to ~1e-8: one step squares that
     if (!(((gt & pos) >> j) & 1u)) {                            // pivot at the rounding level of the Gram matrix (rare)
+      y = 0.0;                                                  // no elimination with this row
       if (raise && ((pos >> j) & 1u)) {
         const double dr = readlane_f64(thr, j);                 // lane j holds the threshold of column j
         wmask |= 1u << j;
-        y = __builtin_amdgcn_rcp(dr);
-        y = fma(fma(-dr, y, 1.0), y, y);
         if (lane == 16 * q + j) rowv = dr;                      // the diagonal element of the row takes the raised value
-      } else {                                                  // dependent column: no elimination
-        dmask |= 1u << j;
-        y = 0.0;
+      } else {
+        dmask |= 1u << j;                                       // dependent column
       }
     }
     const double b_d = rowv * mrow[q];
@@ -126,6 +127,7 @@ __device__ __forceinline__ unsigned diag_factor(f64x4 &dblk, f64x4 &z, double th
     rv = rv * (1.5 - 0.5 * x * rv * rv);
     if ((dmask >> (4 * v + lr)) & 1u) rv = 0.0;
     dblk[v] = sd[v] * rv;
+    if (((wmask >> (4 * v + lr)) & 1u) && lc != 4 * v + lr) dblk[v] = 0.0;      // set aside: the diagonal alone
     z[v] = sz[v] * rv;
   }
   return dmask | (wmask << 16);
@@ -139,12 +141,16 @@ __global__ __launch_bounds__(NB * 64) void chol_mfma_kernel(const double *__rest
                                                             double *__restrict__ R, int64_t ldr,
                                                             int *__restrict__ dead, DevInfo *info, int64_t stride,
                                                             const int *skip_flag, int raise, double floor_abs,
-                                                            int *redo_skip, int redo_mode) {
+                                                            double abs_thr, int *redo_skip, int redo_mode,
+                                                            double *__restrict__ Rinv_elim, int64_t ldre) {
   typedef CholLds<NB> L;
   // redo_skip (device int, strided like the rest in a batch; may be NULL): the switch of the additional
   // CholeskyQR round that follows a factorisation with raised pivots; non-zero = that round is skipped.
   //   redo_mode 1: this launch decides alone: 0 when it raised a pivot, 1 when not (and when it is skipped itself);
   //   redo_mode 2: one of several launches of a blocked factorisation: only ever clears it.
+  // Rinv_elim (fp64, ld ldre, may be NULL): a second copy of R^-1 whose columns of set-aside rows are zero.  A blocked
+  // factorisation forms its panel R[j, rest] = X_jj^T G[j, rest] with it, so that the rows set aside come out zero
+  // there as they do inside this kernel, and take no part in the trailing update.
   if (redo_skip != nullptr)
     redo_skip = reinterpret_cast<int *>(reinterpret_cast<char *>(redo_skip) + (int64_t)blockIdx.x * stride);
   if (skip_flag != nullptr &&
@@ -166,6 +172,7 @@ __global__ __launch_bounds__(NB * 64) void chol_mfma_kernel(const double *__rest
   double *d0 = Td + NB * 16 * TLD;         // LP: reference squared norms for the pivot test
   __shared__ double piv[16];
   __shared__ int n_dead, n_weak, bad;
+  __shared__ unsigned char aside[16 * NB];
   const int tid = threadIdx.x, lane = tid & 63, wr = tid >> 6;      // wr: block row of this wavefront
   const int lr = lane >> 4, lc = lane & 15;
   // register slot t of wavefront wr holds column block (wr + t) mod NB: slot 0 is the
@@ -214,7 +221,9 @@ __global__ __launch_bounds__(NB * 64) void chol_mfma_kernel(const double *__rest
       const double d0c = d0[k0 + lc];
       const unsigned pos = (unsigned)__ballot(d0c > 0.0 && d0c >= floor_abs) & 0xffffu;
       f64x4 z;
-      const unsigned masks = diag_factor(acc[0], z, tau * d0c, pos, lane, piv, raise != 0);
+      // pivot threshold: tau times the column's reference norm, or the same for every column (abs_thr > 0:
+      // rounds that work on a panel whose resolved columns have unit length)
+      const unsigned masks = diag_factor(acc[0], z, abs_thr > 0.0 ? abs_thr : tau * d0c, pos, lane, piv, raise != 0);
       const unsigned dmask = masks & 0xffffu, wmask = masks >> 16;
 #pragma unroll
       for (int v = 0; v < 4; ++v) {
@@ -223,6 +232,7 @@ __global__ __launch_bounds__(NB * 64) void chol_mfma_kernel(const double *__rest
         Td[(k0 + lc) * TLD + row] = z[v];                                      // T[c][row] = Z[row][c]
       }
       if (lane < 16 && k0 + lane < nb) dead[k0 + lane] = (int)((dmask >> lane) & 1u);
+      if (lane < 16) aside[k0 + lane] = (unsigned char)((wmask >> lane) & 1u);
       if (lane == 0) {
         const int valid = min(16, nb - k0);
         n_dead += __popc(dmask & ((1u << valid) - 1u));     // one writer at a time (steps are separated by barriers)
@@ -240,6 +250,14 @@ __global__ __launch_bounds__(NB * 64) void chol_mfma_kernel(const double *__rest
       for (int s = 0; s < 4; ++s)
 #pragma unroll
         for (int t = 1; t < NB; ++t) o[t] = Mfma<double>::run(ta[s], acc[t][s], o[t]);
+      if (wmask != 0u) {
+        // rows set aside keep nothing of R to the right of the diagonal (their part of R^-1, the Z slots, stays)
+#pragma unroll
+        for (int t = 1; t < NB; ++t)
+#pragma unroll
+          for (int v = 0; v < 4; ++v)
+            if (wr + t < NB && ((wmask >> (4 * v + lr)) & 1u)) o[t][v] = 0.0;
+      }
 #pragma unroll
       for (int t = 1; t < NB; ++t) {
         double *dst = Sm + (k0 + lr) * LD + 16 * col_block(t) + lc;
@@ -291,6 +309,7 @@ __global__ __launch_bounds__(NB * 64) void chol_mfma_kernel(const double *__rest
           double v = 0.0;
           if (r <= c) v = (r >= k0) ? Td[r * TLD + lc] : Sm[c * LD + r];
           Rinv[r * ldri_i + c] = (TOut)v;
+          if (Rinv_elim != nullptr) Rinv_elim[r * (int)ldre + c] = aside[c] ? 0.0 : v;
         }
       }
     }
@@ -374,20 +393,22 @@ int chol_max_block(const rsvd_ctx *ctx) {
 
 size_t chol_scratch_elems(const rsvd_ctx *ctx, int64_t l) {
   if (l <= chol_max_block(ctx)) return 0;
-  // blocked path: g0 (l, padded to even) + fp64 R^-1 (l*l) + R (l*l) + product scratch (l*l)
-  return (size_t)l + 1 + 3 * (size_t)l * (size_t)l;
+  // blocked path: g0 (l, padded to even) + fp64 R^-1 (l*l) + R (l*l) + product scratch (l*l) + the inverse of one
+  // diagonal block with the columns of set-aside rows cleared (128 x 128)
+  return (size_t)l + 1 + 3 * (size_t)l * (size_t)l + 128 * 128;
 }
 
 template <typename TOut>
 static hipError_t launch_block(hipStream_t s, const double *G, int64_t ldg, int n_parts, int64_t part_stride, int nb,
                                const double *g0, double tau, TOut *Rinv, int64_t ldri, double *R, int64_t ldr,
                                int *dead, DevInfo *info, int batch, int64_t stride, const int *skip_flag,
-                               const CholPivoting &pv, int redo_mode) {
+                               const CholPivoting &pv, int redo_mode, double *Rinv_elim = nullptr,
+                               int64_t ldre = 0) {
   // one workgroup, one wavefront per 16-row block
 #define RSVD_CHOL_CASE(NBV)                                                                                         \
   hipLaunchKernelGGL((chol_mfma_kernel<TOut, NBV>), dim3(batch), dim3(NBV * 64), CholLds<NBV>::bytes, s, G, ldg,    \
                      n_parts, part_stride, nb, g0, tau, Rinv, ldri, R, ldr, dead, info, stride, skip_flag,          \
-                     pv.raise, pv.floor_abs, pv.redo_skip, redo_mode)
+                     pv.raise, pv.floor_abs, pv.abs_thr, pv.redo_skip, redo_mode, Rinv_elim, ldre)
   switch ((nb + 15) / 16) {
     case 1: RSVD_CHOL_CASE(1); break;
     case 2: RSVD_CHOL_CASE(2); break;
@@ -562,6 +583,8 @@ hipError_t chol_inverse_launch(rsvd_ctx *ctx, hipStream_t s, rsvd_dtype out_dtyp
   double *Xf = g0 + ((l + 1) & ~(int64_t)1);
   double *Rf = Xf + l * l;
   double *T = Rf + l * l;
+  double *E = T + l * l;               // nb x nb (ld nb): X_jj without the columns of rows set aside
+  const bool aside = pv.raise != 0;
   hipError_t e;
   hipLaunchKernelGGL(save_diag_kernel, dim3((unsigned)ceil_div(l, 256)), dim3(256), 0, s, G, ldg, (int)l, g0,
                      skip_flag, pv.redo_skip);
@@ -575,14 +598,14 @@ hipError_t chol_inverse_launch(rsvd_ctx *ctx, hipStream_t s, rsvd_dtype out_dtyp
     {
       ProfScope ps(ctx, s, PK_CHOL);
       e = launch_block<double>(s, G + j0 * ldg + j0, ldg, 1, 0, (int)b, g0 + j0, tau, Xf + j0 * l + j0, l,
-                               Rf + j0 * l + j0, l, dead + j0, info, 1, 0, skip_flag, pv, 2);
+                               Rf + j0 * l + j0, l, dead + j0, info, 1, 0, skip_flag, pv, 2, aside ? E : nullptr, nb);
     }
     if (e != hipSuccess) return e;
     if (rest > 0) {
       // panel: R[j, rest] = X_jj^T G[j, rest]
       GemmDesc p;
       p.trans_a = 1; p.M = b; p.N = rest; p.K = b;
-      p.A = Xf + j0 * l + j0; p.lda = l;
+      p.A = aside ? E : Xf + j0 * l + j0; p.lda = aside ? nb : l;
       p.B = G + j0 * ldg + j0 + b; p.ldb = ldg;
       p.C = Rf + j0 * l + j0 + b; p.ldc = l;
       p.force_splits = 1; p.skip_flag = skip_flag;

@@ -142,15 +142,18 @@ size_t chol_scratch_elems(const rsvd_ctx *ctx, int64_t l);
 //   skip_flag (device, may be NULL; strided like the rest in a batch): non-zero = do nothing.
 //   pv: what happens to a pivot at or below tau * (original squared norm of its column):
 //     raise = 0: the column is dropped (flagged in `dead`; the caller replaces it);
-//     raise = 1: the pivot is raised to that threshold and the column stays (only a column whose original
-//       squared norm is zero or below floor_abs is dropped);
+//     raise = 1: the column is set aside - it stays in Q, scaled by 1 / sqrt(threshold) instead of normalised,
+//       and is not used to eliminate the later ones (only a column whose original squared norm is zero or
+//       below floor_abs is dropped);
 //     floor_abs: columns whose original squared norm is below this are dropped outright;
+//     abs_thr > 0: the threshold is this value for every column instead of tau * (its squared norm);
 //     redo_skip (device int, strided by `stride` in a batch, may be NULL): set to 0 when a pivot was raised,
 //       to 1 otherwise (also when skip_flag switches the factorisation off) - the skip flag of the
 //       additional CholeskyQR round that raised pivots call for.
 struct CholPivoting {
   int raise = 0;
   double floor_abs = 0.0;
+  double abs_thr = 0.0;
   int *redo_skip = nullptr;
 };
 hipError_t chol_inverse_launch(rsvd_ctx *ctx, hipStream_t s, rsvd_dtype out_dtype, int64_t l,

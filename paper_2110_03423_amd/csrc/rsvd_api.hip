@@ -173,10 +173,11 @@ struct Layout {
   size_t bufM[2], bufN[2];          // m x l and n x l panels (ld l), ping-pong for CholeskyQR
   size_t partial, partial_bytes;    // split-K scratch
   size_t G, chol_scratch;           // fp64 Gram matrix, blocked-Cholesky scratch
-  size_t Rinv, R1, R2, R3, Rb;      // R^-1 (dtype), R factors of the rounds and their product (fp64)
+  size_t Rinv, R1, R2, R3, R4, Rb;  // R^-1 (dtype), R factors of the rounds and their product (fp64)
   size_t dead, info;                // flags per column, DevInfo
   size_t flags;                     // device-side switches (ints): [0] = the power scheme may skip one side,
-                                    // [1] = no pivot was raised: the additional CholeskyQR round is skipped
+                                    // [1], [2] = no pivot was raised in the first / second CholeskyQR round:
+                                    // the additional round that would resolve it is skipped
   size_t sigma, Wj, Xj;             // all l triplets of step 5: sigma, Ub (= W), X
   size_t jac_scratch, jac_scratch_bytes;
   size_t mean;                      // centred variant: column means (n, fp64)
@@ -205,7 +206,8 @@ static Layout make_layout(const rsvd_ctx *ctx, rsvd_dtype dtype, int64_t m, int6
   L.Rinv = take((size_t)l * l * es);
   L.R1 = take((size_t)l * l * 8);
   L.R2 = take((size_t)l * l * 8);
-  L.R3 = take(dtype == RSVD_F64 ? (size_t)l * l * 8 : 0);      // the additional round exists for fp64 panels only
+  L.R3 = take(dtype == RSVD_F64 ? (size_t)l * l * 8 : 0);      // the additional rounds exist for fp64 panels only
+  L.R4 = take(dtype == RSVD_F64 ? (size_t)l * l * 8 : 0);
   L.Rb = take((size_t)l * l * 8);
   L.dead = take((size_t)l * sizeof(int));
   L.info = take(sizeof(DevInfo));
@@ -254,12 +256,13 @@ static int fail_hip(rsvd_ctx *ctx, hipError_t e, const char *where) {
 // of the largest one; what lies below drowns in the rounding of the Gram matrix.  For fp32 panels that is the
 // end of it (the panel itself carries nothing finer) and such a column is replaced by a fresh Gaussian
 // direction.  For fp64 panels - where Householder QR, the paper's step 3, would keep directions down to the
-// rounding level of the data - a pivot at that level is RAISED to the threshold instead (see chol.hip): the column
-// stays, short of unit length, the first round sets a device flag, and ONE MORE ROUND, issued with every call and
-// switched on by that flag, works on a panel whose weak directions have been magnified by 1 / sqrt(tau).  Together
-// the rounds resolve directions down to ~tau ~ 1e-12 of the largest; only what is below that (or exactly zero)
-// is replaced.  Without raised pivots the additional round returns at once and the result is the one of the
-// plain scheme, bit for bit.
+// rounding level of the data - such a column is SET ASIDE instead (see chol.hip): it stays in the panel, divided by
+// sqrt(threshold) and so short of unit length, the round sets a device flag, and AN ADDITIONAL ROUND, issued with every call and
+// switched on by that flag, works on a panel whose weak directions have been magnified by 1 / sqrt(tau).  Each
+// round resolves another six decades; a two-round call has two additional rounds behind it and so reaches the
+// rounding level of the data, a one-round call (inside the power scheme) one, which keeps ~1e-12.  Only what is
+// below that (or exactly zero) is replaced.  Without raised pivots the additional rounds return at once and the
+// result is the one of the plain scheme, bit for bit.
 static int orthonormalize(rsvd_ctx *ctx, hipStream_t s, rsvd_dtype dtype, const Ws &w, int64_t rows, int64_t l,
                           void *Y, int64_t ldy, void *tmp, double *Rout, uint64_t seed, uint32_t refill_stream,
                           int rounds = 2, const int *skip_flag = nullptr, bool keep_r = false) {
@@ -317,39 +320,58 @@ static int orthonormalize(rsvd_ctx *ctx, hipStream_t s, rsvd_dtype dtype, const 
     RSVD_TRY(gemm_launch(ctx, s, kind, a), "apply R^-1");
     return 0;
   };
+  // fp64 panels.  A column set aside in round r leaves it scaled by 1 / sqrt(tau), and so does the rounding noise
+  // of the panel (~eps of a column of Y): behind r such rounds a column whose squared norm is below
+  // (16 eps)^2 / tau^r holds nothing but that noise and is dropped.  From the second round on the resolved columns
+  // have unit length and the pivot threshold is tau itself for every column.
+  const double noise2 = 256.0 * 2.220446049250313e-16 * 2.220446049250313e-16;
+  const double floor_after[3] = {0.0, noise2 / tau, noise2 / (tau * tau)};
+  int *redo2_skip = redo_skip ? redo_skip + 1 : nullptr;             // 0 = the second round raised a pivot as well
   int rc;
   for (int round = 0; round < rounds; ++round) {
     CholPivoting pv;
     if (rescue) {
-      if (round == 0) { pv.raise = 1; pv.redo_skip = redo_skip; }
-      else pv.floor_abs = tau;        // a column that the first round left this short carried nothing but rounding
+      // the first round of every call, and the second round of a two-round call (which then has a fourth to fall
+      // back on), raise weak pivots; each leaves the switch of the additional round that resolves them
+      pv.raise = 1;
+      pv.redo_skip = round == 0 ? redo_skip : redo2_skip;
+      if (round > 0) { pv.floor_abs = floor_after[round]; pv.abs_thr = tau; }
     }
     double *R = (Rout || (keep_r && round == 0)) ? w.at<double>(round == 0 ? L.R1 : L.R2) : nullptr;
     if ((rc = one_round(round, src, lds_, dst, ldd, skip_flag, pv, R))) return rc;
     void *tp = src; src = dst; dst = tp;
     int64_t tl = lds_; lds_ = ldd; ldd = tl;
   }
-  if (rescue) {
-    // the additional round on the result (now in `src`), gated by the flag the first round left
+  // The additional rounds on the result (now in `src`): one behind a single round (the power scheme needs a
+  // well-conditioned basis, not every last direction), two behind a double round; each runs when the round two
+  // places before it raised a pivot.  Six decades of the panel's spectrum are resolved per round, so three
+  // resolving rounds and a polishing one reach the rounding level of fp64; what is still weak in the last
+  // resolving round is dropped and replaced.
+  const int extra = rescue ? rounds : 0;
+  for (int x = 0; x < extra; ++x) {
+    const int *gate = x == 0 ? redo_skip : redo2_skip;
     CholPivoting pv;
-    pv.floor_abs = tau;
-    double *R = Rout ? w.at<double>(L.R3) : nullptr;
+    pv.abs_thr = tau;
+    pv.floor_abs = rounds + x < 3 ? floor_after[rounds + x] : 0.0;      // (the fourth round sees unit columns only)
+    double *R = Rout ? w.at<double>(x == 0 ? L.R3 : L.R4) : nullptr;
     if (l <= 128) {
-      if ((rc = one_round(rounds, src, lds_, src, lds_, redo_skip, pv, R))) return rc;
+      if ((rc = one_round(rounds + x, src, lds_, src, lds_, gate, pv, R))) return rc;
     } else {
-      if ((rc = one_round(rounds, src, lds_, dst, ldd, redo_skip, pv, R))) return rc;
+      if ((rc = one_round(rounds + x, src, lds_, dst, ldd, gate, pv, R))) return rc;
       ProfScope ps(ctx, s, PK_SMALL);
-      RSVD_TRY(copy2d_launch(s, dtype, dst, ldd, src, lds_, rows, l, redo_skip), "copy panel");
+      RSVD_TRY(copy2d_launch(s, dtype, dst, ldd, src, lds_, rows, l, gate), "copy panel");
     }
   }
   if (Rout) {
     ProfScope ps(ctx, s, PK_SMALL);
     RSVD_TRY(triu_product_launch(s, l, w.at<double>(L.R2), w.at<double>(L.R1), Rout, w.batch, w.stride), "R product");
-    if (rescue) {
-      // R = R3 (R2 R1) when the additional round ran
-      RSVD_TRY(triu_product_launch(s, l, w.at<double>(L.R3), Rout, w.at<double>(L.G), w.batch, w.stride, redo_skip),
+    for (int x = 0; x < extra; ++x) {
+      // R = R3 (R2 R1), then R4 (R3 R2 R1), for the additional rounds that ran
+      const int *gate = x == 0 ? redo_skip : redo2_skip;
+      RSVD_TRY(triu_product_launch(s, l, w.at<double>(x == 0 ? L.R3 : L.R4), Rout, w.at<double>(L.G), w.batch,
+                                   w.stride, gate),
                "R product");
-      RSVD_TRY(copy_launch(s, RSVD_F64, w.at<void>(L.G), Rout, l * l, w.batch, w.stride, w.stride, redo_skip), "copy R");
+      RSVD_TRY(copy_launch(s, RSVD_F64, w.at<void>(L.G), Rout, l * l, w.batch, w.stride, w.stride, gate), "copy R");
     }
   }
   return 0;

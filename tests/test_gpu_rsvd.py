@@ -304,7 +304,7 @@ def test_ill_conditioned_panel_keeps_the_full_schedule():
     cfg1 = scaled(CONFIGS[1], 300, 200, rank=9, k=9, p=5)  # rank-deficient sketch: never dropped
     A1 = workloads.build(cfg1)
     _, _, _, info = ctx().rsvd_run(to_dev(A1), cfg1.k, cfg1.p, 2, seed=0)
-    assert info.skipped_reorth == 0 and info.refilled_columns > 0
+    assert info.skipped_reorth == 0 and info.refilled_columns + info.raised_pivots > 0
 
 
 @pytest.mark.parametrize("dt", ["f32", "f64"])
