@@ -137,6 +137,13 @@ def sweep(args):
 
     ctx = Rsvd(0)
     dev = "cuda:0"
+    if args.calibrate_copy:
+        src = torch.ones(1 << 28, dtype=torch.float32, device=dev)      # 1 GiB read + 1 GiB written
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+        torch.cuda.empty_cache()
     for cid in (3, 5):
         base = workloads.CONFIGS[cid]
         A = workloads.build(base, device=dev)
