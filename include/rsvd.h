@@ -207,6 +207,12 @@ int rsvd_run_batched(rsvd_ctx *ctx, void *stream, rsvd_dtype dtype, rsvd_job job
 /* ---- stage entry points: each step of Algorithm 1 on its own, for per-stage
  * parity tests and timing.  They run the same kernels as rsvd_run. ---- */
 
+/* Bytes of workspace that the stage calls which work on one rows x l panel need (rsvd_stage_orth and
+ * rsvd_stage_small_svd with that panel; rsvd_stage_jacobi with rows = l): the panels and l x l matrices only,
+ * nothing sized by a matrix A.  The figure of rsvd_workspace_bytes() for an m x n problem with m, n >= rows and
+ * the same k + p = l also suffices; the product stages (rsvd_stage_gemm_an / _atn) take that figure. */
+int rsvd_stage_workspace_bytes(rsvd_ctx *ctx, rsvd_dtype dtype, int64_t rows, int64_t l, size_t *bytes);
+
 /* Step 1: Omega (rows x cols, leading dimension ldo) of iid N(0,1) from
  * Philox4x32-10 + Box-Muller; element (i, j) is element i*cols + j of stream
  * `stream_id` under `seed` (stream 0 is the sketch of rsvd_run). */

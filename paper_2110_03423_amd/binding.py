@@ -48,6 +48,7 @@ PROTOTYPES = {
     "rsvd_workspace_bytes_batched": [_VP, _INT, _INT, _I64, _I64, _INT, _INT, _INT, _INT, C.POINTER(_SZ)],
     "rsvd_run_batched": [_VP, _VP, _INT, _INT, _INT, _I64, _I64, _VP, _I64, _I64, _INT, _INT, _INT, _U64,
                          _VP, _I64, _VP, _I64, _I64, _VP, _I64, _I64, _VP, _SZ, C.POINTER(_Info)],
+    "rsvd_stage_workspace_bytes": [_VP, _INT, _I64, _I64, C.POINTER(_SZ)],
     "rsvd_stage_sketch": [_VP, _VP, _INT, _U64, _U32, _I64, _I64, _VP, _I64],
     "rsvd_stage_philox_raw": [_VP, _VP, _U64, _U32, _U64, _I64, _VP],
     "rsvd_stage_gemm_an": [_VP, _VP, _INT, _I64, _I64, _I64, _VP, _I64, _VP, _I64, _VP, _I64, _VP, _SZ],
@@ -158,12 +159,22 @@ class Rsvd:
         return out.value
 
     def workspace(self, dtype, m, n, k, p):
-        """A cached uint8 tensor large enough for the problem (grown on demand)."""
-        need = self.workspace_bytes(dtype, m, n, k, p)
+        """A cached uint8 tensor large enough for the problem (grown on demand).  The cache is one buffer per
+        context: calls that rely on it must stay on one stream (a call on another stream could still be using
+        the buffer that a growing request replaces); pass `workspace=` to own the buffer yourself."""
+        return self._grow(self.workspace_bytes(dtype, m, n, k, p))
+
+    def _grow(self, need):
         if self._ws is None or self._ws.numel() < need:
             self._ws = None
             self._ws = self.torch.empty(need, dtype=self.torch.uint8, device=self.device)
         return self._ws
+
+    def stage_workspace(self, dtype, rows, l):
+        """Cached workspace for the stage calls on one rows x l panel (orth, small_svd, jacobi)."""
+        out = C.c_size_t()
+        self._check(self.lib.rsvd_stage_workspace_bytes(self.h, dtype, rows, l, C.byref(out)))
+        return self._grow(out.value)
 
     def _empty(self, shape, like):
         return self.torch.empty(shape, dtype=like.dtype, device=self.device)
@@ -281,7 +292,7 @@ class Rsvd:
         """In place on Y.  Returns (Y, R or None, info)."""
         rows, l = Y.shape
         dt = _dtype_code(Y)
-        ws = self.workspace(dt, rows, rows, l, 0)
+        ws = self.stage_workspace(dt, rows, l)
         R = self.torch.empty((l, l), dtype=self.torch.float64, device=self.device) if want_r else None
         info = _Info()
         self._check(self.lib.rsvd_stage_orth(self.h, self._stream(), dt, rows, l, _ptr(Y), Y.stride(0), _ptr(R),
@@ -292,7 +303,7 @@ class Rsvd:
         """Bt (n, l) is overwritten.  Returns (sigma, Ub, V, info)."""
         n, l = Bt.shape
         dt = _dtype_code(Bt)
-        ws = self.workspace(dt, n, n, l, 0)
+        ws = self.stage_workspace(dt, n, l)
         sigma = self._empty((l,), Bt)
         Ub = self._empty((l, l), Bt)
         V = self._empty((n, l), Bt)
@@ -306,7 +317,7 @@ class Rsvd:
         """M (l, l) is overwritten.  Returns (sigma, X, W, info)."""
         l = M.shape[0]
         dt = _dtype_code(M)
-        ws = self.workspace(dt, l, l, l, 0)
+        ws = self.stage_workspace(dt, l, l)
         sigma = self._empty((l,), M)
         X = self._empty((l, l), M)
         W = self._empty((l, l), M)

@@ -62,7 +62,7 @@ __global__ __launch_bounds__(256) void copy2d_kernel(const T *__restrict__ src, 
 // Column means: out64[j] = (1 / rows) * sum_i X[i][j], accumulated in fp64 in two deterministic
 // stages (row chunks of kColsumRows, then the chunks in order); out (may be NULL) receives the
 // same values rounded to the matrix type.
-constexpr int kColsumRows = 128;
+constexpr int kColsumRows = 512;
 
 template <typename T>
 __global__ __launch_bounds__(256) void colsum_partial_kernel(const T *__restrict__ X, int64_t ldx, int64_t rows,
@@ -711,6 +711,16 @@ int rsvd_run(rsvd_ctx *ctx, void *stream, rsvd_dtype dtype, rsvd_job job, int64_
                   workspace_bytes, info, 0, nullptr);
 }
 
+int rsvd_stage_workspace_bytes(rsvd_ctx *ctx, rsvd_dtype dtype, int64_t rows, int64_t l, size_t *bytes) {
+  if (ctx == nullptr) return -1;
+  if (!valid_dtype(dtype)) return -2;
+  if (rows < 1) return -3;
+  if (l < 1 || l > rows) return -4;
+  if (bytes == nullptr) return -5;
+  *bytes = make_layout(ctx, dtype, rows, l, l).total;
+  return 0;
+}
+
 int rsvd_run_static(rsvd_ctx *ctx, void *stream, rsvd_dtype dtype, rsvd_job job, int64_t m, int64_t n, const void *A,
                     int64_t lda, int k, int p, int q, uint64_t seed, void *S, void *U, int64_t ldu, void *Vt,
                     int64_t ldvt, rsvd_info *info) {
@@ -840,7 +850,7 @@ int rsvd_stage_orth(rsvd_ctx *ctx, void *stream, rsvd_dtype dtype, int64_t rows,
   if (Y == nullptr) return -6;
   if (ldy < l) return -7;
   Ws w;
-  w.L = make_layout(ctx, dtype, rows, rows, l);
+  w.L = make_layout(ctx, dtype, rows, l, l);           // a rows x l panel and l x l matrices: nothing sized by a matrix A
   w.base = (char *)workspace;
   if (workspace == nullptr || ((uintptr_t)workspace & 255) != 0) return -11;
   if (workspace_bytes < w.L.total) return -12;
@@ -868,7 +878,7 @@ int rsvd_stage_small_svd(rsvd_ctx *ctx, void *stream, rsvd_dtype dtype, int64_t 
   if (V == nullptr) return -10;
   if (ldv < l) return -11;
   Ws w;
-  w.L = make_layout(ctx, dtype, n, n, l);
+  w.L = make_layout(ctx, dtype, n, l, l);              // as rsvd_stage_orth: the n x l panel takes the "m" slots
   w.base = (char *)workspace;
   if (workspace == nullptr || ((uintptr_t)workspace & 255) != 0) return -13;
   if (workspace_bytes < w.L.total) return -14;
@@ -876,7 +886,7 @@ int rsvd_stage_small_svd(rsvd_ctx *ctx, void *stream, rsvd_dtype dtype, int64_t 
   if (ctx->device < 0) return RSVD_ERR_NO_DEVICE;
   hipStream_t s = (hipStream_t)stream;
   RSVD_TRY(zero_ints_launch(s, w.at<int>(w.L.info), kDevInfoInts), "zero info");
-  int rc = small_svd(ctx, s, dtype, w, n, l, Bt, ldbt, w.at<void>(w.L.bufN[1]), seed, 16u);
+  int rc = small_svd(ctx, s, dtype, w, n, l, Bt, ldbt, w.at<void>(w.L.bufM[1]), seed, 16u);
   if (rc) return rc;
   RSVD_TRY(copy_launch(s, dtype, w.at<void>(w.L.sigma), sigma, l), "copy sigma");
   RSVD_TRY(copy_launch(s, dtype, w.at<void>(w.L.Wj), Ub, l * l), "copy Ub");

@@ -167,6 +167,24 @@ def test_stage_entry_points_check_then_decline(plan):
     assert lib.rsvd_stage_lift(h, None, F32, 500, 40, 30, PTR, 40, PTR, 30, PTR, 499, 1, None, 0) == -12   # transposed: ldu >= m
 
 
+def test_stage_workspace_is_sized_by_the_panel_alone(plan):
+    lib, h, out = plan.lib, plan.h, C.c_size_t()
+    assert lib.rsvd_stage_workspace_bytes(h, F32, 100000, 120, C.byref(out)) == 0
+    panels = 2 * 100000 * 120 * 4
+    assert out.value % 256 == 0 and panels < out.value < panels + (64 << 20)      # no term grows with rows^2
+    assert out.value <= plan.workspace_bytes(F32, 100000, 100000, 120, 0)           # the full-problem figure also covers it
+    need = out.value
+    assert lib.rsvd_stage_orth(h, None, F32, 100000, 120, PTR, 120, None, 0, 16, PTR, need, None) == ERR_NO_DEVICE
+    assert lib.rsvd_stage_orth(h, None, F32, 100000, 120, PTR, 120, None, 0, 16, PTR, need - 1, None) == -12
+    assert lib.rsvd_stage_small_svd(h, None, F32, 100000, 120, PTR, 120, PTR, PTR, PTR, 120, 0, PTR, need, None) == ERR_NO_DEVICE
+    assert lib.rsvd_stage_workspace_bytes(h, F64, 64, 64, C.byref(out)) == 0
+    assert lib.rsvd_stage_jacobi(h, None, F64, 64, PTR, PTR, PTR, PTR, PTR, out.value, None) == ERR_NO_DEVICE
+    assert lib.rsvd_stage_workspace_bytes(h, 3, 64, 64, C.byref(out)) == -2
+    assert lib.rsvd_stage_workspace_bytes(h, F64, 0, 64, C.byref(out)) == -3
+    assert lib.rsvd_stage_workspace_bytes(h, F64, 64, 65, C.byref(out)) == -4
+    assert lib.rsvd_stage_workspace_bytes(h, F64, 64, 64, None) == -5
+
+
 def test_no_such_device_is_an_error(plan):
     h = C.c_void_p()
     lib = plan.lib
