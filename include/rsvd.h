@@ -124,6 +124,10 @@ int rsvd_workspace_bytes(rsvd_ctx *ctx, rsvd_dtype dtype, int64_t m, int64_t n,
  *          no synchronisation, no memset nodes, nothing read from the
  *          workspace before it is written - so it may be recorded into a HIP
  *          graph (after one ordinary call of the same shape) and replayed.
+ * Singular values that are numerically zero (below eps * ||B||_F, B = Q^T A):
+ * their rows of Vt are orthonormal like all the others, their columns of U are
+ * zero (the small SVD rotates the rows of the triangular factor of B^T and
+ * normalises what is left of them; nothing is left of these).
  * Requires k >= 1, p >= 0, q >= 0, k + p <= min(m, n).
  * Re-orthonormalisation inside the power scheme (step 2; the algorithm as
  * printed has none, it is there for floating point): after every product by
@@ -262,7 +266,14 @@ int rsvd_stage_small_svd(rsvd_ctx *ctx, void *stream, rsvd_dtype dtype,
                          rsvd_info *info);
 
 /* One-sided Jacobi SVD of a small square matrix alone: M (l x l, ld l, row-major,
- * overwritten) = X diag(sigma) W^T; sigma descending, X and W l x l (ld l). */
+ * overwritten) = X diag(sigma) W^T; sigma descending, X and W l x l (ld l).
+ * The rotations act on the columns of M (W accumulates them and is orthogonal
+ * to rounding whatever M is; a column of X that belongs to a numerically zero
+ * singular value is zero).  They converge in the fewest sweeps when the columns
+ * are graded in length, as the rows of a triangular factor are: for such an M
+ * pass its transpose and swap X and W (rsvd_run and rsvd_stage_small_svd do
+ * that with the factor of B^T).  RSVD_ERR_NO_CONVERGENCE after 30 sweeps
+ * (24 above the single-workgroup orders). */
 int rsvd_stage_jacobi(rsvd_ctx *ctx, void *stream, rsvd_dtype dtype, int64_t l,
                       void *M, void *sigma, void *X, void *W,
                       void *workspace, size_t workspace_bytes, rsvd_info *info);

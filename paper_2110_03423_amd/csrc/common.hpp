@@ -183,8 +183,12 @@ size_t jacobi_scratch_bytes(const rsvd_ctx *ctx, rsvd_dtype dtype, int64_t l);
 // One-sided Jacobi SVD  M = X diag(sigma) W^T  of the l x l row-major matrix M
 // (ld l; fp64 when m_is_f64 else `dtype`).  Outputs in `dtype`, sigma descending.
 // batch > 1 (LDS-resident orders only): problem b = blockIdx.x adds b * stride bytes to M, sigma, X, W.
+// rows != 0: the rotations act on the rows of M, i.e. M^T = X diag(sigma) W^T is what is decomposed (the
+// caller swaps X and W to get the factors of M).  One-sided Jacobi converges much faster on vectors of graded
+// length; of a triangular factor those are the rows.
 hipError_t jacobi_launch(rsvd_ctx *ctx, hipStream_t s, rsvd_dtype dtype, int64_t l,
                          const void *M, int m_is_f64, void *sigma, void *X, void *W,
-                         DevInfo *info, void *scratch, size_t scratch_bytes, int batch = 1, int64_t stride = 0);
+                         DevInfo *info, void *scratch, size_t scratch_bytes, int batch = 1, int64_t stride = 0,
+                         int rows = 0);
 
 }  // namespace rsvd

@@ -10,10 +10,14 @@
 //
 // Stopping rule (the paper gives none): a sweep in which every pair satisfies
 // |a_p . a_q| <= tol * ||a_p|| * ||a_q||, tol = eps * sqrt(l); at most 30 sweeps.
-// Jacobi converges quadratically (the paper: "3-4 iterations ... converges
-// quadratically"), so a sweep whose largest relative inner product rho was at
-// most sqrt(tol) / 4 leaves at most ~rho^2 < tol behind and is taken as the last
-// one, which saves the sweep that would only confirm it.
+// The sweep that would only confirm this is saved when the rate of the last two sweeps says what it would find
+// (jacobi_done below): with rho the largest relative inner product a sweep rotated away, the next sweep meets about
+// rho^2 where the method converges quadratically (the paper: "3-4 iterations ... converges quadratically"; taken for
+// granted only if the last step was at least of order 1.5 and rho <= sqrt(tol) / 4), and about rho^2 / rho_prev
+// where it does not - inside a cluster of nearly equal singular values the rotations are large however small the
+// inner products, and a sweep gains a constant factor only; there the sweep is saved once that estimate is below
+// 8 tol.  (Stopping on rho <= sqrt(tol) / 4 alone left 1e-4 (fp32) / 1e-10 (fp64) between the vectors of such a
+// cluster.)
 // A column whose norm has fallen below eps * ||M||_F counts as zero and is no
 // longer rotated (rotating it would change its partner by less than the
 // rounding level); without this floor the surplus columns of a rank-deficient M
@@ -29,6 +33,20 @@ constexpr int kJacobiMaxSweeps = 30;
 template <typename T> struct Eps;
 template <> struct Eps<float>  { static constexpr float  value = 1.1920929e-07f; };
 template <> struct Eps<double> { static constexpr double value = 2.220446049250313e-16; };
+
+// Was this sweep the last one?  rho: the largest relative inner product it rotated away (0: none), rho_prev: that
+// of the sweep before (negative: there was none).
+__host__ __device__ __forceinline__ bool jacobi_done(float rho, float rho_prev, float tol) {
+  if (rho <= tol) return true;
+  if (rho_prev < 0.f) return false;                                  // one sweep says nothing about the rate
+  if (rho <= 0.25f * sqrtf(tol) && rho <= rho_prev * sqrtf(rho_prev)) return true;      // next: ~rho^2 < tol
+  return rho * rho <= 8.f * tol * rho_prev;                          // next: ~rho^2 / rho_prev, a few tol at most
+}
+// The same from the per-sweep record of the block kernels: did the sweeps up to s - 1 finish the job?
+__device__ __forceinline__ bool jacobi_done_before(const int *counters, int s, float tol) {
+  if (s <= 0) return false;
+  return jacobi_done(__int_as_float(counters[s - 1]), s > 1 ? __int_as_float(counters[s - 2]) : -1.f, tol);
+}
 
 // DPP lane moves: no LDS traffic, unlike a shuffle.
 template <int CTRL> __device__ __forceinline__ float dpp_mov(float v) {
@@ -206,7 +224,7 @@ __host__ __device__ inline int jacobi_ldm(int l, int G, int elem_size) {
 template <typename T, typename TIn, int RPL, int G>
 __global__ __launch_bounds__(64 * G) void jacobi_lds_kernel(const TIn *__restrict__ M, int l, T *__restrict__ sigma,
                                                          T *__restrict__ X, T *__restrict__ W, DevInfo *info,
-                                                         int64_t stride) {
+                                                         int64_t stride, int rows) {
   extern __shared__ __attribute__((aligned(16))) double lds_raw[];
   if (blockIdx.x != 0) {              // batched launch: one problem per workgroup, `stride` bytes apart
     const int64_t off = (int64_t)blockIdx.x * stride;
@@ -258,7 +276,8 @@ __global__ __launch_bounds__(64 * G) void jacobi_lds_kernel(const TIn *__restric
     for (int idx = tid; idx < l * l; idx += nt) {
       const int r = idx / l, c = idx - r * l;
       const T v = (T)M[idx];
-      Mc[c * ldm + r] = v;
+      if (rows) Mc[r * ldm + c] = v;                      // the rows of M are what is rotated: M^T is decomposed
+      else Mc[c * ldm + r] = v;
       Jc[c * ldm + r] = (r == c) ? (T)1 : (T)0;
       fro2 += v * v;
     }
@@ -288,7 +307,7 @@ __global__ __launch_bounds__(64 * G) void jacobi_lds_kernel(const TIn *__restric
   const T tol = Eps<T>::value * sqrt((T)l);
   int sweeps = 0;
   bool converged = (l < 2);
-  const float rho_last = 0.25f * sqrtf((float)tol);
+  float rho_prev = -1.f;
   constexpr int NV = RPL / (8 / (int)sizeof(T));
   while (!converged && sweeps < kJacobiMaxSweeps) {
     ++sweeps;
@@ -321,7 +340,8 @@ __global__ __launch_bounds__(64 * G) void jacobi_lds_kernel(const TIn *__restric
     }
     if (rho > 0.f) atomicMax(&rotations, __float_as_int(rho));   // positive floats order like their bit patterns
     __syncthreads();
-    converged = (__int_as_float(rotations) <= rho_last);
+    converged = jacobi_done(__int_as_float(rotations), rho_prev, (float)tol);
+    rho_prev = __int_as_float(rotations);
     __syncthreads();
     if (tid == 0) rotations = 0;
     __syncthreads();
@@ -363,14 +383,17 @@ __global__ __launch_bounds__(64 * G) void jacobi_lds_kernel(const TIn *__restric
 // row c of Mt, contiguous).  The columns are cut into blocks of b; an outer
 // sweep is a round-robin tournament over the blocks, one kernel launch per
 // round, one workgroup per block pair.  The workgroup pulls its two blocks
-// (2b columns of length l) into LDS, runs inner sweeps of the same pairwise
-// rotations as above over those columns while accumulating them in a small
-// 2b x 2b matrix T, writes the columns back and applies T to the matching
-// columns of J.  Every rotation is an exact plane rotation of actual columns of
-// M, so accuracy and the stopping rule are those of the plain method.
-// counters[s] collects the rotations of outer sweep s; a launch of sweep s > 0
-// that finds counters[s-1] == 0 returns at once (converged), which keeps the
-// whole sequence free of host synchronisation.
+// (2b columns of length l) into LDS, runs the same pairwise rotations as above
+// over those columns while accumulating them in a small 2b x 2b matrix T,
+// writes the columns back and leaves T for the matching columns of J.  In the
+// launch that rotates the pairs inside one block every rotation is a plane
+// rotation of actual columns; the launches over block pairs take the rotations
+// from the Gram matrix of the panel and apply T once (jb_cross_kernel), or
+// rotate column by column where that panel does not fit in LDS (jb_panel_kernel).
+// counters[s] collects the largest relative inner product that outer sweep s
+// rotated away; a launch that finds the sweeps before it sufficient
+// (jacobi_done_before) returns at once, which keeps the whole sequence free of
+// host synchronisation.
 
 // Sum over the 32 lanes of a pair group: the 16-lane row by DPP (neighbours, pairs,
 // half-row mirror, row mirror), then one exchange with the partner row.
@@ -506,7 +529,7 @@ __global__ __launch_bounds__(256) void jb_fro_kernel(const double *__restrict__ 
 // the type whatever the scale of the input.  Grid of workgroups, each taking a slab of elements.
 template <typename T>
 __global__ __launch_bounds__(256) void jb_init_kernel(const double *__restrict__ M, int l, T *__restrict__ Mt,
-                                                      T *__restrict__ Jt, JbHeader *hdr) {
+                                                      T *__restrict__ Jt, JbHeader *hdr, int rows) {
   double fro2 = 0;
   for (int i = 0; i < kJbFroParts; ++i) fro2 += hdr->partial[i];
   double sc = 1.0, unscale = 1.0;
@@ -519,7 +542,7 @@ __global__ __launch_bounds__(256) void jb_init_kernel(const double *__restrict__
   for (int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; idx < (int64_t)l * l;
        idx += (int64_t)gridDim.x * blockDim.x) {
     const int r = (int)(idx / l), c = (int)(idx - (int64_t)r * l);
-    Mt[(int64_t)c * l + r] = (T)(M[idx] * sc);
+    Mt[rows ? idx : (int64_t)c * l + r] = (T)(M[idx] * sc);      // rows: M^T is decomposed, its columns are M's rows
     Jt[idx] = (r == c) ? (T)1 : (T)0;
   }
   if (blockIdx.x == 0) {
@@ -620,6 +643,23 @@ __device__ __forceinline__ void jb_apply_t(T *__restrict__ Jt, const T *__restri
   }
 }
 
+// J role of a launch: workgroup j behind the rot_wgs rotating ones applies the T that block pair g of the launch
+// before (phase, round, sweep = prev_*) left in the other slot of the ring to one chunk of rows of J.
+template <typename T>
+__device__ __forceinline__ void jb_j_role(T *__restrict__ Jt, int l, int b, int nblk, int rot_wgs, int prev_phase,
+                                          int prev_round, int prev_sweep, const T *__restrict__ Tring,
+                                          const int *__restrict__ chg, int slot, const JbHeader *hdr, float tol,
+                                          T *lds) {
+  const int chunks = (l + kJbRowChunk - 1) / kJbRowChunk;
+  const int j = (int)blockIdx.x - rot_wgs;
+  const int g = j / chunks;
+  if (jacobi_done_before(hdr->counters, prev_sweep, tol)) return;                  // that launch did nothing
+  const JbPair pr = jb_pair(prev_phase, prev_round, g, l, b, nblk);
+  const int pslot = slot ^ 1;
+  if (!pr.valid || chg[pslot * nblk + g] == 0) return;
+  jb_apply_t<T>(Jt, Tring + ((size_t)pslot * nblk + g) * (size_t)(4 * b * b), l, b, pr, j - g * chunks, lds);
+}
+
 template <typename T, int NV>
 __global__ __launch_bounds__(1024) void jb_panel_kernel(T *__restrict__ Mt, T *__restrict__ Jt, int l, int b,
                                                         int nblk, int phase, int round, int sweep, int rot_wgs,
@@ -627,23 +667,13 @@ __global__ __launch_bounds__(1024) void jb_panel_kernel(T *__restrict__ Mt, T *_
                                                         T *__restrict__ Tring, int *__restrict__ chg, int slot,
                                                         JbHeader *hdr) {
   const T tol = Eps<T>::value * sqrt((T)l);
-  const float rho_last = 0.25f * sqrtf((float)tol);            // see the stopping rule at the top of this file
   extern __shared__ __attribute__((aligned(16))) double lds_raw[];
   if ((int)blockIdx.x >= rot_wgs) {
-    // J role: the launch before (phase, round, sweep = prev_*) left its T in the other slot
-    const int chunks = (l + kJbRowChunk - 1) / kJbRowChunk;
-    const int j = (int)blockIdx.x - rot_wgs;
-    const int g = j / chunks;
-    if (prev_sweep > 0 && __int_as_float(hdr->counters[prev_sweep - 1]) <= rho_last) return;   // that launch did nothing
-    const JbPair pr = jb_pair(prev_phase, prev_round, g, l, b, nblk);
-    const int pslot = slot ^ 1;
-    if (!pr.valid || chg[pslot * nblk + g] == 0) return;
-    jb_apply_t<T>(Jt, Tring + ((size_t)pslot * nblk + g) * (size_t)(4 * b * b), l, b, pr, j - g * chunks,
-                  reinterpret_cast<T *>(lds_raw));
+    jb_j_role<T>(Jt, l, b, nblk, rot_wgs, prev_phase, prev_round, prev_sweep, Tring, chg, slot, hdr, (float)tol,
+                 reinterpret_cast<T *>(lds_raw));
     return;
   }
-  // converged in the previous sweep
-  if (sweep > 0 && __int_as_float(hdr->counters[sweep - 1]) <= rho_last) return;
+  if (jacobi_done_before(hdr->counters, sweep, (float)tol)) return;        // the sweeps before finished the job
   const JbPair pr = jb_pair(phase, round, (int)blockIdx.x, l, b, nblk);
   if (!pr.valid) return;                                       // bye
   const int bi = pr.bi, bj = pr.bj, cols_i = pr.cols_i, cols_j = pr.cols_j;
@@ -787,6 +817,295 @@ __global__ __launch_bounds__(1024) void jb_panel_kernel(T *__restrict__ Mt, T *_
   }
 }
 
+// ---- cross phase through the Gram matrix of the block pair ----
+//
+// The b rounds of a cross launch rotate 2b columns of length l; done column by column (jb_panel_kernel) a round
+// costs ~1 us of plain vector instructions whatever l is.  The rotations only need inner products, and those
+// follow from the 2b x 2b Gram matrix G of the panel: G is formed once on the matrix cores, the b rounds rotate G
+// on both sides (G <- J^T G J, a 2 x 2 block per thread) and accumulate T <- T J, and the panel is multiplied by T
+// once, again on the matrix cores.  Pair order, rotation formulas, thresholds and the stopping rule are those of
+// the column-by-column kernel; the first round sees exact inner products, later rounds the tracked ones (their
+// error is of second order in the rotation angles and is wiped out by the next launch, which forms G afresh).
+constexpr int kJgB = 16;                    // block width this kernel is written for
+constexpr int kJgN = 2 * kJgB;              // columns of a panel
+constexpr int kJgLd = kJgN + 1;             // row stride of G and T in LDS
+constexpr int kJgMat = kJgN * kJgLd;        // elements of one such matrix
+constexpr int kJgPart = 3 * 256;            // elements of one partial sum of G (three 16 x 16 blocks)
+
+// Column stride of the panel in LDS: l padded to whole 16-row blocks, plus what spreads 16 columns over the banks.
+template <typename T> __host__ __device__ constexpr int jg_ldp(int l) {
+  return (l + 15) / 16 * 16 + (sizeof(T) == 4 ? 2 : 1);
+}
+template <typename T> __host__ __device__ constexpr size_t jg_lds_bytes(int l) {
+  return ((size_t)kJgN * jg_ldp<T>(l) + 5 * (size_t)kJgMat) * sizeof(T);
+}
+
+// Rotation of pair `a` in round r (columns p = a and q = b + (a + r) mod b of the panel), from the tracked Gram
+// matrix: (c, s) = (1, 0) when the pair is left alone; returns the relative inner product that is rotated away
+// (0 if none).  Without branches: the chain of dependent instructions of a round starts here.
+template <typename T>
+__device__ __forceinline__ float jg_pair_params(const T *G, int a, int r, int cols_i, int cols_j, T tol, T floor2,
+                                                int &q, T &c, T &s) {
+  const int qi = (a + r) & (kJgB - 1);
+  q = kJgB + qi;
+  const T alpha = G[a * kJgLd + a], beta = G[q * kJgLd + q], gamma = G[a * kJgLd + q];
+  const T rel = fabs(gamma) * fast_rsq(alpha * beta);
+  const bool rot = (a < cols_i) & (qi < cols_j) & (alpha > floor2) & (beta > floor2) & (rel > tol);
+  const T g = rot ? gamma : (T)1;
+  const T zeta = (beta - alpha) * fast_rcp((T)2 * g);
+  const T az = fabs(zeta);
+  T cc, ss;
+  if constexpr (sizeof(T) == 4) {
+    // t = 1 / (|zeta| + sqrt(1 + zeta^2)), c = 1 / sqrt(1 + t^2), s = c t: s tied to c, so that c^2 + s^2 - 1 stays
+    // at the 1e-9 level in fp32 (the columns of T and J keep their length over thousands of rotations)
+    const T t_small = (T)0.5 * fast_rcp(az);                     // |zeta| > 1e7: zeta^2 would overflow
+    const T t_usual = fast_rcp(az + fast_sqrt((T)1 + zeta * zeta));
+    const T t = az > (T)1e7 ? t_small : t_usual;
+    cc = fast_rsq((T)1 + t * t);
+    ss = cc * t;
+  } else {
+    // the same rotation with one reciprocal square root less on the chain of dependent instructions (each costs
+    // two Newton steps in fp64): with w = sqrt(1 + zeta^2), c^2 = (|zeta| + w) / (2 w), s^2 = 1 / (2 w (|zeta| + w))
+    const T q2 = (T)1 + zeta * zeta;
+    const T u = fast_rsq(q2);
+    const T w = q2 * u;
+    const T c_usual = fast_sqrt((T)0.5 + (T)0.5 * az * u);
+    const T s_usual = fast_rsq((T)2 * w * (az + w));
+    const bool huge = az > (T)1e100;                             // zeta^2 would overflow; t = 1 / (2 |zeta|)
+    cc = huge ? (T)1 : c_usual;
+    ss = huge ? (T)0.5 * fast_rcp(az) : s_usual;
+  }
+  ss = zeta < (T)0 ? -ss : ss;
+  c = rot ? cc : (T)1;
+  s = rot ? ss : (T)0;
+  return rot ? (float)rel : 0.f;
+}
+
+template <typename T> __device__ __forceinline__ T lane_read(T v, int src_lane);
+template <> __device__ __forceinline__ float lane_read<float>(float v, int src_lane) {
+  return __int_as_float(__builtin_amdgcn_ds_bpermute(src_lane << 2, __float_as_int(v)));
+}
+template <> __device__ __forceinline__ double lane_read<double>(double v, int src_lane) {
+  const long long b = __double_as_longlong(v);
+  const int lo = __builtin_amdgcn_ds_bpermute(src_lane << 2, (int)b);
+  const int hi = __builtin_amdgcn_ds_bpermute(src_lane << 2, (int)(b >> 32));
+  return __longlong_as_double(((long long)hi << 32) | (long long)(unsigned int)lo);
+}
+
+template <typename T>
+__global__ __launch_bounds__(1024) void jb_cross_kernel(T *__restrict__ Mt, T *__restrict__ Jt, int l, int nblk,
+                                                        int round, int sweep, int rot_wgs, int prev_phase,
+                                                        int prev_round, int prev_sweep, T *__restrict__ Tring,
+                                                        int *__restrict__ chg, int slot, JbHeader *hdr) {
+  constexpr int b = kJgB;
+  const T tol = Eps<T>::value * sqrt((T)l);
+  extern __shared__ __attribute__((aligned(16))) double lds_raw[];
+  if ((int)blockIdx.x >= rot_wgs) {
+    jb_j_role<T>(Jt, l, b, nblk, rot_wgs, prev_phase, prev_round, prev_sweep, Tring, chg, slot, hdr, (float)tol,
+                 reinterpret_cast<T *>(lds_raw));
+    return;
+  }
+  if (jacobi_done_before(hdr->counters, sweep, (float)tol)) return;        // the sweeps before finished the job
+  const JbPair pr = jb_pair(1, round, (int)blockIdx.x, l, b, nblk);
+  if (!pr.valid) return;                                       // bye
+  const int cols_i = pr.cols_i, cols_j = pr.cols_j, ncols = cols_i + cols_j;
+  const int ldp = jg_ldp<T>(l), lp = (l + 15) / 16 * 16;
+  T *Pc = reinterpret_cast<T *>(lds_raw);                      // [2b][ldp]: column c of the panel, zero padded
+  T *G0 = Pc + (size_t)kJgN * ldp;                             // G, even rounds
+  T *R4 = G0 + kJgMat;                                         // four matrices: the five partial sums of G, then T0, T1, G1 and the (c, s) of every round
+  __shared__ int rotations;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int r16 = lane & 15, kq = lane >> 4;
+  auto gcol = [&](int c) { return c < b ? pr.bi * b + c : pr.bj * b + (c - b); };      // global column of panel column c
+  auto live = [&](int c) { return c < b ? c < cols_i : c - b < cols_j; };
+
+  // panel in: wavefront w takes columns w and w + 16, every load in flight before the first LDS store
+  {
+    constexpr int MAXJ = sizeof(T) == 4 ? 17 : 8;              // 64 * MAXJ rows at most (the LDS limit is lower)
+    T v[2][MAXJ];
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+      const int c = wave + 16 * u;
+      const T *src = Mt + (int64_t)gcol(live(c) ? c : 0) * l;
+#pragma unroll
+      for (int j = 0; j < MAXJ; ++j) {
+        const int rr = lane + 64 * j;
+        v[u][j] = (live(c) && rr < l) ? src[rr] : (T)0;
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+      const int c = wave + 16 * u;
+#pragma unroll
+      for (int j = 0; j < MAXJ; ++j) {
+        const int rr = lane + 64 * j;
+        if (rr < lp) Pc[c * ldp + rr] = v[u][j];
+      }
+    }
+  }
+  if (tid == 0) rotations = 0;
+  __syncthreads();
+
+  // G = P^T P: wavefront w takes 16 x 16 block (ti, tj) over the quarter sl of the rows, eight k-steps of
+  // operands at a time ahead of their matrix instructions, two accumulators
+  typedef typename Mfma<T>::vec acc_t;
+  {
+    // (G is symmetric: blocks (0,0), (0,1) and (1,1) only, five row slices each, fifteen wavefronts)
+    const int sl = wave / 3, tile = wave - 3 * sl;
+    const int ti = tile >> 1, tj = (tile + 1) >> 1;
+    const int steps = lp / 4, per = (steps + 4) / 5;
+    const int s0 = sl * per, s1 = (wave == 15) ? 0 : ((s0 + per < steps) ? s0 + per : steps);
+    acc_t acc0 = (acc_t)(T)0, acc1 = (acc_t)(T)0;
+    const T *ap = Pc + (ti * 16 + r16) * ldp + kq;
+    const T *bp = Pc + (tj * 16 + r16) * ldp + kq;
+    for (int st = s0; st < s1; st += 8) {
+      T av[8], bv[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        const bool ok = st + u < s1;
+        av[u] = ok ? ap[4 * (st + u)] : (T)0;
+        bv[u] = ok ? bp[4 * (st + u)] : (T)0;
+      }
+#pragma unroll
+      for (int u = 0; u < 8; u += 2) {
+        acc0 = Mfma<T>::run(av[u], bv[u], acc0);
+        acc1 = Mfma<T>::run(av[u + 1], bv[u + 1], acc1);
+      }
+    }
+    if (wave < 15) {
+      T *dst = R4 + sl * kJgPart + tile * 256;
+#pragma unroll
+      for (int v = 0; v < 4; ++v) dst[Mfma<T>::row(lane, v) * 16 + r16] = acc0[v] + acc1[v];
+    }
+  }
+  __syncthreads();
+  {
+    // entry (i, j) of G from the five partial sums of its block (the block above the diagonal read transposed below it)
+    const int i = tid >> 5, j = tid & 31;
+    const int bi2 = i >> 4, bj2 = j >> 4;
+    const bool lower = bi2 > bj2;
+    const int tile = lower ? 1 : bi2 + bj2;
+    const int e = tile * 256 + (lower ? (j & 15) * 16 + (i & 15) : (i & 15) * 16 + (j & 15));
+    G0[i * kJgLd + j] = ((R4[e] + R4[kJgPart + e]) + (R4[2 * kJgPart + e] + R4[3 * kJgPart + e])) + R4[4 * kJgPart + e];
+  }
+  __syncthreads();
+  T *Tb[2] = {R4, R4 + kJgMat};
+  T *Gb[2] = {G0, R4 + 2 * kJgMat};
+  {
+    const int i = tid >> 5, j = tid & 31;
+    Tb[0][i * kJgLd + j] = (i == j) ? (T)1 : (T)0;
+  }
+  __syncthreads();
+
+  // b rounds.  Wavefronts 0-3 (one per SIMD: the chain of dependent instructions of a round is theirs alone):
+  // G <- J^T G J, thread (a, bb) the rows of pair a and the columns of pair bb; every lane works out the rotation of
+  // pair bb = lane mod 16, fetches that of pair a from lane a, and the first sixteen leave (c, s) of the round in
+  // LDS.  Wavefronts 4-11: T <- T J one round behind, thread (rr, bb) row rr and the columns of pair bb.  One barrier
+  // per round (G and T alternate between two copies).
+  const T floor2 = (T)(Eps<T>::value * Eps<T>::value * hdr->fro2);
+  T *CS = R4 + 3 * kJgMat;                                     // [b rounds][16 pairs][c, s], in the fourth matrix
+  float rho = 0.f;
+  const int bb = tid & 15;
+  auto rotate_t = [&](int r) {                                 // T <- T J_r
+    const T *Ts = Tb[r & 1];
+    T *Td = Tb[(r & 1) ^ 1];
+    const int rr = (tid - 256) >> 4;
+    const int qb = kJgB + ((bb + r) & (kJgB - 1));
+    const T cb = CS[(r * 16 + bb) * 2], sb = CS[(r * 16 + bb) * 2 + 1];
+    const T tp = Ts[rr * kJgLd + bb], tq = Ts[rr * kJgLd + qb];
+    Td[rr * kJgLd + bb] = cb * tp - sb * tq;
+    Td[rr * kJgLd + qb] = sb * tp + cb * tq;
+  };
+  for (int r = 0; r < b; ++r) {
+    if (tid < 256) {
+      const T *Gs = Gb[r & 1];
+      T *Gd = Gb[(r & 1) ^ 1];
+      int qb;
+      T cb, sb;
+      const float rel = jg_pair_params<T>(Gs, bb, r, cols_i, cols_j, tol, floor2, qb, cb, sb);
+      const int a = tid >> 4;
+      const int qa = kJgB + ((a + r) & (kJgB - 1));
+      const T g00 = Gs[a * kJgLd + bb], g01 = Gs[a * kJgLd + qb];
+      const T g10 = Gs[qa * kJgLd + bb], g11 = Gs[qa * kJgLd + qb];
+      const T ca = lane_read<T>(cb, a), sa = lane_read<T>(sb, a);
+      const T h00 = ca * g00 - sa * g10, h01 = ca * g01 - sa * g11;
+      const T h10 = sa * g00 + ca * g10, h11 = sa * g01 + ca * g11;
+      T n00 = cb * h00 - sb * h01, n01 = sb * h00 + cb * h01;
+      T n10 = cb * h10 - sb * h11, n11 = sb * h10 + cb * h11;
+      if (a == bb && rel > 0.f) {
+        n01 = (T)0;
+        n10 = (T)0;
+        rho = fmaxf(rho, rel);
+      }
+      Gd[a * kJgLd + bb] = n00; Gd[a * kJgLd + qb] = n01;
+      Gd[qa * kJgLd + bb] = n10; Gd[qa * kJgLd + qb] = n11;
+      if (a == 0) {
+        CS[(r * 16 + bb) * 2] = cb;
+        CS[(r * 16 + bb) * 2 + 1] = sb;
+      }
+    } else if (tid < 768 && r > 0) {
+      rotate_t(r - 1);
+    }
+    __syncthreads();
+  }
+  if (tid >= 256 && tid < 768) rotate_t(b - 1);
+  if (rho > 0.f) atomicMax(&rotations, __float_as_int(rho));
+  __syncthreads();
+  const int rho_bits = rotations;
+  if (rho_bits == 0) {                                        // nothing changed: leave M alone, no T to apply
+    if (tid == 0) chg[slot * nblk + blockIdx.x] = 0;
+    return;
+  }
+  const T *Tf = Tb[b & 1];                                    // T[k][j]
+  // panel out: (P T)^T = T^T P^T in 16 x 16 blocks; wavefront w takes the output columns jb * 16 ... and the row
+  // blocks rb, rb + 8, ..., two of them at a time
+  {
+    const int jb = wave & 1;
+    T ta[kJgN / 4];
+#pragma unroll
+    for (int ks = 0; ks < kJgN / 4; ++ks) ta[ks] = Tf[(4 * ks + kq) * kJgLd + jb * 16 + r16];     // A[i = column][k] = T[k][column]
+    const int nrb = lp / 16;
+    for (int rb = wave >> 1; rb < nrb; rb += 16) {
+      const int rb2 = rb + 8;
+      const bool two = rb2 < nrb;
+      const T *bp0 = Pc + kq * ldp + rb * 16 + r16;                                              // B[k][n = row] = P[row][k]
+      const T *bp1 = Pc + kq * ldp + (two ? rb2 : rb) * 16 + r16;
+      T b0[kJgN / 4], b1[kJgN / 4];
+#pragma unroll
+      for (int ks = 0; ks < kJgN / 4; ++ks) { b0[ks] = bp0[(4 * ks) * ldp]; b1[ks] = bp1[(4 * ks) * ldp]; }
+      acc_t acc0 = (acc_t)(T)0, acc1 = (acc_t)(T)0;
+#pragma unroll
+      for (int ks = 0; ks < kJgN / 4; ++ks) {
+        acc0 = Mfma<T>::run(ta[ks], b0[ks], acc0);
+        acc1 = Mfma<T>::run(ta[ks], b1[ks], acc1);
+      }
+#pragma unroll
+      for (int v = 0; v < 4; ++v) {
+        const int c = jb * 16 + Mfma<T>::row(lane, v);
+        if (live(c)) {
+          T *dst = Mt + (int64_t)gcol(c) * l;
+          if (rb * 16 + r16 < l) dst[rb * 16 + r16] = acc0[v];
+          if (two && rb2 * 16 + r16 < l) dst[rb2 * 16 + r16] = acc1[v];
+        }
+      }
+    }
+  }
+  T *Tg = Tring + ((size_t)slot * nblk + blockIdx.x) * (size_t)(4 * b * b);
+  {
+    // ring format: Tg[c * 2b + k] = T[k][c] over the live columns, packed (those of the first block, then the second)
+    const int c = tid >> 5, k = tid & 31;
+    auto unpack = [&](int x) { return x < cols_i ? x : b + (x - cols_i); };
+    T val = (T)0;
+    if (c < ncols && k < ncols) val = Tf[unpack(k) * kJgLd + unpack(c)];
+    else if (c == k) val = (T)1;
+    Tg[c * (2 * b) + k] = val;
+  }
+  if (tid == 0) {
+    chg[slot * nblk + blockIdx.x] = 1;
+    atomicMax(&hdr->counters[sweep], rho_bits);
+  }
+}
+
 // Column norms (one wavefront per column), then ranks by counting, then the scatter.
 template <typename T>
 __global__ __launch_bounds__(256) void jb_norms_kernel(const T *__restrict__ Mt, int l, T *__restrict__ nrm) {
@@ -815,12 +1134,12 @@ __global__ __launch_bounds__(256) void jb_rank_kernel(const T *__restrict__ nrm,
     sigma[rank] = mine * (T)hdr->unscale;
   }
   if (j == 0 && info != nullptr) {
-    const float rho_last = 0.25f * sqrtf((float)(Eps<T>::value * sqrt((T)l)));
+    const float tol = (float)(Eps<T>::value * sqrt((T)l));
     int used = max_sweeps;
-    for (int s = 0; s < max_sweeps; ++s)
-      if (__int_as_float(hdr->counters[s]) <= rho_last) { used = s + 1; break; }
+    for (int s = 1; s <= max_sweeps; ++s)
+      if (jacobi_done_before(hdr->counters, s, tol)) { used = s; break; }
     atomicMax(&info->jacobi_sweeps, used);
-    if (__int_as_float(hdr->counters[max_sweeps - 1]) > rho_last) atomicMax(&info->status, (int)RSVD_ERR_NO_CONVERGENCE);
+    if (!jacobi_done_before(hdr->counters, max_sweeps, tol)) atomicMax(&info->status, (int)RSVD_ERR_NO_CONVERGENCE);
   }
 }
 
@@ -897,7 +1216,7 @@ size_t jacobi_scratch_bytes(const rsvd_ctx *ctx, rsvd_dtype dtype, int64_t l) {
 
 template <typename T>
 static hipError_t jacobi_block_launch(rsvd_ctx *ctx, hipStream_t s, rsvd_dtype dtype, int l, const double *M,
-                                      T *sigma, T *X, T *W, DevInfo *info, char *scratch) {
+                                      T *sigma, T *X, T *W, DevInfo *info, char *scratch, int rows) {
   const int b = jb_block_width(ctx, dtype, l);
   if (b == 0) return hipErrorNotSupported;
   const size_t es = sizeof(T);
@@ -917,19 +1236,26 @@ static hipError_t jacobi_block_launch(rsvd_ctx *ctx, hipStream_t s, rsvd_dtype d
   const size_t lds_j = ((size_t)(2 * b) * (kJbRowChunk + 8) + (size_t)(2 * b) * (2 * b + 2)) * es;   // jb_apply_t
   const size_t lds = lds_rot > lds_j ? lds_rot : lds_j;
   const int chunks = (l + kJbRowChunk - 1) / kJbRowChunk;
+  // cross launches go through the Gram matrix of the block pair when its panel of 2b columns fits in LDS
+  const bool gram_cross = b == kJgB && jg_lds_bytes<T>(l) + 1024 <= ctx->lds_per_block;
+  const size_t lds_gram = jg_lds_bytes<T>(l) > lds_j ? jg_lds_bytes<T>(l) : lds_j;
   ProfScope ps(ctx, s, PK_JACOBI);
   hipLaunchKernelGGL(jb_fro_kernel, dim3(kJbFroParts), dim3(256), 0, s, M, l, hdr);
   {
     int64_t blocks = ((int64_t)l * l + 255) / 256;
     if (blocks > 1024) blocks = 1024;
-    hipLaunchKernelGGL((jb_init_kernel<T>), dim3((unsigned)blocks), dim3(256), 0, s, M, l, Mt, Jt, hdr);
+    hipLaunchKernelGGL((jb_init_kernel<T>), dim3((unsigned)blocks), dim3(256), 0, s, M, l, Mt, Jt, hdr, rows);
   }
 #define RSVD_JB_CASE(NVV)                                                                                        \
   case NVV: {                                                                                                    \
     int slot = 0, pp = -1, pr = 0, psw = 0, pwgs = 0;          /* the launch before: phase, round, sweep, pairs */ \
     auto go = [&](int phase, int round, int sweep, int wgs) {                                                    \
-      hipLaunchKernelGGL((jb_panel_kernel<T, NVV>), dim3(wgs + pwgs * chunks), dim3(1024), lds, s, Mt, Jt, l, b, \
-                         nblk, phase, round, sweep, wgs, pp, pr, psw, Tring, chg, slot, hdr);                    \
+      if (phase == 1 && wgs > 0 && gram_cross)                                                                   \
+        hipLaunchKernelGGL((jb_cross_kernel<T>), dim3(wgs + pwgs * chunks), dim3(1024), lds_gram, s, Mt, Jt, l,  \
+                           nblk, round, sweep, wgs, pp, pr, psw, Tring, chg, slot, hdr);                         \
+      else                                                                                                       \
+        hipLaunchKernelGGL((jb_panel_kernel<T, NVV>), dim3(wgs + pwgs * chunks), dim3(1024), lds, s, Mt, Jt, l,  \
+                           b, nblk, phase, round, sweep, wgs, pp, pr, psw, Tring, chg, slot, hdr);               \
       pp = phase; pr = round; psw = sweep; pwgs = wgs; slot ^= 1;                                                \
     };                                                                                                           \
     for (int sweep = 0; sweep < kJbMaxSweeps; ++sweep) {                                                         \
@@ -954,31 +1280,31 @@ static hipError_t jacobi_block_launch(rsvd_ctx *ctx, hipStream_t s, rsvd_dtype d
 
 template <typename T, typename TIn, int RPL, int G>
 static hipError_t launch_lds(hipStream_t s, int nt, size_t lds, const void *M, int l, void *sigma, void *X, void *W,
-                             DevInfo *info, int batch, int64_t stride) {
+                             DevInfo *info, int batch, int64_t stride, int rows) {
   hipLaunchKernelGGL((jacobi_lds_kernel<T, TIn, RPL, G>), dim3(batch), dim3(nt), lds, s, (const TIn *)M, l,
-                     (T *)sigma, (T *)X, (T *)W, info, stride);
+                     (T *)sigma, (T *)X, (T *)W, info, stride, rows);
   return hipGetLastError();
 }
 
 // rows per lane = padded rows / G
 template <typename T, typename TIn>
 static hipError_t launch_lds_g(hipStream_t s, int nt, int G, int rpl, size_t lds, const void *M, int l, void *sigma,
-                               void *X, void *W, DevInfo *info, int batch, int64_t stride) {
+                               void *X, void *W, DevInfo *info, int batch, int64_t stride, int rows) {
   if (G == 16) {
     // fp32 rows come in pairs (8-byte units), fp64 rows singly
     if constexpr (sizeof(T) == 8) {
       switch (rpl) {
-        case 1: return launch_lds<T, TIn, 1, 16>(s, nt, lds, M, l, sigma, X, W, info, batch, stride);
-        case 3: return launch_lds<T, TIn, 3, 16>(s, nt, lds, M, l, sigma, X, W, info, batch, stride);
-        case 5: return launch_lds<T, TIn, 5, 16>(s, nt, lds, M, l, sigma, X, W, info, batch, stride);
+        case 1: return launch_lds<T, TIn, 1, 16>(s, nt, lds, M, l, sigma, X, W, info, batch, stride, rows);
+        case 3: return launch_lds<T, TIn, 3, 16>(s, nt, lds, M, l, sigma, X, W, info, batch, stride, rows);
+        case 5: return launch_lds<T, TIn, 5, 16>(s, nt, lds, M, l, sigma, X, W, info, batch, stride, rows);
         default: break;
       }
     }
     switch (rpl) {
-      case 2: return launch_lds<T, TIn, 2, 16>(s, nt, lds, M, l, sigma, X, W, info, batch, stride);
-      case 4: return launch_lds<T, TIn, 4, 16>(s, nt, lds, M, l, sigma, X, W, info, batch, stride);
-      case 6: return launch_lds<T, TIn, 6, 16>(s, nt, lds, M, l, sigma, X, W, info, batch, stride);
-      case 8: return launch_lds<T, TIn, 8, 16>(s, nt, lds, M, l, sigma, X, W, info, batch, stride);
+      case 2: return launch_lds<T, TIn, 2, 16>(s, nt, lds, M, l, sigma, X, W, info, batch, stride, rows);
+      case 4: return launch_lds<T, TIn, 4, 16>(s, nt, lds, M, l, sigma, X, W, info, batch, stride, rows);
+      case 6: return launch_lds<T, TIn, 6, 16>(s, nt, lds, M, l, sigma, X, W, info, batch, stride, rows);
+      case 8: return launch_lds<T, TIn, 8, 16>(s, nt, lds, M, l, sigma, X, W, info, batch, stride, rows);
       default: return hipErrorNotSupported;
     }
   }
@@ -1021,12 +1347,18 @@ hipError_t jacobi_init_device(rsvd_ctx *ctx) {
   raise_lds_limit_lds<double, double, 8>(e);
   raise_lds_limit_panels<float>(e);
   raise_lds_limit_panels<double>(e);
+  if (e == hipSuccess)
+    e = hipFuncSetAttribute(reinterpret_cast<const void *>(&jb_cross_kernel<float>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 4096);
+  if (e == hipSuccess)
+    e = hipFuncSetAttribute(reinterpret_cast<const void *>(&jb_cross_kernel<double>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 4096);
   return e;
 }
 
 hipError_t jacobi_launch(rsvd_ctx *ctx, hipStream_t s, rsvd_dtype dtype, int64_t l, const void *M,
                          int m_is_f64, void *sigma, void *X, void *W, DevInfo *info, void *scratch,
-                         size_t scratch_bytes, int batch, int64_t stride) {
+                         size_t scratch_bytes, int batch, int64_t stride, int rows) {
   if (batch < 1 || batch > 65535) return hipErrorInvalidValue;
   if (l > jacobi_max_lds_order(ctx, dtype)) {
     if (batch != 1) return hipErrorNotSupported;       // the block path is not batched
@@ -1035,9 +1367,9 @@ hipError_t jacobi_launch(rsvd_ctx *ctx, hipStream_t s, rsvd_dtype dtype, int64_t
     if (need == 0 || scratch == nullptr || scratch_bytes < need || !m_is_f64) return hipErrorNotSupported;
     if (dtype == RSVD_F32)
       return jacobi_block_launch<float>(ctx, s, dtype, (int)l, (const double *)M, (float *)sigma, (float *)X,
-                                        (float *)W, info, (char *)scratch);
+                                        (float *)W, info, (char *)scratch, rows);
     return jacobi_block_launch<double>(ctx, s, dtype, (int)l, (const double *)M, (double *)sigma, (double *)X,
-                                       (double *)W, info, (char *)scratch);
+                                       (double *)W, info, (char *)scratch, rows);
   }
   // one G-lane group per column pair of a round, all pairs of a round at once
   const int npairs = (int)((l + 1) / 2);
@@ -1048,10 +1380,10 @@ hipError_t jacobi_launch(rsvd_ctx *ctx, hipStream_t s, rsvd_dtype dtype, int64_t
   const size_t lds = jacobi_lds_bytes(dtype, l);
   ProfScope ps(ctx, s, PK_JACOBI);
   if (dtype == RSVD_F32) {
-    if (m_is_f64) return launch_lds_g<float, double>(s, nt, G, g, lds, M, (int)l, sigma, X, W, info, batch, stride);
-    return launch_lds_g<float, float>(s, nt, G, g, lds, M, (int)l, sigma, X, W, info, batch, stride);
+    if (m_is_f64) return launch_lds_g<float, double>(s, nt, G, g, lds, M, (int)l, sigma, X, W, info, batch, stride, rows);
+    return launch_lds_g<float, float>(s, nt, G, g, lds, M, (int)l, sigma, X, W, info, batch, stride, rows);
   }
-  return launch_lds_g<double, double>(s, nt, G, g, lds, M, (int)l, sigma, X, W, info, batch, stride);
+  return launch_lds_g<double, double>(s, nt, G, g, lds, M, (int)l, sigma, X, W, info, batch, stride, rows);
 }
 
 }  // namespace rsvd

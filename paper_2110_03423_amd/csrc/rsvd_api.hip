@@ -407,9 +407,12 @@ static int small_svd(rsvd_ctx *ctx, hipStream_t s, rsvd_dtype dtype, const Ws &w
   const Layout &L = w.L;
   int rc = orthonormalize(ctx, s, dtype, w, n, l, Bt, ldbt, tmp, w.at<double>(L.Rb), seed, refill_stream);
   if (rc) return rc;
-  hipError_t e = jacobi_launch(ctx, s, dtype, l, w.at<void>(L.Rb), 1, w.at<void>(L.sigma), w.at<void>(L.Xj),
-                               w.at<void>(L.Wj), w.at<DevInfo>(L.info), w.at<void>(L.jac_scratch),
-                               L.jac_scratch_bytes, w.batch, w.stride);
+  // Rb = X Sigma W^T from the rows of Rb, i.e. from Rb^T = W Sigma X^T (hence the swapped outputs): the rows of the
+  // triangular factor are graded like the singular values, its columns are not, and the rotations converge in
+  // about half the sweeps on the former when the spectrum is steep (a third when the factor is rank deficient)
+  hipError_t e = jacobi_launch(ctx, s, dtype, l, w.at<void>(L.Rb), 1, w.at<void>(L.sigma), w.at<void>(L.Wj),
+                               w.at<void>(L.Xj), w.at<DevInfo>(L.info), w.at<void>(L.jac_scratch),
+                               L.jac_scratch_bytes, w.batch, w.stride, 1);
   if (e == hipErrorNotSupported) return RSVD_ERR_UNSUPPORTED;
   RSVD_TRY(e, "jacobi");
   return 0;

@@ -310,7 +310,8 @@ def test_ill_conditioned_panel_keeps_the_full_schedule():
 @pytest.mark.parametrize("dt", ["f32", "f64"])
 def test_degenerate_inputs(dt):
     """Zero and constant matrices, a single row, a single column, 1 x 1: finite outputs, the singular values of the
-    textbook answer, orthonormal left vectors; nothing hangs and nothing is flagged."""
+    textbook answer, orthonormal right vectors (the left vectors of singular values that are numerically zero
+    come back as zero columns); nothing hangs and nothing is flagged."""
     say("degenerate", dt)
     T = np.float32 if dt == "f32" else np.float64
     eps = parity.EPS[dt]
@@ -325,7 +326,8 @@ def test_degenerate_inputs(dt):
 
     S, U, Vt, info = run(np.zeros((300, 200)), 5, 5, 2)
     assert (S == 0).all() and info.refilled_columns > 0
-    assert parity.orthonormality(U) <= 50 * eps                    # arbitrary, but orthonormal
+    assert parity.orthonormality(Vt.T) <= 50 * eps                 # arbitrary, but orthonormal
+    assert (U == 0).all()                                          # no direction belongs to a zero singular value
     S, U, Vt, _ = run(np.full((300, 200), 3.0), 4, 4, 1)
     assert S[0] == pytest.approx(3.0 * np.sqrt(300 * 200), rel=20 * eps) and (S[1:] <= 1e3 * eps * S[0]).all()
     assert np.abs(np.abs(U[:, 0]) - 1 / np.sqrt(300)).max() <= 50 * eps

@@ -276,6 +276,48 @@ def test_small_svd_of_projected_factor(dt, n, l):
     assert np.abs(np.abs(np.sum(V * Vto.T, axis=0)) - 1).max() <= 100 * l * eps / gap
 
 
+HARD_FACTORS = [  # (dtype, n, l, singular values of B): steep decays and flat clusters, orders on both Jacobi paths
+    ("f32", 900, 96, lambda i, l: 10.0 ** (-i / 16.0), 12),                      # six decades
+    ("f32", 1200, 261, lambda i, l: 10.0 ** (-i / 40.0), 12),                    # six and a half, block path
+    ("f64", 800, 60, lambda i, l: 10.0 ** (-i / 5.0), 12),                       # twelve decades
+    ("f64", 1000, 200, lambda i, l: 10.0 ** (-i / 20.0), 12),                    # ten, block path
+    # flat clusters: inside one the sweeps gain a constant factor only, down to the rounding level of the type
+    ("f32", 900, 80, lambda i, l: np.where(i < l // 2, 1.0, 1e-3), 12),
+    ("f64", 1100, 200, lambda i, l: np.where(i < l // 2, 1.0, 1e-3), 20),
+    ("f64", 700, 120, lambda i, l: np.where(i < l // 4, 10.0 ** (-i / 5.0), 1e-6), 20),   # a steep head above a flat tail
+]
+
+
+@pytest.mark.parametrize("dt,n,l,spec,max_sweeps", HARD_FACTORS,
+                         ids=[f"{c[0]}-{c[1]}x{c[2]}-{j}" for j, c in enumerate(HARD_FACTORS)])
+def test_small_svd_of_steep_and_clustered_factors(dt, n, l, spec, max_sweeps):
+    """B with a steep spectrum or with clusters of equal singular values, in general position (no power iteration
+    has lined its rows up): the rotations act on the rows of the triangular factor of B^T, which are graded like
+    the singular values, and need about as many sweeps as on an easy factor (on its columns they needed 20 and
+    more, or ran into the sweep cap); inside a cluster the vectors come out orthogonal to the rounding level."""
+    say("small_svd hard", dt, n, l)
+    T = NPDT[dt]
+    i = np.arange(l, dtype=np.float64)
+    s = np.asarray(spec(i, l), dtype=np.float64) * np.ones(l)
+    B = (workloads.orthonormal_factor(l, l, 70) * s) @ workloads.orthonormal_factor(n, l, 71).T
+    Bt = np.ascontiguousarray(B.T.astype(T))
+    sig, Ub, V, info = ctx().rsvd_stage_small_svd(to_dev(Bt))
+    sig, Ub, V = (to_np(t).astype(np.float64) for t in (sig, Ub, V))
+    B = Bt.astype(np.float64).T
+    so = np.linalg.svd(B, compute_uv=False)
+    tol = parity.jacobi_tol(l, dt)
+    say("  sweeps", info.jacobi_sweeps)
+    assert info.status == 0 and info.jacobi_sweeps <= max_sweeps, info.jacobi_sweeps
+    assert np.abs(sig - so).max() <= tol * so[0]
+    big = so > so[0] * (1e-5 if dt == "f32" else 1e-10)
+    assert (np.abs(sig - so)[big] / so[big]).max() <= (1e-3 if dt == "f32" else 1e-5)
+    assert np.linalg.norm(Ub * sig @ V.T - B) <= tol * so[0]
+    # singular values at the rounding level of the whole factor count as zero: their columns of Ub are zero
+    live = so > 4 * np.finfo(T).eps * np.linalg.norm(so)
+    assert parity.orthonormality(V) <= tol and parity.orthonormality(Ub[:, live]) <= tol
+    assert all(np.abs(np.linalg.norm(Ub[:, j]) - 1) <= tol or not Ub[:, j].any() for j in np.where(~live)[0])
+
+
 def test_small_svd_rank_deficient_factor():
     say("small_svd rank deficient")
     n, l, r = 256, 20, 10
