@@ -180,6 +180,18 @@ hipError_t zero_ints_launch(hipStream_t s, int *p, int n, int batch = 1, int64_t
 // Largest order the single-workgroup LDS-resident Jacobi kernel handles.
 int jacobi_max_lds_order(const rsvd_ctx *ctx, rsvd_dtype dtype);
 size_t jacobi_scratch_bytes(const rsvd_ctx *ctx, rsvd_dtype dtype, int64_t l);
+// Q = Y R^-1 for panels of at most apply_tri_max_order(dtype) columns (Y rows x l, ld ldy; R^-1 l x l upper
+// triangular, ld l; Q may be Y): R^-1 resident in LDS, workgroups walking over 64-row tiles.  Columns flagged in
+// `dead` are replaced by Gaussian directions (element (row, col) from counter row * refill_ld + col of Philox stream
+// refill_stream, times refill_scale).  batch problems `stride` bytes apart (every pointer and the flag);
+// *skip_flag != 0: nothing is done.
+int apply_tri_max_order(rsvd_dtype dtype);
+hipError_t apply_init_device(rsvd_ctx *ctx);
+hipError_t apply_tri_launch(rsvd_ctx *ctx, hipStream_t s, rsvd_dtype dtype, int64_t rows, int64_t l, const void *Y,
+                            int64_t ldy, const void *Rinv, void *Q, int64_t ldq, const int *dead, uint64_t seed,
+                            uint32_t refill_stream, double refill_scale, int64_t refill_ld, int batch, int64_t stride,
+                            const int *skip_flag);
+
 // One-sided Jacobi SVD  M = X diag(sigma) W^T  of the l x l row-major matrix M
 // (ld l; fp64 when m_is_f64 else `dtype`).  Outputs in `dtype`, sigma descending.
 // batch > 1 (LDS-resident orders only): problem b = blockIdx.x adds b * stride bytes to M, sigma, X, W.

@@ -307,6 +307,13 @@ static int orthonormalize(rsvd_ctx *ctx, hipStream_t s, rsvd_dtype dtype, const 
                                  parts ? splits : 1, l * l, tau, w.at<void>(L.Rinv), R, w.at<int>(L.dead),
                                  w.at<DevInfo>(L.info), w.at<double>(L.chol_scratch), w.batch, w.stride, gate, pv),
              "cholesky");
+    if (l <= apply_tri_max_order(dtype)) {
+      RSVD_TRY(apply_tri_launch(ctx, s, dtype, rows, l, from, ld_from, w.at<void>(L.Rinv), to, ld_to, w.at<int>(L.dead),
+                                seed, refill_stream + (uint32_t)round, 1.0 / sqrt((double)rows), l, w.batch, w.stride,
+                                gate),
+               "apply R^-1");
+      return 0;
+    }
     GemmDesc a;
     a.M = rows; a.N = l; a.K = l;
     a.A = from; a.lda = ld_from; a.B = w.at<void>(L.Rinv); a.ldb = l;
@@ -485,6 +492,7 @@ int rsvd_create(rsvd_ctx **out, int device) {
       // per-kernel launch limits (dynamic LDS) of the single-workgroup kernels, for this device
       hipError_t e2 = chol_init_device(c);
       if (e2 == hipSuccess) e2 = jacobi_init_device(c);
+      if (e2 == hipSuccess) e2 = apply_init_device(c);
       if (cur >= 0 && cur != device) (void)hipSetDevice(cur);
       if (e2 != hipSuccess) {
         (void)hipGetLastError();
