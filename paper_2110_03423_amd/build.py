@@ -14,7 +14,7 @@ CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "librsvd_gfx950.so")
 OBJ_DIR = os.path.join(HERE, "_build")
 
-SOURCES = ["sketch.hip", "gemm_f32.hip", "gemm_f64.hip", "gemm_f32acc64.hip", "chol.hip", "jacobi.hip", "apply.hip",
+SOURCES = ["sketch.hip", "gemm_f32.hip", "gemm_f64.hip", "gemm_f32acc64.hip", "chol.hip", "jacobi.hip", "apply.hip", "gram.hip",
            "rsvd_api.hip"]
 
 # Packed fp32 instructions are switched off for device code on purpose.

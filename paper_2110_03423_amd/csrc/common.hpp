@@ -180,6 +180,17 @@ hipError_t zero_ints_launch(hipStream_t s, int *p, int n, int batch = 1, int64_t
 // Largest order the single-workgroup LDS-resident Jacobi kernel handles.
 int jacobi_max_lds_order(const rsvd_ctx *ctx, rsvd_dtype dtype);
 size_t jacobi_scratch_bytes(const rsvd_ctx *ctx, rsvd_dtype dtype, int64_t l);
+// G = Y^T Y in fp64 for panels of at most gram_syrk_max_order() columns (Y rows x l, ld ldy, of type dtype; G l x l,
+// ld l): the 16 x 16 blocks on or above the diagonal only.  The row ranges of the workgroups leave partial matrices
+// ([parts][l][l] in `partial`); up to max_parts of them are left for the consumer to add (*parts_out tells how
+// many; 1 = Gout holds the sum), more are added here.
+int gram_syrk_max_order();
+size_t gram_syrk_partial_bytes(const rsvd_ctx *ctx, int64_t rows, int64_t l);
+hipError_t gram_init_device(rsvd_ctx *ctx);
+hipError_t gram_syrk_launch(rsvd_ctx *ctx, hipStream_t s, rsvd_dtype dtype, int64_t rows, int64_t l, const void *Y,
+                            int64_t ldy, double *Gout, void *partial, size_t partial_bytes, int max_parts,
+                            int *parts_out, int batch, int64_t stride, const int *skip_flag);
+
 // Q = Y R^-1 for panels of at most apply_tri_max_order(dtype) columns (Y rows x l, ld ldy; R^-1 l x l upper
 // triangular, ld l; Q may be Y): R^-1 resident in LDS, workgroups walking over 64-row tiles.  Columns flagged in
 // `dead` are replaced by Gaussian directions (element (row, col) from counter row * refill_ld + col of Philox stream

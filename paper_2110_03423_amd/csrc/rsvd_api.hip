@@ -198,6 +198,8 @@ static Layout make_layout(const rsvd_ctx *ctx, rsvd_dtype dtype, int64_t m, int6
   if ((t = gemm_partial_bytes(ctx, kind, 1, n, l, m)) > pb) pb = t;
   if ((t = gemm_partial_bytes(ctx, gram, 1, l, l, m)) > pb) pb = t;
   if ((t = gemm_partial_bytes(ctx, gram, 1, l, l, n)) > pb) pb = t;
+  if ((t = gram_syrk_partial_bytes(ctx, m, l)) > pb) pb = t;
+  if ((t = gram_syrk_partial_bytes(ctx, n, l)) > pb) pb = t;
   if ((t = colsum_partial_bytes(m, n)) > pb) pb = t;      // column means of the centred variant
   L.partial_bytes = pb;
   L.partial = take(pb);
@@ -287,25 +289,28 @@ static int orthonormalize(rsvd_ctx *ctx, hipStream_t s, rsvd_dtype dtype, const 
   // product kernel spans all l columns: a workgroup has then read its rows completely before it writes them).
   auto one_round = [&](int round, const void *from, int64_t ld_from, void *to, int64_t ld_to, const int *gate,
                        const CholPivoting &pv, double *R) -> int {
-    GemmDesc g;
-    g.trans_a = 1; g.M = l; g.N = l; g.K = rows;
-    g.A = from; g.lda = ld_from; g.B = from; g.ldb = ld_from;
-    g.C = w.at<double>(L.G); g.ldc = l;
-    g.partial = w.at<void>(L.partial); g.partial_bytes = L.partial_bytes;
-    g.prof_kind = PK_GRAM;
-    g.batch = w.batch; g.stride_a = g.stride_b = g.stride_c = g.stride_partial = w.stride;
-    g.skip_flag = gate; g.stride_flag = w.stride;
-    g.upper_only = (l > 96) ? 1 : 0;   // both factorisations read the upper block triangle only; below that one tile covers G
-    // small orders: the Cholesky kernel adds the split-K partials itself
-    int splits = 1;
-    g.skip_reduce = (l <= chol_max_block(ctx)) ? 1 : 0;
-    g.skip_reduce_max = 4;          // more partials than this are cheaper to add in their own kernel
-    g.splits_out = &splits;
-    RSVD_TRY(gemm_launch(ctx, s, gram, g), "gram");
-    const bool parts = g.skip_reduce && splits > 1 && splits <= g.skip_reduce_max;
-    RSVD_TRY(chol_inverse_launch(ctx, s, dtype, l, parts ? w.at<double>(L.partial) : w.at<double>(L.G), l,
-                                 parts ? splits : 1, l * l, tau, w.at<void>(L.Rinv), R, w.at<int>(L.dead),
-                                 w.at<DevInfo>(L.info), w.at<double>(L.chol_scratch), w.batch, w.stride, gate, pv),
+    // Gram matrix: up to 128 columns the kernel that reads the panel once; beyond, the general product on the
+    // upper tiles.  Up to four partial sums are left for the Cholesky kernel to add.
+    int parts = 1;
+    if (l <= gram_syrk_max_order()) {
+      RSVD_TRY(gram_syrk_launch(ctx, s, dtype, rows, l, from, ld_from, w.at<double>(L.G), w.at<void>(L.partial),
+                                L.partial_bytes, 4, &parts, w.batch, w.stride, gate),
+               "gram");
+    } else {
+      GemmDesc g;
+      g.trans_a = 1; g.M = l; g.N = l; g.K = rows;
+      g.A = from; g.lda = ld_from; g.B = from; g.ldb = ld_from;
+      g.C = w.at<double>(L.G); g.ldc = l;
+      g.partial = w.at<void>(L.partial); g.partial_bytes = L.partial_bytes;
+      g.prof_kind = PK_GRAM;
+      g.batch = w.batch; g.stride_a = g.stride_b = g.stride_c = g.stride_partial = w.stride;
+      g.skip_flag = gate; g.stride_flag = w.stride;
+      g.upper_only = 1;              // the blocked factorisation reads the upper block triangle only
+      RSVD_TRY(gemm_launch(ctx, s, gram, g), "gram");
+    }
+    RSVD_TRY(chol_inverse_launch(ctx, s, dtype, l, parts > 1 ? w.at<double>(L.partial) : w.at<double>(L.G), l, parts,
+                                 l * l, tau, w.at<void>(L.Rinv), R, w.at<int>(L.dead), w.at<DevInfo>(L.info),
+                                 w.at<double>(L.chol_scratch), w.batch, w.stride, gate, pv),
              "cholesky");
     if (l <= apply_tri_max_order(dtype)) {
       RSVD_TRY(apply_tri_launch(ctx, s, dtype, rows, l, from, ld_from, w.at<void>(L.Rinv), to, ld_to, w.at<int>(L.dead),
@@ -493,6 +498,7 @@ int rsvd_create(rsvd_ctx **out, int device) {
       hipError_t e2 = chol_init_device(c);
       if (e2 == hipSuccess) e2 = jacobi_init_device(c);
       if (e2 == hipSuccess) e2 = apply_init_device(c);
+      if (e2 == hipSuccess) e2 = gram_init_device(c);
       if (cur >= 0 && cur != device) (void)hipSetDevice(cur);
       if (e2 != hipSuccess) {
         (void)hipGetLastError();
