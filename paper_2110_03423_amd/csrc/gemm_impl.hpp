@@ -450,6 +450,10 @@ inline TileChoice choose_tile(int64_t M, int64_t N, int64_t K, size_t acc_size, 
     if (pad96 <= pad64) t.bn = 96;
     if (pad128 < pad64 && pad128 < pad96) t.bn = 128;
     if (trans_a && t.bn == 96) t.bm = 128;      // measured: 128 x 96 is faster for A^T X, 64 x 96 for A X
+    // a short product with a handful of tiles (the panel and trailing updates of the blocked Cholesky factorisation:
+    // K = 96, 5 to 20 tiles for 256 CUs) is bound by the matrix instructions of one workgroup: smaller tiles, more
+    // workgroups side by side
+    if (K <= 256 && ceil_div(M, t.bm) * ceil_div(N, t.bn) <= 32) { t.bm = 64; t.bn = 64; }
   } else {
     // wide outputs: 128-row tiles, column tile with the least padding.  For op(A) = A and
     // enough tiles to fill the chip twice the 192-wide tile wins on a tie (fewer LDS fragment
