@@ -94,6 +94,28 @@ def test_steep_spectra_in_fp64(cfg, q):
         assert info.refilled_columns == 0                  # a full-rank sketch loses no column
 
 
+GENERAL_POSITION = [  # no power iteration and a steep spectrum: the factor of step 5 is nowhere near diagonal
+    (dataclasses.replace(scaled(CONFIGS[2], 1500, 1200, k=200, p=61), spectrum=lambda i: 10.0 ** (-i / 40.0),
+                         name="f32-steep-l261"), 12),
+    (dataclasses.replace(scaled(CONFIGS[2], 1800, 900, k=160, p=40), dtype="f64", spectrum=lambda i: 10.0 ** (-i / 20.0),
+                         name="f64-steep-l200"), 14),
+    (dataclasses.replace(scaled(CONFIGS[2], 900, 700, k=70, p=26), spectrum=lambda i: 10.0 ** (-i / 16.0),
+                         name="f32-steep-l96"), 10),
+]
+
+
+@pytest.mark.parametrize("cfg,max_sweeps", GENERAL_POSITION, ids=lambda v: v.name if hasattr(v, "name") else f"s{v}")
+def test_no_power_iteration_on_steep_spectra(cfg, max_sweeps):
+    """q = 0 on spectra that fall by six to ten decades inside the sketch: the small SVD gets a triangular factor in
+    general position.  Rotating its columns took 20 and more sweeps or ended in RSVD_ERR_NO_CONVERGENCE; its rows,
+    graded like the singular values, converge in about as many sweeps as an easy factor."""
+    A = workloads.build(cfg)
+    run_and_compare(cfg, to_dev(A), A, q=0)
+    _, _, _, info = ctx().rsvd_run(to_dev(A), cfg.k, cfg.p, 0, seed=cfg.seed)
+    say(f"  sweeps={info.jacobi_sweeps}")
+    assert info.status == 0 and info.jacobi_sweeps <= max_sweeps
+
+
 @pytest.mark.parametrize("q", [0, 1, 3])
 def test_power_iteration_counts(q):
     cfg = scaled(CONFIGS[2], 900, 300, k=12, p=12)
