@@ -272,7 +272,7 @@ int rsvd_stage_small_svd(rsvd_ctx *ctx, void *stream, rsvd_dtype dtype,
  * singular value is zero).  They converge in the fewest sweeps when the columns
  * are graded in length, as the rows of a triangular factor are: for such an M
  * pass its transpose and swap X and W (rsvd_run and rsvd_stage_small_svd do
- * that with the factor of B^T).  RSVD_ERR_NO_CONVERGENCE after 30 sweeps
+ * that with the factor of B^T).  RSVD_ERR_NO_CONVERGENCE after 60 sweeps
  * (24 above the single-workgroup orders). */
 int rsvd_stage_jacobi(rsvd_ctx *ctx, void *stream, rsvd_dtype dtype, int64_t l,
                       void *M, void *sigma, void *X, void *W,

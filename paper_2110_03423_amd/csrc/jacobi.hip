@@ -9,7 +9,8 @@
 // convergence  M J = X diag(sigma)  and  M = X diag(sigma) J^T.
 //
 // Stopping rule (the paper gives none): a sweep in which every pair satisfies
-// |a_p . a_q| <= tol * ||a_p|| * ||a_q||, tol = eps * sqrt(l); at most 30 sweeps.
+// |a_p . a_q| <= tol * ||a_p|| * ||a_q||, tol = eps * sqrt(l); at most 60 sweeps (24 in the block path, whose
+// launches are all issued in advance).
 // The sweep that would only confirm this is saved when the rate of the last two sweeps says what it would find
 // (jacobi_done below): with rho the largest relative inner product a sweep rotated away, the next sweep meets about
 // rho^2 where the method converges quadratically (the paper: "3-4 iterations ... converges quadratically"; taken for
@@ -28,7 +29,7 @@
 
 namespace rsvd {
 
-constexpr int kJacobiMaxSweeps = 30;
+constexpr int kJacobiMaxSweeps = 60;      // (a loop inside the kernel: sweeps that are not needed cost nothing)
 
 template <typename T> struct Eps;
 template <> struct Eps<float>  { static constexpr float  value = 1.1920929e-07f; };
