@@ -90,6 +90,10 @@ struct GemmDesc {
   // are computed; what lies in the tiles strictly below (and their split-K partials) is undefined.
   // Every 16 x 16 block on the diagonal is complete.
   int upper_only = 0;
+  // b_upper != 0: B (K x N, K == N) is upper triangular with exact zeros below its diagonal; the k range of a
+  // column tile stops where its columns of B do (the terms left out are zeros: the result is the same, bit for bit,
+  // for finite A).
+  int b_upper = 0;
   const int *dead = nullptr;
   uint64_t seed = 0; uint32_t refill_stream = 0; double refill_scale = 1.0; int64_t refill_ld = 0;
   void *partial = nullptr; size_t partial_bytes = 0;   // split-K scratch

@@ -32,6 +32,7 @@ struct GemmParams {
   int splits;
   int tiles_n, tiles_m;     // grid shape in tiles; the launch is one-dimensional
   int upper_bm, upper_bn;   // > 0: symmetric result, tiles (of this size) strictly below the diagonal are skipped
+  int b_upper;              // != 0: B is upper triangular (row k is zero before column k): a column tile ends its k range early
   int trans_c;
   double alpha, beta;
   const double *a_shift;    // non-NULL: op(A) is built from A[i][j] - a_shift[j] (one value per column of A)
@@ -202,7 +203,8 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmParams P0) {
   const int64_t n0 = (int64_t)tile_n * BN;
   if (P.upper_bm > 0 && n0 + BN <= m0) return;       // symmetric result: this tile mirrors one that is computed
   const int64_t k_begin = (int64_t)split * P.k_per_split;
-  const int64_t k_end = (k_begin + P.k_per_split < P.K) ? (k_begin + P.k_per_split) : P.K;
+  int64_t k_end = (k_begin + P.k_per_split < P.K) ? (k_begin + P.k_per_split) : P.K;
+  if (P.b_upper != 0 && n0 + BN < k_end) k_end = n0 + BN;      // rows of B from n0 + BN on are zero in these columns
 
   const TIn *A = (const TIn *)P.A;
   const TIn *B = (const TIn *)P.B;
@@ -596,6 +598,7 @@ struct GemmDispatch {
     P.partial = d.partial; P.k_per_split = c.k_per_split; P.splits = c.splits;
     P.trans_c = d.trans_c; P.alpha = d.alpha; P.beta = d.beta;
     P.upper_bm = d.upper_only ? t.bm : 0; P.upper_bn = d.upper_only ? t.bn : 0;
+    P.b_upper = d.b_upper;
     P.a_shift = d.a_shift;
     P.dead = d.dead; P.seed = d.seed; P.refill_stream = d.refill_stream;
     P.refill_scale = d.refill_scale; P.refill_ld = d.refill_ld;

@@ -225,7 +225,7 @@ hipError_t gram_syrk_launch(rsvd_ctx *ctx, hipStream_t s, rsvd_dtype dtype, int6
     R.M = l; R.N = l; R.K = rows;
     R.A = nullptr; R.lda = 0; R.B = nullptr; R.ldb = 0; R.C = Gout; R.ldc = l;
     R.partial = partial; R.k_per_split = 0; R.splits = wgs;
-    R.tiles_n = R.tiles_m = 0; R.upper_bm = 16; R.upper_bn = 16;
+    R.tiles_n = R.tiles_m = 0; R.upper_bm = 16; R.upper_bn = 16; R.b_upper = 0;
     R.trans_c = 0; R.alpha = 1.0; R.beta = 0.0; R.a_shift = nullptr; R.dead = nullptr;
     R.seed = 0; R.refill_stream = 0; R.refill_scale = 1.0; R.refill_ld = 0;
     R.stride_a = R.stride_b = 0; R.stride_c = stride; R.stride_partial = stride; R.stride_dead = 0; R.seed_step = 0;

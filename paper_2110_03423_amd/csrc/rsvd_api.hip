@@ -322,6 +322,7 @@ static int orthonormalize(rsvd_ctx *ctx, hipStream_t s, rsvd_dtype dtype, const 
     GemmDesc a;
     a.M = rows; a.N = l; a.K = l;
     a.A = from; a.lda = ld_from; a.B = w.at<void>(L.Rinv); a.ldb = l;
+    a.b_upper = 1;
     a.C = to; a.ldc = ld_to;
     a.dead = w.at<int>(L.dead); a.seed = seed; a.refill_stream = refill_stream + (uint32_t)round;
     a.refill_scale = 1.0 / sqrt((double)rows); a.refill_ld = l;
