@@ -38,21 +38,28 @@ __device__ __forceinline__ double readlane_f64(double v, int lane) {
 // Elimination on [S | I] by 16 x 16 blocks.  Wavefront r owns block row r for the whole
 // run and keeps it in registers in the accumulator layout of the fp64 matrix-core
 // instruction: slot J >= r is the S block (r, J), slot J < r the block (r, J) of
-// Z = R^-T.  Step kb:
-//   * wavefront kb factors its diagonal block (see diag_factor), multiplies the rest of
-//     its row by T^T, T = R_kk^-1, on the matrix cores (the accumulator layout is also
-//     the B-operand layout, so the row never leaves the registers) and publishes the
-//     finished row (R to the right of the diagonal, Z to the left) and T in LDS;
-//   * one barrier;
-//   * every wavefront r > kb takes  block(r, J) -= R[kb][r]^T block(kb, J)  for its slots.
-// The rows collected in LDS are written out at the end (R^-1 as the transpose of Z).
+// Z = R^-T.  Wavefront 0, whose own row is complete after the first step, factors all the
+// diagonal blocks (diag_factor).  The chain that every
+// step has to wait for is: row kb complete -> update of the next diagonal block -> its
+// factorisation -> scaling of row kb + 1 by T^T, T = R_kk^-1; everything else is moved off it.
+// Step kb, two barriers:
+//   * row kb lies in LDS unscaled, T and R_kk are there: every other wavefront multiplies one
+//     column block of the row by T^T on the matrix cores, in place (one block each instead of the
+//     whole row in one wavefront); wavefront kb + 1, which has just scaled the block above its own
+//     diagonal block, updates that block with it and hands it over through LDS;        -- barrier
+//   * wavefront 0 factors block kb + 1 and publishes R, T and the flags, while the
+//     wavefronts r > kb take  block(r, J) -= R[kb][r]^T block(kb, J)  for their (other) slots,
+//     wavefront kb + 1 then leaves its row in LDS; behind that every wavefront but the factoring
+//     one writes its share of block row kb of R and block column kb of R^-1 (the transpose
+//     of Z).                                                                           -- barrier
 //   g0    : original squared column norms for the pivot test, or NULL to use the diagonal
 //   Rinv  : nb x nb block of R^-1 (ld ldri, type TOut, zeros below the diagonal)
 //   R     : same for R in fp64 (ld ldr), or NULL
 //   dead  : nb flags (1 = pivot <= tau * original squared norm)
 template <int NB> struct CholLds {
   static constexpr int LP = 16 * NB, LD = LP + 1, TLD = 17;
-  static constexpr size_t bytes = ((size_t)LP * LD + (size_t)NB * 16 * TLD + LP) * sizeof(double);
+  // rows of [R | Z], the inverses of the diagonal blocks, the reference norms, the diagonal block in hand
+  static constexpr size_t bytes = ((size_t)LP * LD + (size_t)NB * 16 * TLD + LP + 256) * sizeof(double);
 };
 
 // Factor and invert one 16 x 16 symmetric block held in the accumulator layout
@@ -135,14 +142,15 @@ __device__ __forceinline__ unsigned diag_factor(f64x4 &dblk, f64x4 &z, double th
 
 template <typename TOut, int NB>
 __global__ __launch_bounds__(NB * 64) void chol_mfma_kernel(const double *__restrict__ G, int64_t ldg,
-                                                            int n_parts, int64_t part_stride, int nb,
-                                                            const double *__restrict__ g0, double tau,
-                                                            TOut *__restrict__ Rinv, int64_t ldri,
-                                                            double *__restrict__ R, int64_t ldr,
-                                                            int *__restrict__ dead, DevInfo *info, int64_t stride,
-                                                            const int *skip_flag, int raise, double floor_abs,
-                                                            double abs_thr, int *redo_skip, int redo_mode,
-                                                            double *__restrict__ Rinv_elim, int64_t ldre) {
+                                                                  int n_parts, int64_t part_stride, int nb,
+                                                                  const double *__restrict__ g0, double tau,
+                                                                  TOut *__restrict__ Rinv, int64_t ldri,
+                                                                  double *__restrict__ R, int64_t ldr,
+                                                                  int *__restrict__ dead, DevInfo *info,
+                                                                  int64_t stride, const int *skip_flag, int raise,
+                                                                  double floor_abs, double abs_thr, int *redo_skip,
+                                                                  int redo_mode, double *__restrict__ Rinv_elim,
+                                                                  int64_t ldre) {
   typedef CholLds<NB> L;
   // redo_skip (device int, strided like the rest in a batch; may be NULL): the switch of the additional
   // CholeskyQR round that follows a factorisation with raised pivots; non-zero = that round is skipped.
@@ -165,21 +173,28 @@ __global__ __launch_bounds__(NB * 64) void chol_mfma_kernel(const double *__rest
     if (R != nullptr) R = reinterpret_cast<double *>(reinterpret_cast<char *>(R) + off);
     dead = reinterpret_cast<int *>(reinterpret_cast<char *>(dead) + off);
   }
-  constexpr int LP = L::LP, LD = L::LD, TLD = L::TLD, NT = NB * 64;
+  constexpr int LP = L::LP, LD = L::LD, TLD = L::TLD;
   extern __shared__ double smem[];
-  double *Sm = smem;                       // LP x LD: finished rows of [R | Z]
+  double *Sm = smem;                       // LP x LD: rows of [R | Z]
   double *Td = Sm + LP * LD;               // NB x 16 x TLD: R_kk^-1
   double *d0 = Td + NB * 16 * TLD;         // LP: reference squared norms for the pivot test
+  double *Dg = d0 + LP;                    // 4 x 64: the diagonal block in hand, accumulator layout
   __shared__ double piv[16];
   __shared__ int n_dead, n_weak, bad;
+  __shared__ unsigned wmask_sh;            // rows of the current pivot block that were set aside
   __shared__ unsigned char aside[16 * NB];
-  const int tid = threadIdx.x, lane = tid & 63, wr = tid >> 6;      // wr: block row of this wavefront
+  const int tid = threadIdx.x, lane = tid & 63;
+  // Block row of this wavefront; the wavefront of row 0 also factors the diagonal blocks.  Wavefronts w and w + 4
+  // share a SIMD unit and its matrix pipe: the one next to the factoring wavefront takes row 1, which is complete
+  // after the first step, so that the factorisations that follow have the pipe to themselves.
+  const int wv = tid >> 6;
+  const int wr = NB > 4 ? (wv == 4 ? 1 : (wv == 1 ? 4 : wv)) : wv;
   const int lr = lane >> 4, lc = lane & 15;
   // register slot t of wavefront wr holds column block (wr + t) mod NB: slot 0 is the
   // diagonal block, slots 1 .. NB-1-wr the S blocks to its right, the rest the Z blocks
   auto col_block = [&](int t) { const int J = wr + t; return J >= NB ? J - NB : J; };
 
-  if (tid == 0) { n_dead = 0; n_weak = 0; bad = 0; }
+  if (tid == 0) { n_dead = 0; n_weak = 0; bad = 0; wmask_sh = 0u; }
   __syncthreads();
   // ---- load block row wr: sum of the parts for the S slots, zero for the Z slots, identity padding
   f64x4 acc[NB];
@@ -211,67 +226,89 @@ __global__ __launch_bounds__(NB * 64) void chol_mfma_kernel(const double *__rest
       if (!(fabs(dv) <= 1.79e308)) bad = 1;      // NaN or Inf
     }
   }
+
+  // Wavefront 0: factor the block in Dg as diagonal block kb, publish R_kk, T = R_kk^-1 and the flags.
+  auto factor_block = [&](int kb) {
+    const int k0 = kb * 16;
+    f64x4 dblk, z;
+#pragma unroll
+    for (int v = 0; v < 4; ++v) dblk[v] = Dg[v * 64 + lane];
+    const double d0c = d0[k0 + lc];
+    const unsigned pos = (unsigned)__ballot(d0c > 0.0 && d0c >= floor_abs) & 0xffffu;
+    // pivot threshold: tau times the column's reference norm, or the same for every column (abs_thr > 0:
+    // rounds that work on a panel whose resolved columns have unit length)
+    const unsigned masks = diag_factor(dblk, z, abs_thr > 0.0 ? abs_thr : tau * d0c, pos, lane, piv, raise != 0);
+    const unsigned dmask = masks & 0xffffu, wmask = masks >> 16;
+#pragma unroll
+    for (int v = 0; v < 4; ++v) {
+      const int row = 4 * v + lr;
+      Sm[(k0 + row) * LD + k0 + lc] = (lc >= row) ? dblk[v] : 0.0;          // R_kk
+      Td[(k0 + lc) * TLD + row] = z[v];                                      // T[c][row] = Z[row][c]
+    }
+    if (lane < 16 && k0 + lane < nb) dead[k0 + lane] = (int)((dmask >> lane) & 1u);
+    if (lane < 16) aside[k0 + lane] = (unsigned char)((wmask >> lane) & 1u);
+    if (lane == 0) {
+      const int valid = min(16, nb - k0);
+      n_dead += __popc(dmask & ((1u << valid) - 1u));     // wavefront 0 is the only writer
+      n_weak += __popc(wmask & ((1u << valid) - 1u));
+      wmask_sh = wmask;
+    }
+  };
+  // Row wavefront wr leaves its diagonal block in Dg and the rest of its row, unscaled, in LDS.
+  auto put_diag = [&]() {
+#pragma unroll
+    for (int v = 0; v < 4; ++v) Dg[v * 64 + lane] = acc[0][v];
+  };
+  auto put_row = [&]() {
+#pragma unroll
+    for (int t = 1; t < NB; ++t) {
+      double *dst = Sm + (16 * wr + lr) * LD + 16 * col_block(t) + lc;
+#pragma unroll
+      for (int v = 0; v < 4; ++v) dst[4 * v * LD] = acc[t][v];
+    }
+  };
+
+  if (wr == 0) { put_diag(); put_row(); }
+  __syncthreads();
+  if (wr == 0) factor_block(0);
   __syncthreads();
 
 #pragma unroll 1
   for (int kb = 0; kb < NB; ++kb) {
     const int k0 = kb * 16;
-    if (wr == kb) {
-      // ---- pivot row: factor the diagonal block, scale the row, publish it
-      const double d0c = d0[k0 + lc];
-      const unsigned pos = (unsigned)__ballot(d0c > 0.0 && d0c >= floor_abs) & 0xffffu;
-      f64x4 z;
-      // pivot threshold: tau times the column's reference norm, or the same for every column (abs_thr > 0:
-      // rounds that work on a panel whose resolved columns have unit length)
-      const unsigned masks = diag_factor(acc[0], z, abs_thr > 0.0 ? abs_thr : tau * d0c, pos, lane, piv, raise != 0);
-      const unsigned dmask = masks & 0xffffu, wmask = masks >> 16;
+    // ---- row kb times T^T, in place: wavefront J takes column block J (R to the right of the diagonal, Z to the left)
+    if (wr != kb) {
+      double ta[4], bo[4];
+      double *blk = Sm + (k0 + lr) * LD + 16 * wr + lc;
 #pragma unroll
-      for (int v = 0; v < 4; ++v) {
-        const int row = 4 * v + lr;
-        Sm[(k0 + row) * LD + k0 + lc] = (lc >= row) ? acc[0][v] : 0.0;        // R_kk
-        Td[(k0 + lc) * TLD + row] = z[v];                                      // T[c][row] = Z[row][c]
-      }
-      if (lane < 16 && k0 + lane < nb) dead[k0 + lane] = (int)((dmask >> lane) & 1u);
-      if (lane < 16) aside[k0 + lane] = (unsigned char)((wmask >> lane) & 1u);
-      if (lane == 0) {
-        const int valid = min(16, nb - k0);
-        n_dead += __popc(dmask & ((1u << valid) - 1u));     // one writer at a time (steps are separated by barriers)
-        n_weak += __popc(wmask & ((1u << valid) - 1u));
-      }
-      __builtin_amdgcn_wave_barrier();
-      double ta[4];
+      for (int s = 0; s < 4; ++s) { ta[s] = Td[(k0 + 4 * s + lr) * TLD + lc]; bo[s] = blk[4 * s * LD]; }
+      f64x4 o = {0.0, 0.0, 0.0, 0.0};
 #pragma unroll
-      for (int s = 0; s < 4; ++s) ta[s] = Td[(k0 + 4 * s + lr) * TLD + lc];
-      // (slot loop innermost: consecutive matrix-core instructions are independent)
-      f64x4 o[NB];
+      for (int s = 0; s < 4; ++s) o = Mfma<double>::run(ta[s], bo[s], o);
+      const unsigned wmask = wmask_sh;
+      if (wr > kb && wmask != 0u) {
+        // rows set aside keep nothing of R to the right of the diagonal (their part of R^-1, the Z blocks, stays)
 #pragma unroll
-      for (int t = 1; t < NB; ++t) o[t] = f64x4{0.0, 0.0, 0.0, 0.0};
-#pragma unroll
-      for (int s = 0; s < 4; ++s)
-#pragma unroll
-        for (int t = 1; t < NB; ++t) o[t] = Mfma<double>::run(ta[s], acc[t][s], o[t]);
-      if (wmask != 0u) {
-        // rows set aside keep nothing of R to the right of the diagonal (their part of R^-1, the Z slots, stays)
-#pragma unroll
-        for (int t = 1; t < NB; ++t)
-#pragma unroll
-          for (int v = 0; v < 4; ++v)
-            if (wr + t < NB && ((wmask >> (4 * v + lr)) & 1u)) o[t][v] = 0.0;
+        for (int v = 0; v < 4; ++v)
+          if ((wmask >> (4 * v + lr)) & 1u) o[v] = 0.0;
       }
 #pragma unroll
-      for (int t = 1; t < NB; ++t) {
-        double *dst = Sm + (k0 + lr) * LD + 16 * col_block(t) + lc;
+      for (int v = 0; v < 4; ++v) blk[4 * v * LD] = o[v];
+      if (wr == kb + 1) {
+        // the next pivot row brings its diagonal block up to date with the block it has just scaled (the
+        // accumulator layout is the layout of both operands:  block(wr, wr) -= R[kb][wr]^T R[kb][wr])
+        // and hands it over
 #pragma unroll
-        for (int v = 0; v < 4; ++v) dst[4 * v * LD] = o[t][v];
+        for (int s = 0; s < 4; ++s) acc[0] = Mfma<double>::run(-o[s], o[s], acc[0]);
+        put_diag();
       }
     }
     __syncthreads();
     if (wr > kb) {
       // ---- trailing rows: block(wr, J) -= R[kb][wr]^T block(kb, J)
-      double na[4];
+      double na[4], b[NB][4];
 #pragma unroll
       for (int s = 0; s < 4; ++s) na[s] = -Sm[(k0 + 4 * s + lr) * LD + 16 * wr + lc];
-      double b[NB][4];
 #pragma unroll
       for (int t = 0; t < NB; ++t) {
         const int J = col_block(t);
@@ -283,20 +320,32 @@ __global__ __launch_bounds__(NB * 64) void chol_mfma_kernel(const double *__rest
         for (int s = 0; s < 4; ++s) b[t][s] = on ? src[s * step] : 0.0;      // untouched slots take a zero update
       }
       // (slot loop innermost: consecutive matrix-core instructions are independent)
+      if (wr == kb + 1) {
 #pragma unroll
-      for (int s = 0; s < 4; ++s)
+        for (int s = 0; s < 4; ++s)
 #pragma unroll
-        for (int t = 0; t < NB; ++t) acc[t] = Mfma<double>::run(na[s], b[t][s], acc[t]);
-    } else {
-      // ---- the wavefronts that are done write out block row kb of R and block column kb of R^-1
-      // (R^-1 = Z^T: column k0 + c of R^-1 is row k0 + c of Z), off the critical path
-      const int parts = kb + 1;
+          for (int t = 1; t < NB; ++t) acc[t] = Mfma<double>::run(na[s], b[t][s], acc[t]);
+        put_row();
+      } else {
+#pragma unroll
+        for (int s = 0; s < 4; ++s)
+#pragma unroll
+          for (int t = 0; t < NB; ++t) acc[t] = Mfma<double>::run(na[s], b[t][s], acc[t]);
+      }
+    } else if (wr == 0 && kb + 1 < NB) {
+      factor_block(kb + 1);
+    }
+    // ---- block row kb of R and block column kb of R^-1 are written out (R^-1 = Z^T: column k0 + c of R^-1 is
+    // row k0 + c of Z) by every wavefront but the one that factors, each behind its update: off the critical path
+    const bool last = kb + 1 == NB;
+    if (wr != 0 || last) {
+      const int parts = NB - 1 + (last ? 1 : 0), me = wr == 0 ? NB - 1 : wr - 1;
       const int ldr_i = (int)ldr, ldri_i = (int)ldri;      // orders here are at most a few hundred
       if (R != nullptr) {
         const int rows = min(16, nb - k0);
         for (int c = lane; c < nb; c += 64) {
 #pragma unroll 4
-          for (int i = wr; i < rows; i += parts) {
+          for (int i = me; i < rows; i += parts) {
             const int r = k0 + i;
             R[r * ldr_i + c] = (c >= r) ? Sm[r * LD + c] : 0.0;
           }
@@ -305,7 +354,7 @@ __global__ __launch_bounds__(NB * 64) void chol_mfma_kernel(const double *__rest
       const int c = k0 + lc;
       if (c < nb) {
 #pragma unroll 4
-        for (int r = lr + 4 * wr; r < nb; r += 4 * parts) {
+        for (int r = lr + 4 * me; r < nb; r += 4 * parts) {
           double v = 0.0;
           if (r <= c) v = (r >= k0) ? Td[r * TLD + lc] : Sm[c * LD + r];
           Rinv[r * ldri_i + c] = (TOut)v;
@@ -313,6 +362,7 @@ __global__ __launch_bounds__(NB * 64) void chol_mfma_kernel(const double *__rest
         }
       }
     }
+    __syncthreads();
   }
   if (tid == 0) {
     if (info != nullptr) {
@@ -388,7 +438,7 @@ __global__ void zero_ints_kernel(int *p, int n, int64_t stride) {
 
 int chol_max_block(const rsvd_ctx *ctx) {
   (void)ctx;
-  return 128;      // 8 x 8 blocks of 16 x 16 in 147 KB of LDS
+  return 128;      // 8 x 8 blocks of 16 x 16 in 149 KB of LDS
 }
 
 size_t chol_scratch_elems(const rsvd_ctx *ctx, int64_t l) {
@@ -406,8 +456,8 @@ static hipError_t launch_block(hipStream_t s, const double *G, int64_t ldg, int 
                                int64_t ldre = 0) {
   // one workgroup, one wavefront per 16-row block
 #define RSVD_CHOL_CASE(NBV)                                                                                         \
-  hipLaunchKernelGGL((chol_mfma_kernel<TOut, NBV>), dim3(batch), dim3(NBV * 64), CholLds<NBV>::bytes, s, G, ldg,    \
-                     n_parts, part_stride, nb, g0, tau, Rinv, ldri, R, ldr, dead, info, stride, skip_flag,          \
+  hipLaunchKernelGGL((chol_mfma_kernel<TOut, NBV>), dim3(batch), dim3(NBV * 64), CholLds<NBV>::bytes, s, G,         \
+                     ldg, n_parts, part_stride, nb, g0, tau, Rinv, ldri, R, ldr, dead, info, stride, skip_flag,     \
                      pv.raise, pv.floor_abs, pv.abs_thr, pv.redo_skip, redo_mode, Rinv_elim, ldre)
   switch ((nb + 15) / 16) {
     case 1: RSVD_CHOL_CASE(1); break;
