@@ -193,8 +193,10 @@ int rsvd_run_centered(rsvd_ctx *ctx, void *stream, rsvd_dtype dtype, rsvd_job jo
  * different problems run side by side.  Problem b draws its sketch with
  * seed + b; its results equal those of rsvd_run on that matrix with that seed
  * up to the rounding of a different split of the long sums.
- *   requires k + p within the single-workgroup kernels (128 for fp32, 96 for
- *   fp64; RSVD_ERR_UNSUPPORTED otherwise), batch in 1 .. 65535, strides that
+ *   requires k + p <= 128, the reach of the single-workgroup kernels
+ *   (RSVD_ERR_UNSUPPORTED otherwise; fp64 problems beyond 96 accumulate the
+ *   rotations of step 5 in global memory and take about twice as long there),
+ *   batch in 1 .. 65535, strides that
  *   keep the problems apart, and a workspace of rsvd_workspace_bytes_batched().
  *   info (host, may be NULL) describes the whole batch: the worst status, the
  *   largest sweep count, the total of replaced columns.

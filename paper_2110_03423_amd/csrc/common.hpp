@@ -183,6 +183,8 @@ hipError_t zero_ints_launch(hipStream_t s, int *p, int n, int batch = 1, int64_t
 // ---------------------------------------------------------------- Jacobi
 // Largest order the single-workgroup LDS-resident Jacobi kernel handles.
 int jacobi_max_lds_order(const rsvd_ctx *ctx, rsvd_dtype dtype);
+// Largest order rsvd_run_batched takes (fp64: 128, with the rotations accumulated in global memory beyond 96).
+int jacobi_max_batched_order(const rsvd_ctx *ctx, rsvd_dtype dtype);
 size_t jacobi_scratch_bytes(const rsvd_ctx *ctx, rsvd_dtype dtype, int64_t l);
 // G = Y^T Y in fp64 for panels of at most gram_syrk_max_order() columns (Y rows x l, ld ldy, of type dtype; G l x l,
 // ld l): the 16 x 16 blocks on or above the diagonal only.  The row ranges of the workgroups leave partial matrices

@@ -222,10 +222,14 @@ __host__ __device__ inline int jacobi_ldm(int l, int G, int elem_size) {
   return jacobi_rows_padded(l, G, elem_size) + 2;
 }
 
-template <typename T, typename TIn, int RPL, int G>
+// JG: the columns of J (the accumulated rotations) live in global memory (Jglobal, l columns of ldm elements, one
+// such array per problem of a batch, `stride` bytes apart) instead of LDS, for orders whose two matrices do not fit
+// there together (fp64 beyond 96).  Its columns travel through the cache of the CU: a round takes longer, but
+// the problems of a batch still run side by side, one workgroup each.
+template <typename T, typename TIn, int RPL, int G, bool JG = false>
 __global__ __launch_bounds__(64 * G) void jacobi_lds_kernel(const TIn *__restrict__ M, int l, T *__restrict__ sigma,
                                                          T *__restrict__ X, T *__restrict__ W, DevInfo *info,
-                                                         int64_t stride, int rows) {
+                                                         int64_t stride, int rows, T *__restrict__ Jglobal) {
   extern __shared__ __attribute__((aligned(16))) double lds_raw[];
   if (blockIdx.x != 0) {              // batched launch: one problem per workgroup, `stride` bytes apart
     const int64_t off = (int64_t)blockIdx.x * stride;
@@ -233,11 +237,12 @@ __global__ __launch_bounds__(64 * G) void jacobi_lds_kernel(const TIn *__restric
     sigma = reinterpret_cast<T *>(reinterpret_cast<char *>(sigma) + off);
     X = reinterpret_cast<T *>(reinterpret_cast<char *>(X) + off);
     W = reinterpret_cast<T *>(reinterpret_cast<char *>(W) + off);
+    if (JG) Jglobal = reinterpret_cast<T *>(reinterpret_cast<char *>(Jglobal) + off);
   }
   const int ldm = jacobi_ldm(l, G, (int)sizeof(T));
   T *Mc = reinterpret_cast<T *>(lds_raw);
-  T *Jc = Mc + (size_t)l * ldm;
-  T *nrm = Jc + (size_t)l * ldm;
+  T *Jc = JG ? Jglobal : Mc + (size_t)l * ldm;
+  T *nrm = Mc + (size_t)(JG ? 1 : 2) * l * ldm;
   int *rnk = reinterpret_cast<int *>(nrm + l);
   __shared__ int rotations;
   __shared__ T wave_sum[16];
@@ -1190,6 +1195,15 @@ int jacobi_max_lds_order(const rsvd_ctx *ctx, rsvd_dtype dtype) {
   return l;      // 128 columns = 64 pairs x 16 lanes = the largest workgroup
 }
 
+// Largest order of a batched call: fp64 orders beyond the LDS-resident kernel keep J in global memory, up to the
+// largest workgroup (64 pairs x 16 lanes).
+int jacobi_max_batched_order(const rsvd_ctx *ctx, rsvd_dtype dtype) {
+  return dtype == RSVD_F64 ? 128 : jacobi_max_lds_order(ctx, dtype);
+}
+static size_t jacobi_jglobal_bytes(int64_t l) {
+  return (size_t)l * (size_t)jacobi_ldm((int)l, 16, 8) * 8;
+}
+
 // Units (8 bytes) per lane for order l: ceil(l / V / 32), rounded up to an instantiated value.
 static int jb_units_per_lane(rsvd_dtype dtype, int64_t l) {
   const int v = 8 / (int)dtype_size(dtype);
@@ -1294,7 +1308,16 @@ template <typename T, typename TIn, int RPL, int G>
 static hipError_t launch_lds(hipStream_t s, int nt, size_t lds, const void *M, int l, void *sigma, void *X, void *W,
                              DevInfo *info, int batch, int64_t stride, int rows) {
   hipLaunchKernelGGL((jacobi_lds_kernel<T, TIn, RPL, G>), dim3(batch), dim3(nt), lds, s, (const TIn *)M, l,
-                     (T *)sigma, (T *)X, (T *)W, info, stride, rows);
+                     (T *)sigma, (T *)X, (T *)W, info, stride, rows, (T *)nullptr);
+  return hipGetLastError();
+}
+// fp64 orders 97 .. 128: M in LDS, J in global memory
+template <int RPL>
+static hipError_t launch_lds_jg(hipStream_t s, int nt, size_t lds, const void *M, int l, void *sigma, void *X, void *W,
+                                DevInfo *info, int batch, int64_t stride, int rows, void *Jglobal) {
+  hipLaunchKernelGGL((jacobi_lds_kernel<double, double, RPL, 16, true>), dim3(batch), dim3(nt), lds, s,
+                     (const double *)M, l, (double *)sigma, (double *)X, (double *)W, info, stride, rows,
+                     (double *)Jglobal);
   return hipGetLastError();
 }
 
@@ -1331,6 +1354,12 @@ static void raise_lds_limit_lds(hipError_t &e) {
     e = hipFuncSetAttribute(reinterpret_cast<const void *>(&jacobi_lds_kernel<T, TIn, RPL, 16>),
                             hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 4096);
 }
+template <int RPL>
+static void raise_lds_limit_jg(hipError_t &e) {
+  if (e == hipSuccess)
+    e = hipFuncSetAttribute(reinterpret_cast<const void *>(&jacobi_lds_kernel<double, double, RPL, 16, true>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 4096);
+}
 template <typename T, int NV>
 static void raise_lds_limit_panel(hipError_t &e) {
   if (e == hipSuccess)
@@ -1357,6 +1386,8 @@ hipError_t jacobi_init_device(rsvd_ctx *ctx) {
   raise_lds_limit_lds<double, double, 3>(e); raise_lds_limit_lds<double, double, 4>(e);
   raise_lds_limit_lds<double, double, 5>(e); raise_lds_limit_lds<double, double, 6>(e);
   raise_lds_limit_lds<double, double, 8>(e);
+  raise_lds_limit_jg<7>(e);
+  raise_lds_limit_jg<8>(e);
   raise_lds_limit_panels<float>(e);
   raise_lds_limit_panels<double>(e);
   if (e == hipSuccess)
@@ -1373,7 +1404,20 @@ hipError_t jacobi_launch(rsvd_ctx *ctx, hipStream_t s, rsvd_dtype dtype, int64_t
                          size_t scratch_bytes, int batch, int64_t stride, int rows) {
   if (batch < 1 || batch > 65535) return hipErrorInvalidValue;
   if (l > jacobi_max_lds_order(ctx, dtype)) {
-    if (batch != 1) return hipErrorNotSupported;       // the block path is not batched
+    if (batch != 1) {
+      // the block path is not batched: fp64 orders up to 128 take the one-workgroup kernel with J in global memory
+      // (the block path's scratch, which every problem of the batch has, is larger than one J)
+      if (dtype != RSVD_F64 || l > jacobi_max_batched_order(ctx, dtype) || !m_is_f64 || scratch == nullptr ||
+          scratch_bytes < jacobi_jglobal_bytes(l))
+        return hipErrorNotSupported;
+      const int ldm = jacobi_ldm((int)l, 16, 8);
+      const size_t lds = align_up((size_t)l * ldm * 8 + (size_t)l * (8 + sizeof(int)), 16);
+      const int nt = (int)align_up((size_t)((l + 1) / 2) * 16, 64);
+      ProfScope ps(ctx, s, PK_JACOBI);
+      if (jacobi_rows_padded((int)l, 16, 8) / 16 == 7)
+        return launch_lds_jg<7>(s, nt, lds, M, (int)l, sigma, X, W, info, batch, stride, rows, scratch);
+      return launch_lds_jg<8>(s, nt, lds, M, (int)l, sigma, X, W, info, batch, stride, rows, scratch);
+    }
     // block path: needs the fp64 input (the triangular factor) and its scratch
     const size_t need = jacobi_scratch_bytes(ctx, dtype, l);
     if (need == 0 || scratch == nullptr || scratch_bytes < need || !m_is_f64) return hipErrorNotSupported;

@@ -617,7 +617,7 @@ static int run_impl(rsvd_ctx *ctx, void *stream, rsvd_dtype dtype, rsvd_job job,
   if (workspace == nullptr || ((uintptr_t)workspace & 255) != 0) return -18;
   if (workspace_bytes < w.L.total * (size_t)batch) return -19;
   if (l > jacobi_max_lds_order(ctx, dtype) && jacobi_scratch_bytes(ctx, dtype, l) == 0) return RSVD_ERR_UNSUPPORTED;
-  if (batch > 1 && (l > jacobi_max_lds_order(ctx, dtype) || l > chol_max_block(ctx) || center))
+  if (batch > 1 && (l > jacobi_max_batched_order(ctx, dtype) || l > chol_max_block(ctx) || center))
     return RSVD_ERR_UNSUPPORTED;
   if (ctx->device < 0) return RSVD_ERR_NO_DEVICE;
   hipStream_t s = (hipStream_t)stream;

@@ -45,7 +45,9 @@ CASES = [
     (scaled(CONFIGS[2], 700, 300, k=20, p=12), 5, 2),            # fp32, l = 32, split-K products
     (scaled(CONFIGS[1], 200, 160, rank=12, k=10, p=6), 7, 1),    # fp64, exact recovery, rank-deficient sketch
     (scaled(CONFIGS[3], 2000, 250, rank=25, k=40, p=8), 3, 2),   # fp32, l = 48, noisy tail
-    (scaled(CONFIGS[4], 500, 400, rank=64, k=64, p=32), 4, 1),   # fp64, l = 96: largest fp64 order of the batched path
+    (scaled(CONFIGS[4], 500, 400, rank=64, k=64, p=32), 4, 1),   # fp64, l = 96: largest fp64 order held in LDS whole
+    (scaled(CONFIGS[4], 600, 450, rank=80, k=80, p=25), 3, 1),   # fp64, l = 105: rotations accumulated in global memory
+    (scaled(CONFIGS[4], 700, 500, rank=100, k=100, p=28), 3, 2), # fp64, l = 128: largest order of the batched path
     (scaled(CONFIGS[2], 333, 129, k=7, p=6), 9, 0),              # odd everything: scalar load paths, q = 0
     (scaled(CONFIGS[5], 600, 300, rank=64, k=100, p=28), 3, 1),  # fp32, l = 128: largest order of the batched path
 ]
@@ -125,6 +127,9 @@ def test_batched_rejects_what_it_cannot_do():
     A = torch.zeros((2, 400, 300), dtype=torch.float32, device="cuda:0")
     with pytest.raises(RsvdError) as e:
         c.rsvd_run_batched(A, 120, 40, 1)                     # l = 160: beyond the single-workgroup kernels
+    assert e.value.code == 4
+    with pytest.raises(RsvdError) as e:
+        c.rsvd_run_batched(A.double(), 100, 29, 1)            # l = 129 in fp64 likewise
     assert e.value.code == 4
     with pytest.raises(RsvdError) as e:
         c.rsvd_run_batched(A, 200, 200, 1)                    # k + p > min(m, n): caught when the workspace is sized

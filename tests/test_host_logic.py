@@ -140,11 +140,12 @@ def test_batched_entry_point_reports_positions_of_its_own_prototype(plan):
     assert call(ws=None) == -23
     one = plan.workspace_bytes(F32, 600, 200, 12, 4)
     assert call(ws_bytes=3 * one - 1) == -24 and call(ws_bytes=3 * one) == ERR_NO_DEVICE
-    # a batch needs the single-workgroup Cholesky and Jacobi kernels: l <= 128 (fp32), 96 (fp64)
+    # a batch needs the single-workgroup Cholesky and Jacobi kernels: l <= 128
     assert call(m=2000, n=2000, lda=2000, ldvt=2000, stride_a=4000000, stride_vt=2000 * 130, k=129, p=0, ldu=129,
                 stride_s=129, stride_u=2000 * 129) == UNSUPPORTED
-    assert call(dtype=F64, k=90, p=7, ldu=90, stride_s=90, stride_u=600 * 90, stride_vt=90 * 200) == UNSUPPORTED
-    assert call(dtype=F64, k=90, p=6, ldu=90, stride_s=90, stride_u=600 * 90, stride_vt=90 * 200) == ERR_NO_DEVICE
+    assert call(dtype=F64, k=120, p=9, ldu=120, stride_s=120, stride_u=600 * 120, stride_vt=120 * 200) == UNSUPPORTED
+    assert call(dtype=F64, k=120, p=8, ldu=120, stride_s=120, stride_u=600 * 120, stride_vt=120 * 200) == ERR_NO_DEVICE
+    assert call(dtype=F64, k=90, p=7, ldu=90, stride_s=90, stride_u=600 * 90, stride_vt=90 * 200) == ERR_NO_DEVICE
 
 
 def test_stage_entry_points_check_then_decline(plan):
