@@ -197,6 +197,7 @@ def batched(args):
         (2000, 500, 16, 16, 1, torch.float32, (1, 16, 256)),
         (10000, 2000, 64, 16, 2, torch.float32, (1, 4, 16)),
         (4000, 1000, 32, 16, 2, torch.float64, (1, 16, 64)),
+        (4000, 1000, 100, 28, 1, torch.float64, (1, 4, 32)),      # l = 128 in fp64: rotations accumulated in the workspace
     ]
     for (m, n, k, p, q, tdt, batches) in cases:
         for batch in batches:
